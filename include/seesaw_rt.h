@@ -1,0 +1,188 @@
+/*
+ * seesaw_rt.h - C ABI of the MI355X (gfx950) hot path of re-sharded LLM inference:
+ * one GPU's share of a LLaMA-style decoder layer in the pipeline-parallel layout
+ * used for prefill and in the tensor-parallel layout used for decode, plus the
+ * KV-cache movement through a host-DRAM tier that converts one into the other.
+ *
+ * Conventions shared by every call
+ *   - returns 0 (SS_OK) or a negative SS_E* code; never throws or aborts across
+ *     the ABI; ss_last_error() gives the text of the last failure of a context.
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP
+ *     device memory of the context's GPU; every argument says which it is.
+ *   - activations are row-major [tokens, hidden] in the model dtype (SS_F32:
+ *     IEEE float, SS_BF16: 16-bit brain float, raw bits) and are CALLER-owned
+ *     device buffers; weights are copied by the library at load time; KV pages,
+ *     the host tier, the pinned staging ring and the side stream are
+ *     library-owned.
+ *   - `stream` is a hipStream_t (0 = the null stream).  Layer calls are
+ *     asynchronous on it.  KV movement runs on the library's side stream, driven
+ *     by a library-owned host thread, and is complete after ss_sync().
+ *   - one context per GPU, calls on one context come from one thread at a time.
+ */
+#ifndef SEESAW_RT_H
+#define SEESAW_RT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { SS_F32 = 0, SS_BF16 = 1 };                 /* model dtype */
+enum { SS_PP = 0, SS_TP = 1 };                    /* shard mode */
+enum { SS_ATTN = 1, SS_MLP = 2, SS_BOTH = 3,      /* phase */
+       SS_NO_RESIDUAL = 4 };                      /* flag OR-ed into phase */
+enum { SS_OUT = 0, SS_IN = 1 };                   /* swap direction */
+enum { SS_HOST = 0, SS_DEVICE = 1 };              /* where weight pointers live */
+enum { SS_OK = 0, SS_EINVAL = -1, SS_ENOMEM = -2, SS_ENOENT = -3, SS_EHIP = -4 };
+
+typedef struct ss_ctx ss_ctx;
+
+/* Model shape.  head_dim must be 64 or 128; page_size must be 16. */
+typedef struct {
+    int32_t hidden, n_q_heads, n_kv_heads, head_dim, ffn, n_layers, vocab;
+    float rms_eps, rope_base;
+    int32_t dtype;       /* SS_F32 | SS_BF16 */
+    int32_t page_size;   /* tokens per KV page */
+} ss_model_cfg;
+
+typedef struct {
+    int64_t gpu_kv_pages;    /* pages in the pool of EACH shard descriptor used */
+    int64_t host_tier_bytes; /* capacity of the host tier (complete caches) */
+    int64_t pinned_bytes;    /* pinned staging ring, split into two slots */
+    int32_t device;          /* HIP device ordinal */
+    int32_t max_seq_len;     /* longest sequence (rotary table size) */
+} ss_runtime_cfg;
+
+/*
+ * What one GPU holds (paper section 3.1, Observations 1 and 2; Appendix A.3).
+ *   SS_PP: layers [layer_begin, layer_end), all heads, all FFN columns;
+ *          k and shard are ignored except that k must be >= 1.
+ *   SS_TP: layers [layer_begin, layer_end), q heads [shard*n_q/k, (shard+1)*n_q/k),
+ *          kv heads [shard*n_kv/k, ...), FFN columns [shard*ffn/k, ...).
+ *          k must divide n_q_heads, n_kv_heads and ffn (k > n_kv_heads is refused).
+ * Every distinct descriptor owns its own weights, page pool and page tables, as
+ * a distinct GPU would.
+ */
+typedef struct { int32_t mode, k, shard, layer_begin, layer_end; } ss_shard_desc;
+
+/* A batch of sequences: host arrays, caller-owned, read during the call only.
+ * Tokens of the batch are concatenated in this order in the activation buffers.
+ * q_lens[i] new tokens of sequence i sit at positions kv_lens_before[i] ... */
+typedef struct {
+    int32_t n_seqs;
+    const int64_t* seq_ids;
+    const int32_t* q_lens;
+    const int32_t* kv_lens_before;
+} ss_batch;
+
+/* Full (unsharded) weights of one layer, row-major [in_features, out_features],
+ * model dtype; g1/g2 are the two RMSNorm gains [hidden].
+ * wq [H, n_q*d]  wk, wv [H, n_kv*d]  wo [n_q*d, H]  wg, wu [H, ffn]  wd [ffn, H] */
+typedef struct {
+    const void *g1, *wq, *wk, *wv, *wo, *g2, *wg, *wu, *wd;
+    int32_t location;    /* SS_HOST | SS_DEVICE: applies to all nine pointers */
+} ss_layer_weights;
+
+/* ---- life cycle ------------------------------------------------------- */
+int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out);
+int ss_destroy(ss_ctx* ctx);
+const char* ss_last_error(ss_ctx* ctx);   /* valid until the next failing call */
+
+/* Slices the shard's part out of the full layer and keeps a device copy
+ * (the pointers may be released on return). */
+int ss_load_layer(ss_ctx*, const ss_shard_desc*, int layer, const ss_layer_weights* full);
+
+/* ---- the layer (paper section 2.1: "several linear layers and an attention
+ * layer"; prefill handles all prompt tokens at once, decode one token per
+ * sequence against its KV cache) --------------------------------------------
+ *
+ * x_in [T, hidden] device, out [T, hidden] device (may alias x_in only for
+ * SS_MLP and SS_ATTN with k == 1 is NOT allowed either: keep them distinct).
+ * T = sum of q_lens (prefill) or n_seqs (decode, every q_len must be 1).
+ *
+ * phase SS_ATTN: RMSNorm, QKV projection, rotary embedding, K/V written into
+ *   the shard's paged cache (pages allocated on demand), causal attention, O
+ *   projection.  out = x_in + o when k == 1, else the shard's partial o
+ *   WITHOUT residual (the k partials are summed by the caller: that sum is
+ *   where tensor parallelism places its first all-reduce, paper Table 3).
+ * phase SS_MLP: x_in is the reduced x1.  RMSNorm, gate/up projection, SwiGLU,
+ *   down projection.  out = x1 + y when k == 1, else the partial y.
+ * phase SS_BOTH: both, k == 1 only.
+ * SS_NO_RESIDUAL forces the partial form for k == 1 as well.
+ */
+int ss_layer_prefill(ss_ctx*, const ss_shard_desc*, int layer, int phase, const ss_batch*,
+                     const void* x_in, void* out, void* stream);
+int ss_layer_decode(ss_ctx*, const ss_shard_desc*, int layer, int phase, const ss_batch*,
+                    const void* x_in, void* out, void* stream);
+
+/* ---- KV movement (paper section 4.2 "tiered KV cache buffering" and the
+ * re-sharding paragraph; section 5.2 two-stage swap-out, asynchronous swap-in,
+ * heads-major host layout) ---------------------------------------------------
+ *
+ * Host tier: per sequence one slot holding the COMPLETE cache of exactly s
+ * tokens, element (layer l, c in {0:K,1:V}, kv head g, position p, e) at
+ *   ((((l*2 + c)*n_kv + g)*s + p)*head_dim + e
+ * elements from the slot's base.  Slots are bump-allocated; when the last live
+ * sequence is released the tier is empty and allocation restarts at 0.
+ *
+ * ss_kv_swap(SS_OUT): gathers the descriptor's layers/heads of the listed
+ *   sequences from its pages into heads-major staging, copies to the pinned
+ *   ring (asynchronous DMA on the side stream), then host-copies into the tier
+ *   (stage two, on the library's host thread).  Pages stay allocated: release
+ *   them with ss_kv_free after ss_sync.  SS_ENOMEM when the tier is full.
+ * ss_kv_swap(SS_IN): allocates pages in the descriptor's pool (in call order,
+ *   lowest free id first) and fills them with the descriptor's layers/heads
+ *   taken from the tier.  SS_ENOENT if a sequence is not in the tier.
+ * Ordering: the side stream first waits for everything enqueued on `stream`
+ *   before the call.  Compute that uses swapped-in pages must follow ss_sync().
+ * ss_kv_reshard(from, to) = swap-out under `from`, then swap-in under `to`.
+ */
+int ss_kv_swap(ss_ctx*, const ss_shard_desc*, int dir, const int64_t* seq_ids, int n, void* stream);
+int ss_kv_reshard(ss_ctx*, const ss_shard_desc* from, const ss_shard_desc* to,
+                  const int64_t* seq_ids, int n, void* stream);
+int ss_sync(ss_ctx*);                       /* drains the host thread and the side stream */
+int ss_kv_free(ss_ctx*, const ss_shard_desc*, const int64_t* seq_ids, int n);  /* pages back to the pool */
+int ss_host_tier_release(ss_ctx*, const int64_t* seq_ids, int n);
+
+/* Device-side halves of the movement, without the PCIe leg: staging is a device
+ * buffer laid out [seq][layer_local][K|V][head_local][position][head_dim],
+ * sequences back to back at exact lengths, model dtype.  Export gathers pages
+ * into it; import allocates pages for (seq_ids, lens) and scatters into them.
+ * Both run on `stream`. */
+int ss_kv_export_dev(ss_ctx*, const ss_shard_desc*, const int64_t* seq_ids, int n, void* staging, void* stream);
+int ss_kv_import_dev(ss_ctx*, const ss_shard_desc*, const int64_t* seq_ids, const int32_t* lens, int n,
+                     const void* staging, void* stream);
+
+/* ---- inspection (tests) ------------------------------------------------ */
+/* pages [*n_inout] receives the page ids of seq; *n_inout returns the count. */
+int ss_kv_page_table(ss_ctx*, const ss_shard_desc*, int64_t seq, int32_t* pages, int32_t* n_inout);
+int ss_kv_seq_len(ss_ctx*, const ss_shard_desc*, int64_t seq, int32_t* len_out);
+/* host_out [2][heads_local][s][head_dim], model dtype; synchronises the device. */
+int ss_kv_read(ss_ctx*, const ss_shard_desc*, int64_t seq, int layer, void* host_out);
+/* host_out [2][n_kv][s][head_dim] of one layer straight from the tier. */
+int ss_host_tier_read(ss_ctx*, int64_t seq, int layer, void* host_out);
+int64_t ss_host_tier_used_bytes(ss_ctx*);
+int64_t ss_kv_free_pages(ss_ctx*, const ss_shard_desc*);
+
+/* ---- helpers for the tiny whole-model configuration --------------------- */
+/* embed [vocab, H], gf [H], wlm [H, vocab]; host pointers, model dtype. */
+int ss_load_head(ss_ctx*, const void* embed, const void* gf, const void* wlm);
+int ss_embed(ss_ctx*, const int32_t* token_ids_host, int n, void* x_out, void* stream);
+/* logits [n, vocab] float32 device = RMSNorm(x; gf) * wlm */
+int ss_lm_head(ss_ctx*, const void* x, int n, float* logits, void* stream);
+
+/* ---- timing hooks (bench) ------------------------------------------------ */
+/* Average duration in ms of the kernels of one class since the last reset,
+ * measured with HIP events on the stream they were launched on; enabled with
+ * ss_prof_enable(ctx, 1).  cls: 0 GEMM, 1 prefill attention, 2 decode
+ * attention, 3 KV gather/scatter, 4 everything else.  Returns the number of
+ * launches counted through *n_out. */
+int ss_prof_enable(ss_ctx*, int on);
+int ss_prof_read(ss_ctx*, int cls, double* total_ms_out, int64_t* n_out);
+int ss_prof_reset(ss_ctx*);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

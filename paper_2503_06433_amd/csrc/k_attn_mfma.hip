@@ -1,0 +1,316 @@
+// bf16 MFMA attention for gfx950 against the paged cache: causal prefill and
+// split-KV decode.  Both kernels compute the TRANSPOSED products
+//     S^T = K * Q^T        (rows = cached tokens, columns = queries)
+//     O^T = V^T * P^T      (rows = head dimension, columns = queries)
+// so that the accumulator of the first product is already in the register
+// layout the second product wants for its B operand (each lane owns one query
+// column and a run of tokens): P never travels through LDS or across lanes.
+// K pages are [head][16][D] and V pages are stored transposed, [head][D][16],
+// so both MFMA A operands are plain vector loads straight from the pages.
+//
+// The contraction order inside one MFMA is free as long as both operands agree:
+// the token <-> k-slot assignment below is chosen to match what the S^T
+// accumulator holds, and the V^T operand is gathered with the same assignment.
+#include "ss_device.h"
+#include "ss_kernels.h"
+
+namespace ssk {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+
+struct __attribute__((aligned(8))) vec8 { uint32_t w[2]; };
+
+union Frag {
+    bf16x8_t v;
+    vec16 q;
+    vec8 h[2];
+    uint32_t w[4];
+};
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+    return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
+}
+
+// ======================================================================
+// Prefill.  Block = 4 waves = 128 consecutive queries of one (sequence, q head);
+// each wave owns 32 queries and walks the pages its queries can see, two pages
+// (32 tokens) per step, with v_mfma_f32_32x32x16_bf16:
+//   accumulator register v of lane l <-> token 8*(v/4) + 4*(l/32) + v%4, query l%32.
+// ======================================================================
+template <int D>
+__global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const bf16_t* __restrict__ qkv,
+                                                                bf16_t* __restrict__ out, int n_q, int n_kv,
+                                                                BatchMeta bm, const bf16_t* __restrict__ k_pool,
+                                                                const bf16_t* __restrict__ v_pool,
+                                                                float scale_log2e) {
+    constexpr int KS = D / 16;      // k-steps of the score product
+    constexpr int DT = D / 32;      // 32-row tiles of O^T
+    const int sq = blockIdx.z, a = blockIdx.y;
+    const int q_begin = bm.cu_q[sq], q_len = bm.cu_q[sq + 1] - q_begin;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int q0 = blockIdx.x * 128 + wave * 32;
+    if (q0 >= q_len) return;
+    const int before = bm.kv_before[sq];
+    const int g = a / (n_q / n_kv);
+    const int lq = lane & 31, g2 = lane >> 5;
+    const int qi = q0 + lq;
+    const bool valid = qi < q_len;
+    const int p = before + (valid ? qi : 0);
+    const int last_q = (q0 + 31 < q_len) ? q0 + 31 : q_len - 1;
+    const int n_pages = (before + last_q) / 16 + 1;
+    const size_t row_stride = (size_t)(n_q + 2 * n_kv) * D;
+
+    Frag qf[KS];
+    {
+        const bf16_t* qp = qkv + (size_t)(q_begin + (valid ? qi : 0)) * row_stride + (size_t)a * D + g2 * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks].q = *reinterpret_cast<const vec16*>(qp + ks * 16);
+    }
+    f32x16_t o[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[t][v] = 0.f;
+    float m = -INFINITY, l = 0.f;
+
+    const int32_t* pt = bm.page_tables + (size_t)sq * bm.pt_stride;
+    const size_t page_elems = (size_t)n_kv * 16 * D;
+    const size_t head_off = (size_t)g * 16 * D;
+    const int tok = lq;                       // token row this lane loads of the 32-token step
+    for (int pi = 0; pi < n_pages; pi += 2) {
+        const int pA = pt[pi];
+        const int pB = pt[(pi + 1 < n_pages) ? pi + 1 : pi];
+        // ---- S^T = K Q^T
+        const bf16_t* kp = k_pool + (size_t)(tok < 16 ? pA : pB) * page_elems + head_off + (size_t)(tok & 15) * D + g2 * 8;
+        f32x16_t s;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            Frag kf;
+            kf.q = *reinterpret_cast<const vec16*>(kp + ks * 16);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s, 0, 0, 0);
+        }
+        // ---- mask + streaming softmax (per query column = per lane pair l, l^32)
+        const int t0 = pi * 16;
+        float mx = m;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int tpos = t0 + 8 * (v >> 2) + 4 * g2 + (v & 3);
+            s[v] = (tpos <= p) ? s[v] * scale_log2e : -INFINITY;
+            mx = fmaxf(mx, s[v]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float alpha = exp2f(m - mx);
+        m = mx;
+        float rs = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { s[v] = exp2f(s[v] - mx); rs += s[v]; }
+        l = l * alpha + rs;
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[t][v] *= alpha;
+        // ---- O^T += V^T P^T ; k-slots of step A: tokens {4*g2 + i, 8 + 4*g2 + i}, page A; step B: same of page B
+        Frag pfA, pfB;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            pfA.w[i] = pack_bf16x2(s[2 * i], s[2 * i + 1]);
+            pfB.w[i] = pack_bf16x2(s[8 + 2 * i], s[8 + 2 * i + 1]);
+        }
+        const bf16_t* vA = v_pool + (size_t)pA * page_elems + head_off + (size_t)lq * 16 + 4 * g2;
+        const bf16_t* vB = v_pool + (size_t)pB * page_elems + head_off + (size_t)lq * 16 + 4 * g2;
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+            Frag va, vb;
+            va.h[0] = *reinterpret_cast<const vec8*>(vA + t * 32 * 16);
+            va.h[1] = *reinterpret_cast<const vec8*>(vA + t * 32 * 16 + 8);
+            vb.h[0] = *reinterpret_cast<const vec8*>(vB + t * 32 * 16);
+            vb.h[1] = *reinterpret_cast<const vec8*>(vB + t * 32 * 16 + 8);
+            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pfA.v, o[t], 0, 0, 0);
+            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb.v, pfB.v, o[t], 0, 0, 0);
+        }
+    }
+    l += __shfl_xor(l, 32, 64);
+    if (valid) {
+        const float inv = 1.0f / l;
+        bf16_t* op = out + (size_t)(q_begin + qi) * ((size_t)n_q * D) + (size_t)a * D;
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                vec8 w;
+                w.w[0] = pack_bf16x2(o[t][4 * j] * inv, o[t][4 * j + 1] * inv);
+                w.w[1] = pack_bf16x2(o[t][4 * j + 2] * inv, o[t][4 * j + 3] * inv);
+                *reinterpret_cast<vec8*>(op + t * 32 + 8 * j + 4 * g2) = w;
+            }
+    }
+}
+
+hipError_t attn_generic(int dt, const void* qkv, void* out, int n_q, int n_kv, const BatchMeta& bm,
+                        const KvLayer& kv, hipStream_t s);
+
+hipError_t attn_prefill(int dt, const void* qkv, void* out, int n_q, int n_kv, const BatchMeta& bm,
+                        const KvLayer& kv, bool force_generic, hipStream_t s) {
+    if (bm.T <= 0 || bm.n_seqs <= 0) return hipSuccess;
+    if (dt != BF16 || force_generic || kv.d != 128) return attn_generic(dt, qkv, out, n_q, n_kv, bm, kv, s);
+    if (kv.page_size != 16 || n_kv <= 0 || n_q % n_kv != 0 || kv.n_heads != n_kv) return hipErrorInvalidValue;
+    if (bm.n_seqs > 65535 || n_q > 65535) return hipErrorInvalidValue;
+    dim3 grid((bm.max_q_len + 127) / 128, n_q, bm.n_seqs);
+    const float sl2 = 1.4426950408889634f / sqrtf((float)kv.d);
+    attn_prefill_mfma_kernel<128><<<grid, 256, 0, s>>>((const bf16_t*)qkv, (bf16_t*)out, n_q, n_kv, bm,
+                                                       (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, sl2);
+    return hipGetLastError();
+}
+
+// ======================================================================
+// Decode.  One wave per (work item, kv head).  A work item is a run of pages of
+// one sequence.  All G = n_q / n_kv (<= 16) query heads that share the kv head
+// form the 16 query columns of v_mfma_f32_16x16x32_bf16 (unused columns are
+// zero), so K and V are read from HBM once per group:
+//   accumulator register v of lane l <-> token 4*(l/16) + v, query l%16.
+// Each step covers two pages; k-slot e of lane group g4 is token 4*g4 + e of
+// page A for e < 4 and token 4*g4 + e - 4 of page B for e >= 4.
+// Partial (max, sum, O) of every item go to scratch and are merged per sequence.
+// scratch layout: float [n_items][n_q][D + 4]  (O[D], running max, running sum)
+// ======================================================================
+template <int D>
+__global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __restrict__ qkv, int n_q, int n_kv,
+                                                              BatchMeta bm, DecodeWork wk,
+                                                              const bf16_t* __restrict__ k_pool,
+                                                              const bf16_t* __restrict__ v_pool,
+                                                              float* __restrict__ scratch, float scale_log2e) {
+    constexpr int KS = D / 32;
+    constexpr int DT = D / 16;
+    const int item = blockIdx.x, g = blockIdx.y;
+    const int G = n_q / n_kv;
+    const int sq = wk.item_seq[item];
+    const int page0 = wk.item_page0[item], npg = wk.item_npages[item];
+    const int kv_len = bm.kv_before[sq] + 1;
+    const int lane = threadIdx.x;
+    const int lq = lane & 15, g4 = lane >> 4;
+    const size_t row_stride = (size_t)(n_q + 2 * n_kv) * D;
+
+    Frag qf[KS];
+    if (lq < G) {
+        const bf16_t* qp = qkv + (size_t)bm.cu_q[sq] * row_stride + (size_t)(g * G + lq) * D + g4 * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks].q = *reinterpret_cast<const vec16*>(qp + ks * 32);
+    } else {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks].w[0] = qf[ks].w[1] = qf[ks].w[2] = qf[ks].w[3] = 0u;
+    }
+    f32x4_t o[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t) o[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, l = 0.f;
+
+    const int32_t* pt = bm.page_tables + (size_t)sq * bm.pt_stride + page0;
+    const size_t page_elems = (size_t)n_kv * 16 * D;
+    const size_t head_off = (size_t)g * 16 * D;
+    for (int pi = 0; pi < npg; pi += 2) {
+        const bool hasB = pi + 1 < npg;
+        const int pA = pt[pi];
+        const int pB = pt[hasB ? pi + 1 : pi];
+        const bf16_t* kA = k_pool + (size_t)pA * page_elems + head_off + (size_t)lq * D + g4 * 8;
+        const bf16_t* kB = k_pool + (size_t)pB * page_elems + head_off + (size_t)lq * D + g4 * 8;
+        f32x4_t sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            Frag ka, kb;
+            ka.q = *reinterpret_cast<const vec16*>(kA + ks * 32);
+            kb.q = *reinterpret_cast<const vec16*>(kB + ks * 32);
+            sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka.v, qf[ks].v, sA, 0, 0, 0);
+            sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb.v, qf[ks].v, sB, 0, 0, 0);
+        }
+        const int posA = (page0 + pi) * 16 + 4 * g4;
+        float mx = m;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            sA[v] = (posA + v < kv_len) ? sA[v] * scale_log2e : -INFINITY;
+            sB[v] = (hasB && posA + 16 + v < kv_len) ? sB[v] * scale_log2e : -INFINITY;
+            mx = fmaxf(mx, fmaxf(sA[v], sB[v]));
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        // the first page of an item always holds a visible token: mx is finite
+        const float alpha = exp2f(m - mx);
+        m = mx;
+        float rs = 0.f;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            sA[v] = exp2f(sA[v] - mx);
+            sB[v] = exp2f(sB[v] - mx);
+            rs += sA[v] + sB[v];
+        }
+        l = l * alpha + rs;
+        Frag pf;
+        pf.w[0] = pack_bf16x2(sA[0], sA[1]);
+        pf.w[1] = pack_bf16x2(sA[2], sA[3]);
+        pf.w[2] = pack_bf16x2(sB[0], sB[1]);
+        pf.w[3] = pack_bf16x2(sB[2], sB[3]);
+        const bf16_t* vA = v_pool + (size_t)pA * page_elems + head_off + (size_t)lq * 16 + 4 * g4;
+        const bf16_t* vB = v_pool + (size_t)pB * page_elems + head_off + (size_t)lq * 16 + 4 * g4;
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+            Frag vf;
+            vf.h[0] = *reinterpret_cast<const vec8*>(vA + t * 16 * 16);
+            vf.h[1] = *reinterpret_cast<const vec8*>(vB + t * 16 * 16);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[t][v] *= alpha;
+            o[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf.v, o[t], 0, 0, 0);
+        }
+    }
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (lq < G) {
+        float* sp = scratch + ((size_t)item * n_q + (size_t)(g * G + lq)) * (D + 4);
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+            *reinterpret_cast<f32x4_t*>(sp + t * 16 + 4 * g4) = o[t];
+        if (g4 == 0) { sp[D] = m; sp[D + 1] = l; }
+    }
+}
+
+// Merge of the per-item partials: one block of D threads per (q head, sequence).
+template <int D>
+__global__ __launch_bounds__(D) void attn_decode_merge_kernel(const float* __restrict__ scratch,
+                                                              bf16_t* __restrict__ out, int n_q, BatchMeta bm,
+                                                              DecodeWork wk) {
+    const int a = blockIdx.x, sq = blockIdx.y, e = threadIdx.x;
+    const int i0 = wk.seq_item0[sq], i1 = wk.seq_item0[sq + 1];
+    float M = -INFINITY;
+    for (int i = i0; i < i1; ++i) M = fmaxf(M, scratch[((size_t)i * n_q + a) * (D + 4) + D]);
+    float num = 0.f, den = 0.f;
+    for (int i = i0; i < i1; ++i) {
+        const float* sp = scratch + ((size_t)i * n_q + a) * (D + 4);
+        const float w = exp2f(sp[D] - M);
+        num += w * sp[e];
+        den += w * sp[D + 1];
+    }
+    out[(size_t)bm.cu_q[sq] * ((size_t)n_q * D) + (size_t)a * D + e] = f2bf(num / den);
+}
+
+size_t attn_decode_scratch_floats(int n_items, int n_q, int d) { return (size_t)n_items * n_q * (d + 4); }
+
+hipError_t attn_decode(int dt, const void* qkv, void* out, int n_q, int n_kv, const BatchMeta& bm,
+                       const KvLayer& kv, const DecodeWork& wk, float* scratch, bool force_generic,
+                       hipStream_t s) {
+    if (bm.n_seqs <= 0) return hipSuccess;
+    if (n_kv <= 0 || n_q % n_kv != 0) return hipErrorInvalidValue;
+    const int G = n_q / n_kv;
+    if (dt != BF16 || force_generic || kv.d != 128 || G > 16) return attn_generic(dt, qkv, out, n_q, n_kv, bm, kv, s);
+    if (kv.page_size != 16 || kv.n_heads != n_kv || !scratch || wk.n_items <= 0) return hipErrorInvalidValue;
+    if (n_kv > 65535 || bm.n_seqs > 65535) return hipErrorInvalidValue;
+    const float sl2 = 1.4426950408889634f / sqrtf((float)kv.d);
+    dim3 grid(wk.n_items, n_kv);
+    attn_decode_mfma_kernel<128><<<grid, 64, 0, s>>>((const bf16_t*)qkv, n_q, n_kv, bm, wk,
+                                                     (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, scratch, sl2);
+    dim3 mgrid(n_q, bm.n_seqs);
+    attn_decode_merge_kernel<128><<<mgrid, 128, 0, s>>>(scratch, (bf16_t*)out, n_q, bm, wk);
+    return hipGetLastError();
+}
+
+}  // namespace ssk

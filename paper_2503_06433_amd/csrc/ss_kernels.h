@@ -1,0 +1,122 @@
+// Internal launcher interface between the runtime (ss_runtime.hip) and the
+// kernel files.  Everything here is device pointers + sizes; every launcher
+// validates what its kernel assumes and returns hipErrorInvalidValue instead of
+// launching a grid that would not fit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ssk {
+
+enum Dtype { F32 = 0, BF16 = 1 };
+inline size_t esize(int dt) { return dt == F32 ? 4 : 2; }
+
+enum Epilogue {
+    EPI_STORE = 0,      // C = acc
+    EPI_RESIDUAL = 1,   // C = acc + R   (R has C's shape and leading dimension)
+    EPI_SWIGLU = 2,     // weight rows come in blocks of 32 gate rows followed by the
+                        // matching 32 up rows; C[m, j] = silu(gate_j) * up_j, C has N/2 columns
+    EPI_STORE_F32 = 3,  // C is float regardless of the input dtype
+};
+
+// C[M,N] = A[M,K] * Wt[N,K]^T.  A row-major with leading dimension lda, Wt
+// row-major [N,K] (K contiguous), C row-major with leading dimension ldc.
+// force_generic selects the plain LDS-tiled FMA kernel (any shape, any dtype);
+// otherwise bf16 with K % 64 == 0 runs on the MFMA kernel.
+hipError_t gemm_nt(int dt, const void* A, int lda, const void* Wt, void* C, int ldc,
+                   const void* R, int M, int N, int K, int epi, bool force_generic,
+                   hipStream_t s);
+
+// out[t,:] = x[t,:] * rsqrt(mean(x[t,:]^2) + eps) * g
+hipError_t rmsnorm(int dt, const void* x, const void* g, void* out, int T, int H, float eps,
+                   hipStream_t s);
+
+// out[t, j] = silu(gu[t, j]) * gu[t, F + j]   (unfused form used by the generic GEMM path)
+hipError_t swiglu(int dt, const void* gu, void* out, int T, int F, hipStream_t s);
+
+// Gathers rows of an embedding table.
+hipError_t embed_rows(int dt, const void* table, const int32_t* ids, void* out, int n, int H,
+                      hipStream_t s);
+
+// Paged cache geometry of one shard and one layer.
+//   K page: [n_heads][page_size][d]   (token-major, d contiguous)
+//   V page: [n_heads][d][page_size]   (transposed inside the page: token contiguous)
+// page p of the pool starts at element p * n_heads * page_size * d.
+struct KvLayer {
+    void* k_pool;
+    void* v_pool;
+    int n_heads;     // local kv heads
+    int d;
+    int page_size;
+};
+
+// Per-token metadata of a batch (device arrays): tok_seq[t] = index of the
+// sequence inside the batch, tok_pos[t] = absolute position.  page_tables is
+// [n_seqs, pt_stride] int32.
+struct BatchMeta {
+    const int32_t* tok_seq;
+    const int32_t* tok_pos;
+    const int32_t* page_tables;
+    int pt_stride;
+    const int32_t* cu_q;        // [n_seqs+1] first token of each sequence in the batch
+    const int32_t* kv_before;   // [n_seqs]
+    int n_seqs;
+    int T;
+    int max_q_len;
+};
+
+// Rotates q and k in place inside qkv [T, (n_q + 2 n_kv) d] by the token's
+// position (half-split pairing, angles from the fp32 table rope[pos][d/2][cos,sin]),
+// then writes the rotated k and the v of every token into the pages.
+hipError_t rope_kvwrite(int dt, void* qkv, int n_q, int n_kv, const float* rope_table,
+                        const BatchMeta& bm, const KvLayer& kv, hipStream_t s);
+
+// Causal attention of the batch's new tokens against the paged cache (which
+// already holds them).  q is read from qkv (row stride (n_q + 2 n_kv) d), out is
+// [T, n_q d].  Query at absolute position p sees cache positions 0..p.
+hipError_t attn_prefill(int dt, const void* qkv, void* out, int n_q, int n_kv,
+                        const BatchMeta& bm, const KvLayer& kv, bool force_generic, hipStream_t s);
+
+// One query token per sequence.  work items (seq, first page, n pages) split long
+// sequences; partial results go through `scratch` (floats) and are merged.
+struct DecodeWork {
+    const int32_t* item_seq;    // [n_items]
+    const int32_t* item_page0;  // [n_items] first page index within the sequence
+    const int32_t* item_npages; // [n_items]
+    const int32_t* seq_item0;   // [n_seqs+1] first item of each sequence
+    int n_items;
+    int max_items_per_seq;
+};
+size_t attn_decode_scratch_floats(int n_items, int n_q, int d);
+hipError_t attn_decode(int dt, const void* qkv, void* out, int n_q, int n_kv,
+                       const BatchMeta& bm, const KvLayer& kv, const DecodeWork& wk,
+                       float* scratch, bool force_generic, hipStream_t s);
+
+// KV repack between pages and heads-major staging.
+// unit u = one (sequence, local layer): a staging block [2][n_heads][len][d] at
+// element offset unit_off[u]; its page list starts at pages[unit_pt[u]]; the
+// layer's pools are k_pools[unit_layer[u]] / v_pools[unit_layer[u]].
+struct RepackUnits {
+    const int64_t* unit_off;
+    const int32_t* unit_len;
+    const int32_t* unit_pt;      // offset into `pages`
+    const int32_t* unit_layer;   // local layer index
+    const int32_t* pages;        // concatenated page lists
+    int n_units;
+    int max_pages;               // most pages of any unit
+};
+hipError_t kv_gather(int dt, void* const* k_pools, void* const* v_pools, int n_heads, int d,
+                     int page_size, const RepackUnits& u, void* staging, hipStream_t s);
+hipError_t kv_scatter(int dt, void* const* k_pools, void* const* v_pools, int n_heads, int d,
+                      int page_size, const RepackUnits& u, const void* staging, hipStream_t s);
+
+// Weight slicing at load time: column j (0 <= j < n) of src[K, ld_src], taken from
+// column c0 + j, becomes row  (j / blk) * blk_stride + (j % blk) + row_off  of
+// dst[*, K] (K contiguous).  blk = n, row_off = 0 gives the plain transpose.
+hipError_t slice_transpose(int dt, const void* src, int64_t ld_src, int K, int c0, int n,
+                           void* dst, int blk, int blk_stride, int row_off, hipStream_t s);
+
+// dst[i] = src[i] for i < n (elements of the model dtype); used for gains.
+hipError_t copy_elems(int dt, const void* src, void* dst, int64_t n, hipStream_t s);
+
+}  // namespace ssk

@@ -1,0 +1,1288 @@
+// Host runtime behind the C ABI of include/seesaw_rt.h: shard state (sliced
+// weights, page pools, page tables), the layer pipelines, the host tier, and the
+// asynchronous KV mover (side stream + host thread + pinned two-slot ring).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <atomic>
+#include <condition_variable>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <deque>
+#include <functional>
+#include <map>
+#include <mutex>
+#include <queue>
+#include <string>
+#include <thread>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/seesaw_rt.h"
+#include "ss_kernels.h"
+
+namespace {
+
+struct DevBuf {
+    void* p = nullptr;
+    size_t cap = 0;
+};
+
+struct LayerW {
+    void *g1 = nullptr, *g2 = nullptr, *wqkv_t = nullptr, *wo_t = nullptr, *wgu_t = nullptr, *wd_t = nullptr;
+    bool loaded = false;
+    bool gu_interleaved = false;
+};
+
+struct SeqState {
+    std::vector<int32_t> pages;
+    int32_t len = 0;
+};
+
+struct Shard {
+    ss_shard_desc desc{};
+    int nq_l = 0, nkv_l = 0, f_l = 0, q0 = 0, g0 = 0, f0 = 0, n_layers_l = 0;
+    std::vector<LayerW> w;
+    std::vector<void*> k_pool, v_pool;
+    void** d_k_pools = nullptr;
+    void** d_v_pools = nullptr;
+    bool pools_ready = false;
+    std::priority_queue<int32_t, std::vector<int32_t>, std::greater<int32_t>> free_pages;
+    std::unordered_map<int64_t, SeqState> seqs;
+    uint64_t version = 0;     // bumped on every page-table change
+};
+
+struct DescKey {
+    int32_t v[5];
+    bool operator<(const DescKey& o) const { return std::lexicographical_compare(v, v + 5, o.v, o.v + 5); }
+};
+
+// One slot of batch metadata: pinned host image + device copy + "last use" event.
+struct MetaSlot {
+    uint8_t* host = nullptr;
+    uint8_t* dev = nullptr;
+    size_t cap = 0;
+    hipEvent_t done = nullptr;
+    bool in_flight = false;
+    // cache key
+    Shard* shard = nullptr;
+    uint64_t version = 0;
+    bool decode = false;
+    std::vector<int64_t> seq_ids;
+    std::vector<int32_t> q_lens, kv_before;
+    ssk::BatchMeta bm{};
+    ssk::DecodeWork wk{};
+};
+
+struct SeqJob {
+    int64_t seq;
+    int32_t len;
+    std::vector<int32_t> pages;
+    size_t tier_off;   // bytes
+};
+
+struct Job {
+    int dir;
+    Shard* sh;
+    std::vector<SeqJob> seqs;
+    hipEvent_t after = nullptr;
+};
+
+struct TierSlot {
+    size_t off;     // bytes
+    int32_t len;    // tokens
+};
+
+struct ProfRec {
+    int cls;
+    hipEvent_t a, b;
+};
+
+}  // namespace
+
+struct ss_ctx {
+    ss_model_cfg m{};
+    ss_runtime_cfg rt{};
+    int dt = 0;
+    size_t es = 2;
+    bool force_generic = false;
+    std::string err;
+    std::map<DescKey, Shard*> shards;
+    float* d_rope = nullptr;
+    DevBuf ws_h, ws_qkv, ws_attn, ws_gu, ws_act, ws_x1, ws_scratch;
+    MetaSlot meta[4];
+    int meta_next = 0;
+    void *d_embed = nullptr, *d_gf = nullptr, *d_wlm_t = nullptr;
+    int32_t* d_ids = nullptr;
+    size_t d_ids_cap = 0;
+    // host tier
+    uint8_t* tier = nullptr;
+    size_t tier_cap = 0, tier_top = 0;
+    std::unordered_map<int64_t, TierSlot> tier_slots;
+    // mover
+    hipStream_t side = nullptr;
+    uint8_t* pinned = nullptr;
+    uint8_t* dev_staging = nullptr;
+    size_t slot_bytes = 0;
+    uint8_t* mv_meta_host = nullptr;   // 2 slots
+    uint8_t* mv_meta_dev = nullptr;
+    size_t mv_meta_cap = 0;
+    hipEvent_t mv_ev[2] = {nullptr, nullptr};
+    std::thread worker;
+    std::mutex mu;
+    std::condition_variable cv, cv_idle;
+    std::deque<Job> jobs;
+    bool busy = false, stop = false;
+    std::string worker_err;
+    int worker_rc = 0;
+    // profiling
+    bool prof_on = false;
+    std::vector<ProfRec> prof;
+    std::mutex prof_mu;
+};
+
+namespace {
+
+// The mover thread reports into its own string (read by ss_sync); everything
+// else reports into the context's.
+thread_local std::string* tl_err = nullptr;
+
+int fail(ss_ctx* c, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (tl_err) *tl_err = buf;
+    else if (c) c->err = buf;
+    return code;
+}
+
+#define HIP_TRY(c, expr)                                                                        \
+    do {                                                                                        \
+        hipError_t e_ = (expr);                                                                 \
+        if (e_ != hipSuccess)                                                                   \
+            return fail((c), e_ == hipErrorOutOfMemory ? SS_ENOMEM : SS_EHIP, "%s: %s (%s:%d)", #expr, \
+                        hipGetErrorString(e_), __FILE__, __LINE__);                             \
+    } while (0)
+
+struct ProfScope {
+    ss_ctx* c;
+    int cls;
+    hipStream_t s;
+    hipEvent_t a = nullptr, b = nullptr;
+    ProfScope(ss_ctx* c_, int cls_, hipStream_t s_) : c(c_), cls(cls_), s(s_) {
+        if (c->prof_on) {
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { a = b = nullptr; return; }
+            (void)hipEventRecord(a, s);
+        }
+    }
+    ~ProfScope() {
+        if (a && b) {
+            (void)hipEventRecord(b, s);
+            std::lock_guard<std::mutex> lk(c->prof_mu);
+            c->prof.push_back({cls, a, b});
+        }
+    }
+};
+
+int ensure_buf(ss_ctx* c, DevBuf& b, size_t bytes) {
+    if (bytes <= b.cap) return SS_OK;
+    if (b.p) {
+        HIP_TRY(c, hipDeviceSynchronize());
+        HIP_TRY(c, hipFree(b.p));
+        b.p = nullptr;
+        b.cap = 0;
+    }
+    size_t want = bytes + bytes / 8 + 256;
+    HIP_TRY(c, hipMalloc(&b.p, want));
+    b.cap = want;
+    return SS_OK;
+}
+
+int check_desc(ss_ctx* c, const ss_shard_desc* d) {
+    if (!d) return fail(c, SS_EINVAL, "null shard descriptor");
+    const ss_model_cfg& m = c->m;
+    if (d->mode != SS_PP && d->mode != SS_TP) return fail(c, SS_EINVAL, "bad shard mode %d", d->mode);
+    if (d->k < 1) return fail(c, SS_EINVAL, "shard degree k=%d < 1", d->k);
+    if (d->layer_begin < 0 || d->layer_end > m.n_layers || d->layer_begin >= d->layer_end)
+        return fail(c, SS_EINVAL, "bad layer range [%d,%d) of %d", d->layer_begin, d->layer_end, m.n_layers);
+    if (d->mode == SS_TP) {
+        if (d->shard < 0 || d->shard >= d->k) return fail(c, SS_EINVAL, "shard %d outside [0,%d)", d->shard, d->k);
+        if (d->k > m.n_kv_heads) return fail(c, SS_EINVAL, "k=%d exceeds n_kv_heads=%d", d->k, m.n_kv_heads);
+        if (m.n_q_heads % d->k || m.n_kv_heads % d->k || m.ffn % d->k)
+            return fail(c, SS_EINVAL, "k=%d must divide n_q_heads, n_kv_heads and ffn", d->k);
+    }
+    return SS_OK;
+}
+
+int get_shard(ss_ctx* c, const ss_shard_desc* d, Shard** out) {
+    int rc = check_desc(c, d);
+    if (rc) return rc;
+    DescKey key;
+    key.v[0] = d->mode;
+    key.v[1] = d->mode == SS_TP ? d->k : 1;
+    key.v[2] = d->mode == SS_TP ? d->shard : 0;
+    key.v[3] = d->layer_begin;
+    key.v[4] = d->layer_end;
+    auto it = c->shards.find(key);
+    if (it != c->shards.end()) { *out = it->second; return SS_OK; }
+    Shard* s = new Shard();
+    s->desc = *d;
+    const int k = key.v[1], i = key.v[2];
+    s->nq_l = c->m.n_q_heads / k;
+    s->nkv_l = c->m.n_kv_heads / k;
+    s->f_l = c->m.ffn / k;
+    s->q0 = i * s->nq_l;
+    s->g0 = i * s->nkv_l;
+    s->f0 = i * s->f_l;
+    s->n_layers_l = d->layer_end - d->layer_begin;
+    s->w.resize(s->n_layers_l);
+    c->shards[key] = s;
+    *out = s;
+    return SS_OK;
+}
+
+size_t page_bytes(ss_ctx* c, Shard* s) { return (size_t)s->nkv_l * c->m.page_size * c->m.head_dim * c->es; }
+
+int ensure_pools(ss_ctx* c, Shard* s) {
+    if (s->pools_ready) return SS_OK;
+    const size_t bytes = page_bytes(c, s) * (size_t)c->rt.gpu_kv_pages;
+    s->k_pool.assign(s->n_layers_l, nullptr);
+    s->v_pool.assign(s->n_layers_l, nullptr);
+    for (int l = 0; l < s->n_layers_l; ++l) {
+        HIP_TRY(c, hipMalloc(&s->k_pool[l], bytes));
+        HIP_TRY(c, hipMalloc(&s->v_pool[l], bytes));
+        // finite contents everywhere: masked slots are multiplied by exact zeros
+        HIP_TRY(c, hipMemset(s->k_pool[l], 0, bytes));
+        HIP_TRY(c, hipMemset(s->v_pool[l], 0, bytes));
+    }
+    HIP_TRY(c, hipMalloc((void**)&s->d_k_pools, sizeof(void*) * s->n_layers_l));
+    HIP_TRY(c, hipMalloc((void**)&s->d_v_pools, sizeof(void*) * s->n_layers_l));
+    HIP_TRY(c, hipMemcpy(s->d_k_pools, s->k_pool.data(), sizeof(void*) * s->n_layers_l, hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemcpy(s->d_v_pools, s->v_pool.data(), sizeof(void*) * s->n_layers_l, hipMemcpyHostToDevice));
+    for (int64_t p = 0; p < c->rt.gpu_kv_pages; ++p) s->free_pages.push((int32_t)p);
+    s->pools_ready = true;
+    return SS_OK;
+}
+
+// Grow a sequence's page list to cover `length` tokens: lowest free id first.
+int ensure_pages(ss_ctx* c, Shard* s, int64_t seq, int32_t length) {
+    SeqState& st = s->seqs[seq];
+    const int ps = c->m.page_size;
+    const size_t need = (size_t)((length + ps - 1) / ps);
+    if (need > st.pages.size()) {
+        if (need - st.pages.size() > s->free_pages.size())
+            return fail(c, SS_ENOMEM, "page pool exhausted: sequence %lld needs %zu more pages, %zu free",
+                        (long long)seq, need - st.pages.size(), s->free_pages.size());
+        while (st.pages.size() < need) {
+            st.pages.push_back(s->free_pages.top());
+            s->free_pages.pop();
+        }
+        s->version++;
+    }
+    if (length > st.len) st.len = length;
+    return SS_OK;
+}
+
+ssk::KvLayer kv_layer(ss_ctx* c, Shard* s, int ll) {
+    ssk::KvLayer k;
+    k.k_pool = s->k_pool[ll];
+    k.v_pool = s->v_pool[ll];
+    k.n_heads = s->nkv_l;
+    k.d = c->m.head_dim;
+    k.page_size = c->m.page_size;
+    return k;
+}
+
+constexpr int DECODE_ITEM_PAGES = 16;   // pages (256 tokens) per decode work item
+
+// Builds (or reuses) the device metadata of a batch.  Returns the slot.
+int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream_t stream, MetaSlot** out) {
+    const int n = b->n_seqs;
+    // ---- validation + page allocation (idempotent)
+    int64_t T = 0;
+    int max_q = 0;
+    for (int i = 0; i < n; ++i) {
+        const int ql = b->q_lens[i], before = b->kv_lens_before[i];
+        if (ql <= 0 || before < 0) return fail(c, SS_EINVAL, "sequence %d: q_len=%d kv_len_before=%d", i, ql, before);
+        if (decode && ql != 1) return fail(c, SS_EINVAL, "decode needs q_len == 1 (sequence %d has %d)", i, ql);
+        if (before + ql > c->rt.max_seq_len)
+            return fail(c, SS_EINVAL, "sequence %d reaches length %d > max_seq_len %d", i, before + ql, c->rt.max_seq_len);
+        if (before > 0) {
+            auto it = s->seqs.find(b->seq_ids[i]);
+            if (it == s->seqs.end() || it->second.len < before)
+                return fail(c, SS_ENOENT, "sequence %lld has no %d cached tokens in this shard",
+                            (long long)b->seq_ids[i], before);
+        }
+        T += ql;
+        max_q = std::max(max_q, ql);
+    }
+    if (T > (1 << 30)) return fail(c, SS_EINVAL, "batch too large");
+    for (int i = 0; i < n; ++i) {
+        int rc = ensure_pages(c, s, b->seq_ids[i], b->kv_lens_before[i] + b->q_lens[i]);
+        if (rc) return rc;
+    }
+    // ---- cache lookup
+    for (auto& ms : c->meta) {
+        if (ms.shard == s && ms.version == s->version && ms.decode == decode && (int)ms.seq_ids.size() == n &&
+            !memcmp(ms.seq_ids.data(), b->seq_ids, sizeof(int64_t) * n) &&
+            !memcmp(ms.q_lens.data(), b->q_lens, sizeof(int32_t) * n) &&
+            !memcmp(ms.kv_before.data(), b->kv_lens_before, sizeof(int32_t) * n)) {
+            *out = &ms;
+            return SS_OK;
+        }
+    }
+    // ---- build
+    MetaSlot& ms = c->meta[c->meta_next];
+    c->meta_next = (c->meta_next + 1) % 4;
+    if (ms.in_flight) {
+        HIP_TRY(c, hipEventSynchronize(ms.done));
+        ms.in_flight = false;
+    }
+    ms.shard = nullptr;
+    int pt_stride = 1;
+    std::vector<const SeqState*> sts(n);
+    for (int i = 0; i < n; ++i) {
+        sts[i] = &s->seqs[b->seq_ids[i]];
+        pt_stride = std::max<int>(pt_stride, (int)sts[i]->pages.size());
+    }
+    // decode work items
+    std::vector<int32_t> item_seq, item_page0, item_np, seq_item0;
+    int max_items = 0;
+    if (decode) {
+        seq_item0.resize(n + 1);
+        for (int i = 0; i < n; ++i) {
+            seq_item0[i] = (int32_t)item_seq.size();
+            const int used = (b->kv_lens_before[i] + 1 + c->m.page_size - 1) / c->m.page_size;
+            int cnt = 0;
+            for (int p0 = 0; p0 < used; p0 += DECODE_ITEM_PAGES, ++cnt) {
+                item_seq.push_back(i);
+                item_page0.push_back(p0);
+                item_np.push_back(std::min(DECODE_ITEM_PAGES, used - p0));
+            }
+            max_items = std::max(max_items, cnt);
+        }
+        seq_item0[n] = (int32_t)item_seq.size();
+    }
+    const size_t n_items = item_seq.size();
+    auto al = [](size_t x) { return (x + 63) & ~(size_t)63; };
+    size_t off_tok_seq = 0;
+    size_t off_tok_pos = off_tok_seq + al(4 * (size_t)T);
+    size_t off_cu = off_tok_pos + al(4 * (size_t)T);
+    size_t off_before = off_cu + al(4 * (size_t)(n + 1));
+    size_t off_pt = off_before + al(4 * (size_t)n);
+    size_t off_iseq = off_pt + al(4 * (size_t)n * pt_stride);
+    size_t off_ip0 = off_iseq + al(4 * n_items);
+    size_t off_inp = off_ip0 + al(4 * n_items);
+    size_t off_si0 = off_inp + al(4 * n_items);
+    size_t total = off_si0 + al(4 * (size_t)(n + 1));
+    if (total > ms.cap) {
+        if (ms.host) { HIP_TRY(c, hipHostFree(ms.host)); ms.host = nullptr; }
+        if (ms.dev) { HIP_TRY(c, hipFree(ms.dev)); ms.dev = nullptr; }
+        ms.cap = total + total / 4 + 4096;
+        HIP_TRY(c, hipHostMalloc((void**)&ms.host, ms.cap, hipHostMallocDefault));
+        HIP_TRY(c, hipMalloc((void**)&ms.dev, ms.cap));
+    }
+    int32_t* tok_seq = (int32_t*)(ms.host + off_tok_seq);
+    int32_t* tok_pos = (int32_t*)(ms.host + off_tok_pos);
+    int32_t* cu = (int32_t*)(ms.host + off_cu);
+    int32_t* before = (int32_t*)(ms.host + off_before);
+    int32_t* pt = (int32_t*)(ms.host + off_pt);
+    int t = 0;
+    for (int i = 0; i < n; ++i) {
+        cu[i] = t;
+        before[i] = b->kv_lens_before[i];
+        for (int j = 0; j < b->q_lens[i]; ++j, ++t) {
+            tok_seq[t] = i;
+            tok_pos[t] = b->kv_lens_before[i] + j;
+        }
+        const auto& pg = sts[i]->pages;
+        int32_t* row = pt + (size_t)i * pt_stride;
+        std::copy(pg.begin(), pg.end(), row);
+        std::fill(row + pg.size(), row + pt_stride, pg.empty() ? 0 : pg.back());
+    }
+    cu[n] = t;
+    if (decode) {
+        memcpy(ms.host + off_iseq, item_seq.data(), 4 * n_items);
+        memcpy(ms.host + off_ip0, item_page0.data(), 4 * n_items);
+        memcpy(ms.host + off_inp, item_np.data(), 4 * n_items);
+        memcpy(ms.host + off_si0, seq_item0.data(), 4 * (size_t)(n + 1));
+    }
+    HIP_TRY(c, hipMemcpyAsync(ms.dev, ms.host, total, hipMemcpyHostToDevice, stream));
+    ms.bm.tok_seq = (const int32_t*)(ms.dev + off_tok_seq);
+    ms.bm.tok_pos = (const int32_t*)(ms.dev + off_tok_pos);
+    ms.bm.cu_q = (const int32_t*)(ms.dev + off_cu);
+    ms.bm.kv_before = (const int32_t*)(ms.dev + off_before);
+    ms.bm.page_tables = (const int32_t*)(ms.dev + off_pt);
+    ms.bm.pt_stride = pt_stride;
+    ms.bm.n_seqs = n;
+    ms.bm.T = (int)T;
+    ms.bm.max_q_len = max_q;
+    ms.wk.item_seq = (const int32_t*)(ms.dev + off_iseq);
+    ms.wk.item_page0 = (const int32_t*)(ms.dev + off_ip0);
+    ms.wk.item_npages = (const int32_t*)(ms.dev + off_inp);
+    ms.wk.seq_item0 = (const int32_t*)(ms.dev + off_si0);
+    ms.wk.n_items = (int)n_items;
+    ms.wk.max_items_per_seq = max_items;
+    ms.shard = s;
+    ms.version = s->version;
+    ms.decode = decode;
+    ms.seq_ids.assign(b->seq_ids, b->seq_ids + n);
+    ms.q_lens.assign(b->q_lens, b->q_lens + n);
+    ms.kv_before.assign(b->kv_lens_before, b->kv_lens_before + n);
+    *out = &ms;
+    return SS_OK;
+}
+
+int mark_meta_used(ss_ctx* c, MetaSlot* ms, hipStream_t stream) {
+    if (!ms->done) HIP_TRY(c, hipEventCreateWithFlags(&ms->done, hipEventDisableTiming));
+    HIP_TRY(c, hipEventRecord(ms->done, stream));
+    ms->in_flight = true;
+    return SS_OK;
+}
+
+#define K_TRY(c, expr)                                                                                       \
+    do {                                                                                                     \
+        hipError_t e_ = (expr);                                                                              \
+        if (e_ != hipSuccess)                                                                                \
+            return fail((c), e_ == hipErrorInvalidValue ? SS_EINVAL : SS_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+int run_attn_phase(ss_ctx* c, Shard* s, int ll, const ss_batch* b, bool decode, const void* x_in, void* out,
+                   bool residual, hipStream_t st) {
+    const ss_model_cfg& m = c->m;
+    const LayerW& w = s->w[ll];
+    MetaSlot* ms = nullptr;
+    int rc = prepare_batch(c, s, b, decode, st, &ms);
+    if (rc) return rc;
+    const int T = ms->bm.T, H = m.hidden, d = m.head_dim;
+    const int nqkv = (s->nq_l + 2 * s->nkv_l) * d;
+    if ((rc = ensure_buf(c, c->ws_h, (size_t)T * H * c->es))) return rc;
+    if ((rc = ensure_buf(c, c->ws_qkv, (size_t)T * nqkv * c->es))) return rc;
+    if ((rc = ensure_buf(c, c->ws_attn, (size_t)T * s->nq_l * d * c->es))) return rc;
+    if (decode) {
+        size_t fl = ssk::attn_decode_scratch_floats(ms->wk.n_items, s->nq_l, d);
+        if ((rc = ensure_buf(c, c->ws_scratch, fl * sizeof(float)))) return rc;
+    }
+    const ssk::KvLayer kv = kv_layer(c, s, ll);
+    {
+        ProfScope ps(c, 4, st);
+        K_TRY(c, ssk::rmsnorm(c->dt, x_in, w.g1, c->ws_h.p, T, H, m.rms_eps, st));
+    }
+    {
+        ProfScope ps(c, 0, st);
+        K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, H, w.wqkv_t, c->ws_qkv.p, nqkv, nullptr, T, nqkv, H, ssk::EPI_STORE,
+                              c->force_generic, st));
+    }
+    {
+        ProfScope ps(c, 4, st);
+        K_TRY(c, ssk::rope_kvwrite(c->dt, c->ws_qkv.p, s->nq_l, s->nkv_l, c->d_rope, ms->bm, kv, st));
+    }
+    if (decode) {
+        ProfScope ps(c, 2, st);
+        K_TRY(c, ssk::attn_decode(c->dt, c->ws_qkv.p, c->ws_attn.p, s->nq_l, s->nkv_l, ms->bm, kv, ms->wk,
+                                  (float*)c->ws_scratch.p, c->force_generic, st));
+    } else {
+        ProfScope ps(c, 1, st);
+        K_TRY(c, ssk::attn_prefill(c->dt, c->ws_qkv.p, c->ws_attn.p, s->nq_l, s->nkv_l, ms->bm, kv,
+                                   c->force_generic, st));
+    }
+    {
+        ProfScope ps(c, 0, st);
+        K_TRY(c, ssk::gemm_nt(c->dt, c->ws_attn.p, s->nq_l * d, w.wo_t, out, H, residual ? x_in : nullptr, T, H,
+                              s->nq_l * d, residual ? ssk::EPI_RESIDUAL : ssk::EPI_STORE, c->force_generic, st));
+    }
+    return mark_meta_used(c, ms, st);
+}
+
+int run_mlp_phase(ss_ctx* c, Shard* s, int ll, int T, const void* x1, void* out, bool residual, hipStream_t st) {
+    const ss_model_cfg& m = c->m;
+    const LayerW& w = s->w[ll];
+    const int H = m.hidden, F = s->f_l;
+    int rc;
+    if ((rc = ensure_buf(c, c->ws_h, (size_t)T * H * c->es))) return rc;
+    if ((rc = ensure_buf(c, c->ws_act, (size_t)T * F * c->es))) return rc;
+    {
+        ProfScope ps(c, 4, st);
+        K_TRY(c, ssk::rmsnorm(c->dt, x1, w.g2, c->ws_h.p, T, H, m.rms_eps, st));
+    }
+    if (w.gu_interleaved) {
+        ProfScope ps(c, 0, st);
+        K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, H, w.wgu_t, c->ws_act.p, F, nullptr, T, 2 * F, H, ssk::EPI_SWIGLU,
+                              false, st));
+    } else {
+        if ((rc = ensure_buf(c, c->ws_gu, (size_t)T * 2 * F * c->es))) return rc;
+        {
+            ProfScope ps(c, 0, st);
+            K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, H, w.wgu_t, c->ws_gu.p, 2 * F, nullptr, T, 2 * F, H,
+                                  ssk::EPI_STORE, c->force_generic, st));
+        }
+        ProfScope ps(c, 4, st);
+        K_TRY(c, ssk::swiglu(c->dt, c->ws_gu.p, c->ws_act.p, T, F, st));
+    }
+    {
+        ProfScope ps(c, 0, st);
+        K_TRY(c, ssk::gemm_nt(c->dt, c->ws_act.p, F, w.wd_t, out, H, residual ? x1 : nullptr, T, H, F,
+                              residual ? ssk::EPI_RESIDUAL : ssk::EPI_STORE, c->force_generic, st));
+    }
+    return SS_OK;
+}
+
+int layer_call(ss_ctx* c, const ss_shard_desc* d, int layer, int phase, const ss_batch* b, const void* x_in,
+               void* out, void* stream, bool decode) {
+    if (!c) return SS_EINVAL;
+    if (!b || !x_in || !out || b->n_seqs <= 0 || !b->seq_ids || !b->q_lens || !b->kv_lens_before)
+        return fail(c, SS_EINVAL, "null or empty batch / buffers");
+    if (x_in == out) return fail(c, SS_EINVAL, "out must not alias x_in");
+    Shard* s = nullptr;
+    int rc = get_shard(c, d, &s);
+    if (rc) return rc;
+    if (layer < d->layer_begin || layer >= d->layer_end)
+        return fail(c, SS_EINVAL, "layer %d outside the shard's range [%d,%d)", layer, d->layer_begin, d->layer_end);
+    const int ll = layer - d->layer_begin;
+    if (!s->w[ll].loaded) return fail(c, SS_EINVAL, "layer %d not loaded for this shard", layer);
+    const bool nores = (phase & SS_NO_RESIDUAL) != 0;
+    const int ph = phase & 3;
+    if (ph == 0) return fail(c, SS_EINVAL, "bad phase %d", phase);
+    const int k = d->mode == SS_TP ? d->k : 1;
+    if (ph == SS_BOTH && (k != 1 || nores)) return fail(c, SS_EINVAL, "SS_BOTH needs k == 1 and residuals");
+    const bool residual = (k == 1) && !nores;
+    if ((rc = ensure_pools(c, s))) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    int64_t T = 0;
+    for (int i = 0; i < b->n_seqs; ++i) T += b->q_lens[i];
+    if (ph == SS_ATTN) return run_attn_phase(c, s, ll, b, decode, x_in, out, residual, st);
+    if (ph == SS_MLP) {
+        if (T <= 0 || T > (1 << 30)) return fail(c, SS_EINVAL, "bad token count");
+        return run_mlp_phase(c, s, ll, (int)T, x_in, out, residual, st);
+    }
+    if ((rc = ensure_buf(c, c->ws_x1, (size_t)T * c->m.hidden * c->es))) return rc;
+    if ((rc = run_attn_phase(c, s, ll, b, decode, x_in, c->ws_x1.p, true, st))) return rc;
+    return run_mlp_phase(c, s, ll, (int)T, c->ws_x1.p, out, true, st);
+}
+
+// ------------------------------------------------------------------ mover
+struct Unit {
+    int seq_idx;     // index into job.seqs
+    int ll;          // local layer
+    size_t bytes;
+};
+
+// Fills the repack metadata of units [u0,u1) into host image `h`; returns the
+// device-side struct (pointers relative to `dbase`).  Staging offsets are
+// relative to the chunk start.
+size_t build_units(ss_ctx* c, Shard* s, const std::vector<SeqJob>& seqs, const std::vector<Unit>& units, size_t u0,
+                   size_t u1, uint8_t* h, uint8_t* dbase, size_t cap, ssk::RepackUnits* ru) {
+    const size_t n = u1 - u0;
+    // page lists: one per distinct sequence in the chunk
+    std::vector<int> seq_first;   // seq_idx of units, compacted
+    size_t n_pages = 0;
+    std::unordered_map<int, size_t> pt_off;
+    for (size_t u = u0; u < u1; ++u) {
+        const int si = units[u].seq_idx;
+        if (!pt_off.count(si)) {
+            pt_off[si] = n_pages;
+            seq_first.push_back(si);
+            n_pages += (seqs[si].len + c->m.page_size - 1) / c->m.page_size;
+        }
+    }
+    auto al = [](size_t x) { return (x + 63) & ~(size_t)63; };
+    const size_t o_off = 0, o_len = o_off + al(8 * n), o_pt = o_len + al(4 * n), o_layer = o_pt + al(4 * n);
+    const size_t o_pages = o_layer + al(4 * n), total = o_pages + al(4 * n_pages);
+    if (total > cap) return 0;
+    int64_t* uoff = (int64_t*)(h + o_off);
+    int32_t* ulen = (int32_t*)(h + o_len);
+    int32_t* upt = (int32_t*)(h + o_pt);
+    int32_t* ulay = (int32_t*)(h + o_layer);
+    int32_t* pages = (int32_t*)(h + o_pages);
+    for (int si : seq_first) {
+        const size_t np = (seqs[si].len + c->m.page_size - 1) / c->m.page_size;
+        std::copy(seqs[si].pages.begin(), seqs[si].pages.begin() + np, pages + pt_off[si]);
+    }
+    size_t off_elems = 0;
+    int max_pages = 0;
+    for (size_t u = u0; u < u1; ++u) {
+        const SeqJob& sj = seqs[units[u].seq_idx];
+        uoff[u - u0] = (int64_t)off_elems;
+        ulen[u - u0] = sj.len;
+        upt[u - u0] = (int32_t)pt_off[units[u].seq_idx];
+        ulay[u - u0] = units[u].ll;
+        off_elems += units[u].bytes / c->es;
+        max_pages = std::max(max_pages, (sj.len + c->m.page_size - 1) / c->m.page_size);
+    }
+    ru->unit_off = (const int64_t*)(dbase + o_off);
+    ru->unit_len = (const int32_t*)(dbase + o_len);
+    ru->unit_pt = (const int32_t*)(dbase + o_pt);
+    ru->unit_layer = (const int32_t*)(dbase + o_layer);
+    ru->pages = (const int32_t*)(dbase + o_pages);
+    ru->n_units = (int)n;
+    ru->max_pages = max_pages;
+    (void)s;
+    return total;
+}
+
+std::vector<Unit> make_units(ss_ctx* c, Shard* s, const std::vector<SeqJob>& seqs) {
+    std::vector<Unit> units;
+    for (size_t i = 0; i < seqs.size(); ++i)
+        for (int ll = 0; ll < s->n_layers_l; ++ll)
+            units.push_back({(int)i, ll, (size_t)2 * s->nkv_l * seqs[i].len * c->m.head_dim * c->es});
+    return units;
+}
+
+// Host tier address of the run (layer, c, first local head) of a sequence.
+uint8_t* tier_run(ss_ctx* c, Shard* s, const SeqJob& sj, int ll, int kv) {
+    const size_t layer = (size_t)(s->desc.layer_begin + ll);
+    const size_t elems = (((layer * 2 + kv) * c->m.n_kv_heads + s->g0) * (size_t)sj.len) * c->m.head_dim;
+    return c->tier + sj.tier_off + elems * c->es;
+}
+
+int worker_job(ss_ctx* c, Job& job) {
+    Shard* s = job.sh;
+    if (job.after) {
+        HIP_TRY(c, hipStreamWaitEvent(c->side, job.after, 0));
+    }
+    const std::vector<Unit> units = make_units(c, s, job.seqs);
+    const size_t run_elems_bytes = c->es * c->m.head_dim;   // per token per head
+    // chunks of consecutive units fitting one slot
+    std::vector<std::pair<size_t, size_t>> chunks;
+    for (size_t u = 0; u < units.size();) {
+        size_t bytes = 0, v = u;
+        while (v < units.size() && bytes + units[v].bytes <= c->slot_bytes && v - u < 65535) bytes += units[v++].bytes;
+        if (v == u) return fail(c, SS_ENOMEM, "pinned slot (%zu bytes) smaller than one sequence-layer unit (%zu bytes)",
+                                c->slot_bytes, units[u].bytes);
+        chunks.push_back({u, v});
+        u = v;
+    }
+    auto host_copy = [&](size_t ci, bool to_tier) {
+        const int slot = (int)(ci & 1);
+        uint8_t* p = c->pinned + (size_t)slot * c->slot_bytes;
+        for (size_t u = chunks[ci].first; u < chunks[ci].second; ++u) {
+            const SeqJob& sj = job.seqs[units[u].seq_idx];
+            const size_t run = (size_t)s->nkv_l * sj.len * run_elems_bytes;
+            for (int kv = 0; kv < 2; ++kv) {
+                uint8_t* t = tier_run(c, s, sj, units[u].ll, kv);
+                if (to_tier) memcpy(t, p, run); else memcpy(p, t, run);
+                p += run;
+            }
+        }
+    };
+    auto chunk_bytes = [&](size_t ci) {
+        size_t b = 0;
+        for (size_t u = chunks[ci].first; u < chunks[ci].second; ++u) b += units[u].bytes;
+        return b;
+    };
+    const size_t meta_half = c->mv_meta_cap / 2;
+    for (size_t ci = 0; ci < chunks.size(); ++ci) {
+        const int slot = (int)(ci & 1);
+        uint8_t* mh = c->mv_meta_host + slot * meta_half;
+        uint8_t* md = c->mv_meta_dev + slot * meta_half;
+        uint8_t* dst = c->dev_staging + (size_t)slot * c->slot_bytes;
+        uint8_t* pin = c->pinned + (size_t)slot * c->slot_bytes;
+        ssk::RepackUnits ru{};
+        if (ci >= 2) HIP_TRY(c, hipEventSynchronize(c->mv_ev[slot]));   // slot's previous DMA and metadata are done
+        const size_t mbytes = build_units(c, s, job.seqs, units, chunks[ci].first, chunks[ci].second, mh, md, meta_half, &ru);
+        if (!mbytes) return fail(c, SS_ENOMEM, "KV mover metadata region too small");
+        const size_t bytes = chunk_bytes(ci);
+        if (job.dir == SS_OUT) {
+            HIP_TRY(c, hipMemcpyAsync(md, mh, mbytes, hipMemcpyHostToDevice, c->side));
+            {
+                ProfScope ps(c, 3, c->side);
+                K_TRY(c, ssk::kv_gather(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru,
+                                        dst, c->side));
+            }
+            HIP_TRY(c, hipMemcpyAsync(pin, dst, bytes, hipMemcpyDeviceToHost, c->side));
+            HIP_TRY(c, hipEventRecord(c->mv_ev[slot], c->side));
+            if (ci >= 1) {   // stage two of the previous chunk overlaps this chunk's gather + DMA
+                HIP_TRY(c, hipEventSynchronize(c->mv_ev[slot ^ 1]));
+                host_copy(ci - 1, true);
+            }
+        } else {
+            host_copy(ci, false);   // overlaps the previous chunk's DMA + scatter
+            HIP_TRY(c, hipMemcpyAsync(md, mh, mbytes, hipMemcpyHostToDevice, c->side));
+            HIP_TRY(c, hipMemcpyAsync(dst, pin, bytes, hipMemcpyHostToDevice, c->side));
+            {
+                ProfScope ps(c, 3, c->side);
+                K_TRY(c, ssk::kv_scatter(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size,
+                                         ru, dst, c->side));
+            }
+            HIP_TRY(c, hipEventRecord(c->mv_ev[slot], c->side));
+        }
+    }
+    if (job.dir == SS_OUT && !chunks.empty()) {
+        const size_t last = chunks.size() - 1;
+        HIP_TRY(c, hipEventSynchronize(c->mv_ev[last & 1]));
+        host_copy(last, true);
+    } else {
+        HIP_TRY(c, hipStreamSynchronize(c->side));
+    }
+    return SS_OK;
+}
+
+void worker_main(ss_ctx* c) {
+    (void)hipSetDevice(c->rt.device);
+    std::string local_err;
+    tl_err = &local_err;
+    for (;;) {
+        Job job;
+        {
+            std::unique_lock<std::mutex> lk(c->mu);
+            c->cv.wait(lk, [&] { return c->stop || !c->jobs.empty(); });
+            if (c->jobs.empty()) return;   // stop requested and queue drained
+            job = std::move(c->jobs.front());
+            c->jobs.pop_front();
+            c->busy = true;
+        }
+        local_err.clear();
+        const int rc = worker_job(c, job);
+        if (job.after) (void)hipEventDestroy(job.after);
+        {
+            std::lock_guard<std::mutex> lk(c->mu);
+            if (rc && !c->worker_rc) {
+                c->worker_rc = rc;
+                c->worker_err = local_err;
+            }
+            c->busy = false;
+        }
+        c->cv_idle.notify_all();
+    }
+}
+
+}  // namespace
+
+// =====================================================================
+// C ABI
+// =====================================================================
+namespace {
+
+void wait_idle(ss_ctx* c) {
+    std::unique_lock<std::mutex> lk(c->mu);
+    c->cv_idle.wait(lk, [&] { return c->jobs.empty() && !c->busy; });
+}
+
+int upload_matrix(ss_ctx* c, const void* src, int location, size_t bytes, void** tmp_out, const void** dev_src) {
+    *tmp_out = nullptr;
+    if (location == SS_DEVICE) { *dev_src = src; return SS_OK; }
+    HIP_TRY(c, hipMalloc(tmp_out, bytes));
+    hipError_t e = hipMemcpy(*tmp_out, src, bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(*tmp_out); *tmp_out = nullptr; return fail(c, SS_EHIP, "weight upload: %s", hipGetErrorString(e)); }
+    *dev_src = *tmp_out;
+    return SS_OK;
+}
+
+// dst rows <- columns [c0, c0+n) of src[K, ld] (one full matrix staged at a time)
+int slice_into(ss_ctx* c, const void* src, int location, size_t src_rows, size_t ld, size_t row0, int K, int c0, int n,
+               void* dst, int blk, int blk_stride, int row_off) {
+    void* tmp = nullptr;
+    const void* dsrc = nullptr;
+    int rc = upload_matrix(c, src, location, src_rows * ld * c->es, &tmp, &dsrc);
+    if (rc) return rc;
+    const uint8_t* base = (const uint8_t*)dsrc + row0 * ld * c->es;
+    hipError_t e = ssk::slice_transpose(c->dt, base, (int64_t)ld, K, c0, n, dst, blk, blk_stride, row_off, 0);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (tmp) (void)hipFree(tmp);
+    if (e != hipSuccess) return fail(c, SS_EHIP, "weight slicing: %s", hipGetErrorString(e));
+    return SS_OK;
+}
+
+int copy_vec(ss_ctx* c, const void* src, int location, size_t n, void** dst) {
+    if (!*dst) HIP_TRY(c, hipMalloc(dst, n * c->es));
+    HIP_TRY(c, hipMemcpy(*dst, src, n * c->es, location == SS_DEVICE ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice));
+    return SS_OK;
+}
+
+int enqueue_job(ss_ctx* c, Job&& job, hipStream_t stream) {
+    HIP_TRY(c, hipEventCreateWithFlags(&job.after, hipEventDisableTiming));
+    HIP_TRY(c, hipEventRecord(job.after, stream));
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        c->jobs.push_back(std::move(job));
+    }
+    c->cv.notify_one();
+    return SS_OK;
+}
+
+size_t seq_tier_bytes(ss_ctx* c, int32_t len) {
+    return (size_t)c->m.n_layers * 2 * c->m.n_kv_heads * (size_t)len * c->m.head_dim * c->es;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out) {
+    if (!model || !rt || !out) return SS_EINVAL;
+    *out = nullptr;
+    const ss_model_cfg& m = *model;
+    if (m.hidden <= 0 || m.n_q_heads <= 0 || m.n_kv_heads <= 0 || m.ffn <= 0 || m.n_layers <= 0) return SS_EINVAL;
+    if ((m.head_dim != 64 && m.head_dim != 128) || m.page_size != 16) return SS_EINVAL;
+    if (m.n_q_heads % m.n_kv_heads) return SS_EINVAL;
+    if (m.dtype != SS_F32 && m.dtype != SS_BF16) return SS_EINVAL;
+    if (rt->gpu_kv_pages <= 0 || rt->gpu_kv_pages > (1ll << 30) || rt->max_seq_len <= 0 || rt->host_tier_bytes < 0 ||
+        rt->pinned_bytes < 0)
+        return SS_EINVAL;
+    if (hipSetDevice(rt->device) != hipSuccess) return SS_EHIP;
+    ss_ctx* c = new ss_ctx();
+    c->m = m;
+    c->rt = *rt;
+    c->dt = m.dtype;
+    c->es = m.dtype == SS_F32 ? 4 : 2;
+    const char* fg = getenv("SS_FORCE_GENERIC");
+    c->force_generic = fg && fg[0] == '1';
+    int rc = SS_OK;
+    auto boot = [&]() -> int {
+        // rotary table: cos/sin of p * base^(-2i/d), evaluated in double, stored as float pairs
+        const int half = m.head_dim / 2;
+        std::vector<float> tab((size_t)rt->max_seq_len * half * 2);
+        for (int p = 0; p < rt->max_seq_len; ++p)
+            for (int i = 0; i < half; ++i) {
+                const double ang = (double)p * std::pow((double)m.rope_base, -2.0 * i / m.head_dim);
+                tab[((size_t)p * half + i) * 2] = (float)std::cos(ang);
+                tab[((size_t)p * half + i) * 2 + 1] = (float)std::sin(ang);
+            }
+        HIP_TRY(c, hipMalloc((void**)&c->d_rope, tab.size() * sizeof(float)));
+        HIP_TRY(c, hipMemcpy(c->d_rope, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice));
+        if (rt->host_tier_bytes > 0) {
+            c->tier = (uint8_t*)malloc((size_t)rt->host_tier_bytes);
+            if (!c->tier) return fail(c, SS_ENOMEM, "host tier allocation failed");
+            c->tier_cap = (size_t)rt->host_tier_bytes;
+        }
+        c->slot_bytes = ((size_t)rt->pinned_bytes / 2) & ~(size_t)255;
+        if (c->slot_bytes) {
+            HIP_TRY(c, hipHostMalloc((void**)&c->pinned, 2 * c->slot_bytes, hipHostMallocDefault));
+            HIP_TRY(c, hipMalloc((void**)&c->dev_staging, 2 * c->slot_bytes));
+        }
+        c->mv_meta_cap = 16u << 20;
+        HIP_TRY(c, hipHostMalloc((void**)&c->mv_meta_host, c->mv_meta_cap, hipHostMallocDefault));
+        HIP_TRY(c, hipMalloc((void**)&c->mv_meta_dev, c->mv_meta_cap));
+        HIP_TRY(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+        for (int i = 0; i < 2; ++i) HIP_TRY(c, hipEventCreateWithFlags(&c->mv_ev[i], hipEventDisableTiming));
+        return SS_OK;
+    };
+    rc = boot();
+    if (rc) { fprintf(stderr, "ss_create: %s\n", c->err.c_str()); delete c; return rc; }
+    c->worker = std::thread(worker_main, c);
+    *out = c;
+    return SS_OK;
+}
+
+int ss_destroy(ss_ctx* c) {
+    if (!c) return SS_EINVAL;
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        c->stop = true;
+    }
+    c->cv.notify_all();
+    if (c->worker.joinable()) c->worker.join();
+    (void)hipSetDevice(c->rt.device);
+    (void)hipDeviceSynchronize();
+    for (auto& kv : c->shards) {
+        Shard* s = kv.second;
+        for (auto& w : s->w) {
+            for (void* p : {w.g1, w.g2, w.wqkv_t, w.wo_t, w.wgu_t, w.wd_t})
+                if (p) (void)hipFree(p);
+        }
+        for (void* p : s->k_pool) if (p) (void)hipFree(p);
+        for (void* p : s->v_pool) if (p) (void)hipFree(p);
+        if (s->d_k_pools) (void)hipFree(s->d_k_pools);
+        if (s->d_v_pools) (void)hipFree(s->d_v_pools);
+        delete s;
+    }
+    for (DevBuf* b : {&c->ws_h, &c->ws_qkv, &c->ws_attn, &c->ws_gu, &c->ws_act, &c->ws_x1, &c->ws_scratch})
+        if (b->p) (void)hipFree(b->p);
+    for (auto& ms : c->meta) {
+        if (ms.host) (void)hipHostFree(ms.host);
+        if (ms.dev) (void)hipFree(ms.dev);
+        if (ms.done) (void)hipEventDestroy(ms.done);
+    }
+    for (void* p : {(void*)c->d_rope, c->d_embed, c->d_gf, c->d_wlm_t, (void*)c->d_ids, (void*)c->dev_staging,
+                    (void*)c->mv_meta_dev})
+        if (p) (void)hipFree(p);
+    if (c->pinned) (void)hipHostFree(c->pinned);
+    if (c->mv_meta_host) (void)hipHostFree(c->mv_meta_host);
+    for (int i = 0; i < 2; ++i) if (c->mv_ev[i]) (void)hipEventDestroy(c->mv_ev[i]);
+    if (c->side) (void)hipStreamDestroy(c->side);
+    for (auto& r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    free(c->tier);
+    delete c;
+    return SS_OK;
+}
+
+const char* ss_last_error(ss_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+int ss_load_layer(ss_ctx* c, const ss_shard_desc* d, int layer, const ss_layer_weights* w) {
+    if (!c) return SS_EINVAL;
+    if (!w || !w->g1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->g2 || !w->wg || !w->wu || !w->wd)
+        return fail(c, SS_EINVAL, "null weight pointer");
+    if (w->location != SS_HOST && w->location != SS_DEVICE) return fail(c, SS_EINVAL, "bad weight location");
+    Shard* s = nullptr;
+    int rc = get_shard(c, d, &s);
+    if (rc) return rc;
+    if (layer < d->layer_begin || layer >= d->layer_end) return fail(c, SS_EINVAL, "layer %d outside the shard", layer);
+    LayerW& L = s->w[layer - d->layer_begin];
+    const ss_model_cfg& m = c->m;
+    const int H = m.hidden, dh = m.head_dim;
+    const int nq = s->nq_l * dh, nkv = s->nkv_l * dh, F = s->f_l;
+    const size_t es = c->es;
+    auto alloc = [&](void** p, size_t bytes) -> int {
+        if (!*p) HIP_TRY(c, hipMalloc(p, bytes));
+        return SS_OK;
+    };
+    if ((rc = alloc(&L.wqkv_t, (size_t)(nq + 2 * nkv) * H * es))) return rc;
+    if ((rc = alloc(&L.wo_t, (size_t)H * nq * es))) return rc;
+    if ((rc = alloc(&L.wgu_t, (size_t)2 * F * H * es))) return rc;
+    if ((rc = alloc(&L.wd_t, (size_t)H * F * es))) return rc;
+    if ((rc = copy_vec(c, w->g1, w->location, H, &L.g1))) return rc;
+    if ((rc = copy_vec(c, w->g2, w->location, H, &L.g2))) return rc;
+    uint8_t* qkv = (uint8_t*)L.wqkv_t;
+    const size_t qd = (size_t)m.n_q_heads * dh, kd = (size_t)m.n_kv_heads * dh;
+    if ((rc = slice_into(c, w->wq, w->location, H, qd, 0, H, s->q0 * dh, nq, qkv, nq, nq, 0))) return rc;
+    if ((rc = slice_into(c, w->wk, w->location, H, kd, 0, H, s->g0 * dh, nkv, qkv + (size_t)nq * H * es, nkv, nkv, 0))) return rc;
+    if ((rc = slice_into(c, w->wv, w->location, H, kd, 0, H, s->g0 * dh, nkv, qkv + (size_t)(nq + nkv) * H * es, nkv, nkv, 0))) return rc;
+    // Wo rows of this shard's heads -> Wo^T [H, nq]
+    if ((rc = slice_into(c, w->wo, w->location, qd, H, (size_t)s->q0 * dh, nq, 0, H, L.wo_t, H, H, 0))) return rc;
+    // gate / up: interleaved in blocks of 32 rows when the fused SwiGLU epilogue can run
+    L.gu_interleaved = (c->dt == SS_BF16) && !c->force_generic && (F % 32 == 0) && (H % 64 == 0);
+    if (L.gu_interleaved) {
+        if ((rc = slice_into(c, w->wg, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, 32, 64, 0))) return rc;
+        if ((rc = slice_into(c, w->wu, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, 32, 64, 32))) return rc;
+    } else {
+        if ((rc = slice_into(c, w->wg, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, F, F, 0))) return rc;
+        if ((rc = slice_into(c, w->wu, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, F, F, F))) return rc;
+    }
+    if ((rc = slice_into(c, w->wd, w->location, m.ffn, H, (size_t)s->f0, F, 0, H, L.wd_t, H, H, 0))) return rc;
+    L.loaded = true;
+    return SS_OK;
+}
+
+int ss_layer_prefill(ss_ctx* c, const ss_shard_desc* d, int layer, int phase, const ss_batch* b, const void* x_in,
+                     void* out, void* stream) {
+    return layer_call(c, d, layer, phase, b, x_in, out, stream, false);
+}
+
+int ss_layer_decode(ss_ctx* c, const ss_shard_desc* d, int layer, int phase, const ss_batch* b, const void* x_in,
+                    void* out, void* stream) {
+    return layer_call(c, d, layer, phase, b, x_in, out, stream, true);
+}
+
+int ss_kv_swap(ss_ctx* c, const ss_shard_desc* d, int dir, const int64_t* seq_ids, int n, void* stream) {
+    if (!c) return SS_EINVAL;
+    if (n < 0 || (n > 0 && !seq_ids)) return fail(c, SS_EINVAL, "bad sequence list");
+    if (dir != SS_OUT && dir != SS_IN) return fail(c, SS_EINVAL, "bad direction %d", dir);
+    if (!c->tier || !c->slot_bytes) return fail(c, SS_EINVAL, "context was created without a host tier / pinned ring");
+    Shard* s = nullptr;
+    int rc = get_shard(c, d, &s);
+    if (rc) return rc;
+    if ((rc = ensure_pools(c, s))) return rc;
+    if (n == 0) return SS_OK;
+    Job job;
+    job.dir = dir;
+    job.sh = s;
+    if (dir == SS_OUT) {
+        size_t need = 0;
+        for (int i = 0; i < n; ++i) {
+            auto it = s->seqs.find(seq_ids[i]);
+            if (it == s->seqs.end()) return fail(c, SS_ENOENT, "sequence %lld not resident in this shard", (long long)seq_ids[i]);
+            auto ts = c->tier_slots.find(seq_ids[i]);
+            if (ts == c->tier_slots.end()) need += seq_tier_bytes(c, it->second.len);
+            else if (ts->second.len != it->second.len)
+                return fail(c, SS_EINVAL, "sequence %lld is in the tier with length %d, shard holds %d",
+                            (long long)seq_ids[i], ts->second.len, it->second.len);
+        }
+        if (c->tier_top + need > c->tier_cap)
+            return fail(c, SS_ENOMEM, "host tier full: need %zu more bytes, %zu free", need, c->tier_cap - c->tier_top);
+        for (int i = 0; i < n; ++i) {
+            const SeqState& st = s->seqs[seq_ids[i]];
+            auto ts = c->tier_slots.find(seq_ids[i]);
+            if (ts == c->tier_slots.end()) {
+                ts = c->tier_slots.emplace(seq_ids[i], TierSlot{c->tier_top, st.len}).first;
+                c->tier_top += seq_tier_bytes(c, st.len);
+            }
+            job.seqs.push_back({seq_ids[i], st.len, st.pages, ts->second.off});
+        }
+    } else {
+        for (int i = 0; i < n; ++i) {
+            if (!c->tier_slots.count(seq_ids[i]))
+                return fail(c, SS_ENOENT, "sequence %lld not in the host tier", (long long)seq_ids[i]);
+            if (s->seqs.count(seq_ids[i]))
+                return fail(c, SS_EINVAL, "sequence %lld already resident in this shard", (long long)seq_ids[i]);
+        }
+        for (int i = 0; i < n; ++i) {
+            const TierSlot& ts = c->tier_slots[seq_ids[i]];
+            if ((rc = ensure_pages(c, s, seq_ids[i], ts.len))) return rc;
+            const SeqState& st = s->seqs[seq_ids[i]];
+            job.seqs.push_back({seq_ids[i], ts.len, st.pages, ts.off});
+        }
+    }
+    return enqueue_job(c, std::move(job), (hipStream_t)stream);
+}
+
+int ss_kv_reshard(ss_ctx* c, const ss_shard_desc* from, const ss_shard_desc* to, const int64_t* seq_ids, int n,
+                  void* stream) {
+    int rc = ss_kv_swap(c, from, SS_OUT, seq_ids, n, stream);
+    if (rc) return rc;
+    return ss_kv_swap(c, to, SS_IN, seq_ids, n, stream);
+}
+
+int ss_sync(ss_ctx* c) {
+    if (!c) return SS_EINVAL;
+    wait_idle(c);
+    HIP_TRY(c, hipStreamSynchronize(c->side));
+    std::lock_guard<std::mutex> lk(c->mu);
+    if (c->worker_rc) {
+        const int rc = c->worker_rc;
+        c->err = "KV mover: " + c->worker_err;
+        c->worker_rc = 0;
+        c->worker_err.clear();
+        return rc;
+    }
+    return SS_OK;
+}
+
+int ss_kv_free(ss_ctx* c, const ss_shard_desc* d, const int64_t* seq_ids, int n) {
+    if (!c) return SS_EINVAL;
+    Shard* s = nullptr;
+    int rc = get_shard(c, d, &s);
+    if (rc) return rc;
+    wait_idle(c);
+    for (int i = 0; i < n; ++i)
+        if (!s->seqs.count(seq_ids[i])) return fail(c, SS_ENOENT, "sequence %lld not resident", (long long)seq_ids[i]);
+    for (int i = 0; i < n; ++i) {
+        auto it = s->seqs.find(seq_ids[i]);
+        if (it == s->seqs.end()) continue;   // listed twice
+        for (int32_t p : it->second.pages) s->free_pages.push(p);
+        s->seqs.erase(it);
+    }
+    s->version++;
+    return SS_OK;
+}
+
+int ss_host_tier_release(ss_ctx* c, const int64_t* seq_ids, int n) {
+    if (!c) return SS_EINVAL;
+    wait_idle(c);
+    for (int i = 0; i < n; ++i)
+        if (!c->tier_slots.count(seq_ids[i])) return fail(c, SS_ENOENT, "sequence %lld not in the host tier", (long long)seq_ids[i]);
+    for (int i = 0; i < n; ++i) c->tier_slots.erase(seq_ids[i]);
+    if (c->tier_slots.empty()) c->tier_top = 0;
+    return SS_OK;
+}
+
+static int xfer_dev(ss_ctx* c, const ss_shard_desc* d, const int64_t* seq_ids, const int32_t* lens, int n, void* staging,
+                    void* stream, bool import) {
+    if (!c) return SS_EINVAL;
+    if (n < 0 || (n > 0 && (!seq_ids || !staging))) return fail(c, SS_EINVAL, "bad arguments");
+    Shard* s = nullptr;
+    int rc = get_shard(c, d, &s);
+    if (rc) return rc;
+    if ((rc = ensure_pools(c, s))) return rc;
+    if (n == 0) return SS_OK;
+    std::vector<SeqJob> seqs;
+    if (import) {
+        if (!lens) return fail(c, SS_EINVAL, "import needs lengths");
+        for (int i = 0; i < n; ++i) {
+            if (lens[i] <= 0) return fail(c, SS_EINVAL, "sequence %d has length %d", i, lens[i]);
+            if (s->seqs.count(seq_ids[i])) return fail(c, SS_EINVAL, "sequence %lld already resident", (long long)seq_ids[i]);
+        }
+        for (int i = 0; i < n; ++i) {
+            if ((rc = ensure_pages(c, s, seq_ids[i], lens[i]))) return rc;
+            seqs.push_back({seq_ids[i], lens[i], s->seqs[seq_ids[i]].pages, 0});
+        }
+    } else {
+        for (int i = 0; i < n; ++i) {
+            auto it = s->seqs.find(seq_ids[i]);
+            if (it == s->seqs.end()) return fail(c, SS_ENOENT, "sequence %lld not resident", (long long)seq_ids[i]);
+            seqs.push_back({seq_ids[i], it->second.len, it->second.pages, 0});
+        }
+    }
+    const std::vector<Unit> units = make_units(c, s, seqs);
+    hipStream_t st = (hipStream_t)stream;
+    // metadata goes through a pageable image and a synchronous copy; the device
+    // image must outlive the kernels, so it is only rewritten after they finished
+    HIP_TRY(c, hipStreamSynchronize(st));
+    std::vector<uint8_t> img(c->mv_meta_cap / 2);
+    static_assert(sizeof(size_t) == 8, "64-bit only");
+    wait_idle(c);   // shares the mover's device metadata region (second half)
+    uint8_t* md = c->mv_meta_dev;
+    size_t stage_off = 0;
+    for (size_t u0 = 0; u0 < units.size(); u0 += 32768) {
+        const size_t u1 = std::min(units.size(), u0 + 32768);
+        ssk::RepackUnits ru{};
+        const size_t mbytes = build_units(c, s, seqs, units, u0, u1, img.data(), md, img.size(), &ru);
+        if (!mbytes) return fail(c, SS_ENOMEM, "repack metadata region too small");
+        HIP_TRY(c, hipMemcpy(md, img.data(), mbytes, hipMemcpyHostToDevice));
+        uint8_t* stg = (uint8_t*)staging + stage_off;
+        {
+            ProfScope ps(c, 3, st);
+            if (import)
+                K_TRY(c, ssk::kv_scatter(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru, stg, st));
+            else
+                K_TRY(c, ssk::kv_gather(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru, stg, st));
+        }
+        for (size_t u = u0; u < u1; ++u) stage_off += units[u].bytes;
+        if (u1 < units.size()) HIP_TRY(c, hipStreamSynchronize(st));
+    }
+    return SS_OK;
+}
+
+int ss_kv_export_dev(ss_ctx* c, const ss_shard_desc* d, const int64_t* seq_ids, int n, void* staging, void* stream) {
+    return xfer_dev(c, d, seq_ids, nullptr, n, staging, stream, false);
+}
+
+int ss_kv_import_dev(ss_ctx* c, const ss_shard_desc* d, const int64_t* seq_ids, const int32_t* lens, int n,
+                     const void* staging, void* stream) {
+    return xfer_dev(c, d, seq_ids, lens, n, const_cast<void*>(staging), stream, true);
+}
+
+int ss_kv_page_table(ss_ctx* c, const ss_shard_desc* d, int64_t seq, int32_t* pages, int32_t* n_inout) {
+    if (!c || !n_inout) return SS_EINVAL;
+    Shard* s = nullptr;
+    int rc = get_shard(c, d, &s);
+    if (rc) return rc;
+    auto it = s->seqs.find(seq);
+    if (it == s->seqs.end()) return fail(c, SS_ENOENT, "sequence %lld not resident", (long long)seq);
+    const int32_t have = (int32_t)it->second.pages.size();
+    if (pages) std::copy(it->second.pages.begin(), it->second.pages.begin() + std::min(have, *n_inout), pages);
+    *n_inout = have;
+    return SS_OK;
+}
+
+int ss_kv_seq_len(ss_ctx* c, const ss_shard_desc* d, int64_t seq, int32_t* len_out) {
+    if (!c || !len_out) return SS_EINVAL;
+    Shard* s = nullptr;
+    int rc = get_shard(c, d, &s);
+    if (rc) return rc;
+    auto it = s->seqs.find(seq);
+    if (it == s->seqs.end()) return fail(c, SS_ENOENT, "sequence %lld not resident", (long long)seq);
+    *len_out = it->second.len;
+    return SS_OK;
+}
+
+int ss_kv_read(ss_ctx* c, const ss_shard_desc* d, int64_t seq, int layer, void* host_out) {
+    if (!c || !host_out) return SS_EINVAL;
+    Shard* s = nullptr;
+    int rc = get_shard(c, d, &s);
+    if (rc) return rc;
+    if (layer < d->layer_begin || layer >= d->layer_end) return fail(c, SS_EINVAL, "layer %d outside the shard", layer);
+    auto it = s->seqs.find(seq);
+    if (it == s->seqs.end()) return fail(c, SS_ENOENT, "sequence %lld not resident", (long long)seq);
+    if (!s->pools_ready) return fail(c, SS_ENOENT, "shard has no cache yet");
+    wait_idle(c);
+    HIP_TRY(c, hipDeviceSynchronize());
+    std::vector<SeqJob> seqs{{seq, it->second.len, it->second.pages, 0}};
+    std::vector<Unit> units{{0, layer - d->layer_begin, (size_t)2 * s->nkv_l * it->second.len * c->m.head_dim * c->es}};
+    std::vector<uint8_t> img(1 << 20);
+    ssk::RepackUnits ru{};
+    const size_t mbytes = build_units(c, s, seqs, units, 0, 1, img.data(), c->mv_meta_dev, img.size(), &ru);
+    if (!mbytes) return fail(c, SS_ENOMEM, "sequence too long for the inspection path");
+    HIP_TRY(c, hipMemcpy(c->mv_meta_dev, img.data(), mbytes, hipMemcpyHostToDevice));
+    void* tmp = nullptr;
+    HIP_TRY(c, hipMalloc(&tmp, units[0].bytes));
+    hipError_t e = ssk::kv_gather(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru, tmp, 0);
+    if (e == hipSuccess) e = hipMemcpy(host_out, tmp, units[0].bytes, hipMemcpyDeviceToHost);
+    (void)hipFree(tmp);
+    if (e != hipSuccess) return fail(c, SS_EHIP, "kv read: %s", hipGetErrorString(e));
+    return SS_OK;
+}
+
+int ss_host_tier_read(ss_ctx* c, int64_t seq, int layer, void* host_out) {
+    if (!c || !host_out) return SS_EINVAL;
+    if (layer < 0 || layer >= c->m.n_layers) return fail(c, SS_EINVAL, "bad layer %d", layer);
+    auto it = c->tier_slots.find(seq);
+    if (it == c->tier_slots.end()) return fail(c, SS_ENOENT, "sequence %lld not in the host tier", (long long)seq);
+    wait_idle(c);
+    const size_t per_layer = (size_t)2 * c->m.n_kv_heads * it->second.len * c->m.head_dim * c->es;
+    memcpy(host_out, c->tier + it->second.off + per_layer * layer, per_layer);
+    return SS_OK;
+}
+
+int64_t ss_host_tier_used_bytes(ss_ctx* c) { return c ? (int64_t)c->tier_top : -1; }
+
+int64_t ss_kv_free_pages(ss_ctx* c, const ss_shard_desc* d) {
+    if (!c) return SS_EINVAL;
+    Shard* s = nullptr;
+    int rc = get_shard(c, d, &s);
+    if (rc) return rc;
+    if (!s->pools_ready) return c->rt.gpu_kv_pages;
+    return (int64_t)s->free_pages.size();
+}
+
+int ss_load_head(ss_ctx* c, const void* embed, const void* gf, const void* wlm) {
+    if (!c || !embed || !gf || !wlm) return SS_EINVAL;
+    if (c->m.vocab <= 0) return fail(c, SS_EINVAL, "model has no vocabulary");
+    const size_t V = c->m.vocab, H = c->m.hidden;
+    int rc;
+    if ((rc = copy_vec(c, embed, SS_HOST, V * H, &c->d_embed))) return rc;
+    if ((rc = copy_vec(c, gf, SS_HOST, H, &c->d_gf))) return rc;
+    if (!c->d_wlm_t) HIP_TRY(c, hipMalloc(&c->d_wlm_t, V * H * c->es));
+    return slice_into(c, wlm, SS_HOST, H, V, 0, (int)H, 0, (int)V, c->d_wlm_t, (int)V, (int)V, 0);
+}
+
+int ss_embed(ss_ctx* c, const int32_t* ids, int n, void* x_out, void* stream) {
+    if (!c || !ids || !x_out || n <= 0) return SS_EINVAL;
+    if (!c->d_embed) return fail(c, SS_EINVAL, "head weights not loaded");
+    for (int i = 0; i < n; ++i)
+        if (ids[i] < 0 || ids[i] >= c->m.vocab) return fail(c, SS_EINVAL, "token id %d out of range", ids[i]);
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(c, hipStreamSynchronize(st));
+    if ((size_t)n > c->d_ids_cap) {
+        if (c->d_ids) HIP_TRY(c, hipFree(c->d_ids));
+        c->d_ids = nullptr;
+        HIP_TRY(c, hipMalloc((void**)&c->d_ids, sizeof(int32_t) * (size_t)n * 2));
+        c->d_ids_cap = (size_t)n * 2;
+    }
+    HIP_TRY(c, hipMemcpy(c->d_ids, ids, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
+    K_TRY(c, ssk::embed_rows(c->dt, c->d_embed, c->d_ids, x_out, n, c->m.hidden, st));
+    return SS_OK;
+}
+
+int ss_lm_head(ss_ctx* c, const void* x, int n, float* logits, void* stream) {
+    if (!c || !x || !logits || n <= 0) return SS_EINVAL;
+    if (!c->d_wlm_t) return fail(c, SS_EINVAL, "head weights not loaded");
+    hipStream_t st = (hipStream_t)stream;
+    int rc = ensure_buf(c, c->ws_h, (size_t)n * c->m.hidden * c->es);
+    if (rc) return rc;
+    K_TRY(c, ssk::rmsnorm(c->dt, x, c->d_gf, c->ws_h.p, n, c->m.hidden, c->m.rms_eps, st));
+    K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, c->m.hidden, c->d_wlm_t, logits, c->m.vocab, nullptr, n, c->m.vocab,
+                          c->m.hidden, ssk::EPI_STORE_F32, true, st));
+    return SS_OK;
+}
+
+int ss_prof_enable(ss_ctx* c, int on) {
+    if (!c) return SS_EINVAL;
+    c->prof_on = on != 0;
+    return SS_OK;
+}
+
+int ss_prof_reset(ss_ctx* c) {
+    if (!c) return SS_EINVAL;
+    wait_idle(c);
+    HIP_TRY(c, hipDeviceSynchronize());
+    std::lock_guard<std::mutex> lk(c->prof_mu);
+    for (auto& r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    c->prof.clear();
+    return SS_OK;
+}
+
+int ss_prof_read(ss_ctx* c, int cls, double* total_ms_out, int64_t* n_out) {
+    if (!c || !total_ms_out || !n_out) return SS_EINVAL;
+    wait_idle(c);
+    HIP_TRY(c, hipDeviceSynchronize());
+    std::lock_guard<std::mutex> lk(c->prof_mu);
+    double tot = 0;
+    int64_t cnt = 0;
+    for (auto& r : c->prof) {
+        if (r.cls != cls) continue;
+        float ms = 0.f;
+        HIP_TRY(c, hipEventElapsedTime(&ms, r.a, r.b));
+        tot += ms;
+        ++cnt;
+    }
+    *total_ms_out = tot;
+    *n_out = cnt;
+    return SS_OK;
+}
+
+}  // extern "C"
