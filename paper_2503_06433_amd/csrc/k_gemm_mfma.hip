@@ -23,6 +23,7 @@ namespace ssk {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ int lds_chunk_off(int row, int kc) {
     // byte offset of 16-byte chunk kc (0..7) of a 128-byte row
@@ -83,7 +84,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
         b_src[i] = Wt + (size_t)gr * K + kc * 8;
         b_dst[i] = lds_chunk_off(row, kc);
     }
-    vec16 a_reg[A_CH], b_reg[B_CH];
+    u32x4_t a_reg[A_CH], b_reg[B_CH];
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -94,53 +95,61 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int nk = K / 64;
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const vec16*>(a_src[i]);
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) b_reg[i] = *reinterpret_cast<const vec16*>(b_src[i]);
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<vec16*>(As + a_dst[i]) = a_reg[i];
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<vec16*>(Bs + b_dst[i]) = b_reg[i];
-    __syncthreads();
-
-    // fragment read offsets inside a buffer (row part fixed per thread)
     const int lrow = lane & 31, lgrp = lane >> 5;
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) {
+
+    auto fetch = [&](int kt) {
 #pragma unroll
-            for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const vec16*>(a_src[i] + (size_t)(kt + 1) * 64);
+        for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const u32x4_t*>(a_src[i] + (size_t)kt * 64);
 #pragma unroll
-            for (int i = 0; i < B_CH; ++i) b_reg[i] = *reinterpret_cast<const vec16*>(b_src[i] + (size_t)(kt + 1) * 64);
-        }
-        const uint8_t* Ab = As + cur * BM * 128;
-        const uint8_t* Bb = Bs + cur * BN * 128;
+        for (int i = 0; i < B_CH; ++i) b_reg[i] = *reinterpret_cast<const u32x4_t*>(b_src[i] + (size_t)kt * 64);
+    };
+    auto stash = [&](int buf) {
+        uint8_t* An = As + buf * BM * 128;
+        uint8_t* Bn = Bs + buf * BN * 128;
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4_t*>(An + a_dst[i]) = a_reg[i];
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4_t*>(Bn + b_dst[i]) = b_reg[i];
+    };
+    // Fragments of k-step ks+1 are read from LDS while the MFMAs of k-step ks run
+    // (two register sets); scheduling barriers keep the compiler from sinking the
+    // reads (or the global prefetch) down to their first use.
+    auto load_frags = [&](const uint8_t* Ab, const uint8_t* Bb, int ks, bf16x8_t* af, bf16x8_t* bfr) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            af[i] = *reinterpret_cast<const bf16x8_t*>(Ab + lds_chunk_off(wm * (BM / WM) + i * 32 + lrow, ks * 2 + lgrp));
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bb + lds_chunk_off(wn * (BN / WN) + j * 32 + lrow, ks * 2 + lgrp));
+    };
+    auto multiply = [&](int buf) {
+        const uint8_t* Ab = As + buf * BM * 128;
+        const uint8_t* Bb = Bs + buf * BN * 128;
+        bf16x8_t af[2][TM], bfr[2][TN];
+        load_frags(Ab, Bb, 0, af[0], bfr[0]);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            bf16x8_t af[TM], bfr[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                af[i] = *reinterpret_cast<const bf16x8_t*>(Ab + lds_chunk_off(wm * (BM / WM) + i * 32 + lrow, ks * 2 + lgrp));
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8_t*>(Bb + lds_chunk_off(wn * (BN / WN) + j * 32 + lrow, ks * 2 + lgrp));
+            if (ks < 3) load_frags(Ab, Bb, ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (kt + 1 < nk) {
-            uint8_t* An = As + (cur ^ 1) * BM * 128;
-            uint8_t* Bn = Bs + (cur ^ 1) * BN * 128;
-#pragma unroll
-            for (int i = 0; i < A_CH; ++i) *reinterpret_cast<vec16*>(An + a_dst[i]) = a_reg[i];
-#pragma unroll
-            for (int i = 0; i < B_CH; ++i) *reinterpret_cast<vec16*>(Bn + b_dst[i]) = b_reg[i];
-        }
+    };
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+        fetch(kt + 1);          // global loads of the next slice fly while this one is multiplied
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(kt & 1);
+        stash((kt + 1) & 1);
         __syncthreads();
     }
+    multiply((nk - 1) & 1);
 
     // ---- epilogue
     const int col_in = lane & 31;
@@ -235,4 +244,21 @@ hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int l
     return launch_cfg<64, 64, 2, 1>(a, lda, w, c, ldc, r, M, N, K, epi, s);
 }
 
+}  // namespace ssk
+
+// Tuning hook (not part of the C ABI): run one named tile configuration.
+namespace ssk {
+hipError_t gemm_mfma_bf16_cfg(int cfg, const void* A, int lda, const void* Wt, void* C, int ldc, const void* R,
+                              int M, int N, int K, int epi, hipStream_t s) {
+    const bf16_t* a = (const bf16_t*)A;
+    const bf16_t* w = (const bf16_t*)Wt;
+    bf16_t* c = (bf16_t*)C;
+    const bf16_t* r = (const bf16_t*)R;
+    switch (cfg) {
+        case 0: return launch_cfg<256, 256, 2, 4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        case 1: return launch_cfg<128, 128, 2, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        case 2: return launch_cfg<64, 64, 2, 1>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        default: return hipErrorInvalidValue;
+    }
+}
 }  // namespace ssk

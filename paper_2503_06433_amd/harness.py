@@ -1,11 +1,13 @@
 """Helpers shared by the GPU parity tests, smoke() and bench.py: turning seeded
-numpy inputs into device buffers and back.  torch is used for device memory
-only; nothing here computes anything of the method."""
+numpy inputs into device buffers and back, and building contexts from a
+workload description.  torch is used for device memory only; nothing here
+computes anything of the method, and nothing here touches the CPU oracle."""
 import numpy as np
 import torch
 
-import paper_2503_06433_amd as ss
 import workloads as wl
+
+from . import binding as ss
 
 
 def model_cfg(cfg):

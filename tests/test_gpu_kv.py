@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     import paper_2503_06433_amd as ss
-    from gpu_util import make_context, to_device, to_raw, pp_desc, tp_desc
+    from paper_2503_06433_amd.harness import make_context, to_device, to_raw, pp_desc, tp_desc
 
 
 def _cfg(dtype, d=128, n_kv=4, n_layers=3):

@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     import paper_2503_06433_amd as ss
-    from gpu_util import (make_context, to_device, to_f64, empty_like_acts, rel_err, tol, pp_desc, tp_desc)
+    from paper_2503_06433_amd.harness import (make_context, to_device, to_f64, empty_like_acts, rel_err, tol, pp_desc, tp_desc)
 
 
 def _load(ctx, desc, cfg, raws):

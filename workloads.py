@@ -199,3 +199,28 @@ def config5():
 
 
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
+
+
+# ---------------------------------------------------------------------------
+# large inputs drawn directly in device memory (torch's seeded generator is the
+# random source; the values are inputs like any other and are copied to the host
+# whenever the oracle needs them)
+# ---------------------------------------------------------------------------
+def device_normal(shape, seed, dtype, std=1.0, device="cuda"):
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(int(seed))
+    t = torch.empty(shape, device=device, dtype=torch.float32 if dtype == F32 else torch.bfloat16)
+    t.normal_(0.0, std, generator=g)
+    return t
+
+
+def device_layer_weights(cfg, seed, std=0.02, device="cuda"):
+    """Same shapes and distributions as make_layer_weights, drawn on the device."""
+    out = {}
+    for j, (name, shape) in enumerate(layer_weight_shapes(cfg).items()):
+        w = device_normal(shape, seed * 16 + j, cfg.dtype, std, device)
+        if name in ("g1", "g2"):
+            w += 1.0
+        out[name] = w
+    return out
