@@ -49,7 +49,7 @@ typedef struct {
 typedef struct {
     int64_t gpu_kv_pages;    /* pages in the pool of EACH shard descriptor used */
     int64_t host_tier_bytes; /* capacity of the host tier (complete caches) */
-    int64_t pinned_bytes;    /* pinned staging ring, split into two slots */
+    int64_t pinned_bytes;    /* pinned staging: two lanes (out, in) of two slots each */
     int32_t device;          /* HIP device ordinal */
     int32_t max_seq_len;     /* longest sequence (rotary table size) */
 } ss_runtime_cfg;
@@ -97,8 +97,7 @@ int ss_load_layer(ss_ctx*, const ss_shard_desc*, int layer, const ss_layer_weigh
  * layer"; prefill handles all prompt tokens at once, decode one token per
  * sequence against its KV cache) --------------------------------------------
  *
- * x_in [T, hidden] device, out [T, hidden] device (may alias x_in only for
- * SS_MLP and SS_ATTN with k == 1 is NOT allowed either: keep them distinct).
+ * x_in [T, hidden] device, out [T, hidden] device; out must not alias x_in.
  * T = sum of q_lens (prefill) or n_seqs (decode, every q_len must be 1).
  *
  * phase SS_ATTN: RMSNorm, QKV projection, rotary embedding, K/V written into
@@ -123,14 +122,16 @@ int ss_layer_decode(ss_ctx*, const ss_shard_desc*, int layer, int phase, const s
  * Host tier: per sequence one slot holding the COMPLETE cache of exactly s
  * tokens, element (layer l, c in {0:K,1:V}, kv head g, position p, e) at
  *   ((((l*2 + c)*n_kv + g)*s + p)*head_dim + e
- * elements from the slot's base.  Slots are bump-allocated; when the last live
+ * elements from the slot's base.  Slots are placed first-fit at the lowest free
+ * address and freed blocks merge with their neighbours, so when the last live
  * sequence is released the tier is empty and allocation restarts at 0.
  *
  * ss_kv_swap(SS_OUT): gathers the descriptor's layers/heads of the listed
  *   sequences from its pages into heads-major staging, copies to the pinned
  *   ring (asynchronous DMA on the side stream), then host-copies into the tier
  *   (stage two, on the library's host thread).  Pages stay allocated: release
- *   them with ss_kv_free after ss_sync.  SS_ENOMEM when the tier is full.
+ *   them with ss_kv_free (which waits for the movements that still read them).  SS_ENOMEM when
+ *   the tier is full.
  * ss_kv_swap(SS_IN): allocates pages in the descriptor's pool (in call order,
  *   lowest free id first) and fills them with the descriptor's layers/heads
  *   taken from the tier.  SS_ENOENT if a sequence is not in the tier.
@@ -142,6 +143,12 @@ int ss_kv_swap(ss_ctx*, const ss_shard_desc*, int dir, const int64_t* seq_ids, i
 int ss_kv_reshard(ss_ctx*, const ss_shard_desc* from, const ss_shard_desc* to,
                   const int64_t* seq_ids, int n, void* stream);
 int ss_sync(ss_ctx*);                       /* drains the host thread and the side stream */
+/* Completion of individual movements (the notification the asynchronous prefetcher gives the
+ * scheduler, paper section 5.2): every ss_kv_swap enqueues one job (ss_kv_reshard two), jobs
+ * complete in order.  ss_kv_jobs_issued returns how many were enqueued so far; ss_kv_wait(n)
+ * returns once the first n have completed (data visible to later compute on any stream). */
+int64_t ss_kv_jobs_issued(ss_ctx*);
+int ss_kv_wait(ss_ctx*, int64_t n_jobs);
 int ss_kv_free(ss_ctx*, const ss_shard_desc*, const int64_t* seq_ids, int n);  /* pages back to the pool */
 int ss_host_tier_release(ss_ctx*, const int64_t* seq_ids, int n);
 

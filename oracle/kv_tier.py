@@ -59,32 +59,44 @@ def tier_get(tier, base, s, n_kv, d, layers, heads):
 
 
 class TierAllocator:
-    """Bump allocation of sequence slots in the host tier.  A sequence that does
-    not fit means the tier is full (the paper's trigger for leaving the prefill
-    phase); when the last live sequence is released the tier is empty again
-    and the bump pointer returns to 0 (the trigger for leaving decode)."""
+    """Placement of sequence slots in the host tier: first fit at the lowest
+    free address; a released block merges with free neighbours.  A sequence that
+    fits nowhere means the tier is full (the paper's trigger for leaving the
+    prefill phase); once every live sequence is released the tier is one free
+    block again and placement restarts at 0 (the trigger for leaving decode).
+    Keeping holes reusable lets the swap-out of one batch overlap the drain of
+    the previous one."""
 
     def __init__(self, capacity_elems):
         self.capacity = capacity_elems
-        self.top = 0
+        self.free = [(0, capacity_elems)]        # sorted (offset, length)
         self.base = {}
-        self.live = 0
+
+    @property
+    def used(self):
+        return sum(n for _, n in self.base.values())
 
     def place(self, seq, elems):
         if seq in self.base:
             return self.base[seq][0]
-        if self.top + elems > self.capacity:
-            raise MemoryError("host tier full")
-        self.base[seq] = (self.top, elems)
-        self.top += elems
-        self.live += 1
-        return self.base[seq][0]
+        for j, (off, length) in enumerate(self.free):
+            if length >= elems:
+                self.free[j:j + 1] = [(off + elems, length - elems)] if length > elems else []
+                self.base[seq] = (off, elems)
+                return off
+        raise MemoryError("host tier full")
 
     def release(self, seq):
-        del self.base[seq]
-        self.live -= 1
-        if self.live == 0:
-            self.top = 0
+        off, elems = self.base.pop(seq)
+        blocks = sorted(self.free + [(off, elems)])
+        merged = [blocks[0]]
+        for o, n in blocks[1:]:
+            po, pn = merged[-1]
+            if po + pn == o:
+                merged[-1] = (po, pn + n)
+            else:
+                merged.append((o, n))
+        self.free = merged
 
 
 # --------------------------------------------------------------------------

@@ -80,6 +80,8 @@ def load_library():
         "ss_kv_swap": (I, [V, D, I, P(L), I, V]),
         "ss_kv_reshard": (I, [V, D, D, P(L), I, V]),
         "ss_sync": (I, [V]),
+        "ss_kv_jobs_issued": (L, [V]),
+        "ss_kv_wait": (I, [V, L]),
         "ss_kv_free": (I, [V, D, P(L), I]),
         "ss_host_tier_release": (I, [V, P(L), I]),
         "ss_kv_export_dev": (I, [V, D, P(L), I, V, V]),
@@ -106,7 +108,7 @@ def load_library():
 
 
 EXPORTED = ("ss_create ss_destroy ss_last_error ss_load_layer ss_layer_prefill ss_layer_decode ss_kv_swap "
-            "ss_kv_reshard ss_sync ss_kv_free ss_host_tier_release ss_kv_export_dev ss_kv_import_dev "
+            "ss_kv_reshard ss_sync ss_kv_jobs_issued ss_kv_wait ss_kv_free ss_host_tier_release ss_kv_export_dev ss_kv_import_dev "
             "ss_kv_page_table ss_kv_seq_len ss_kv_read ss_host_tier_read ss_host_tier_used_bytes "
             "ss_kv_free_pages ss_load_head ss_embed ss_lm_head ss_prof_enable ss_prof_read ss_prof_reset").split()
 
@@ -193,6 +195,12 @@ class Context:
 
     def sync(self):
         self._ck(self.lib.ss_sync(self.h))
+
+    def kv_jobs_issued(self):
+        return self.lib.ss_kv_jobs_issued(self.h)
+
+    def kv_wait(self, n_jobs):
+        self._ck(self.lib.ss_kv_wait(self.h, n_jobs))
 
     def kv_free(self, desc, seq_ids):
         s = _i64(seq_ids)

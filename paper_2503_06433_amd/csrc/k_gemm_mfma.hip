@@ -24,6 +24,7 @@ namespace ssk {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+constexpr int EPI_PARTIAL = 100;   // internal: fp32 split-K partials
 
 __device__ __forceinline__ int lds_chunk_off(int row, int kc) {
     // byte offset of 16-byte chunk kc (0..7) of a 128-byte row
@@ -36,7 +37,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
                                                                  const bf16_t* __restrict__ Wt,
                                                                  bf16_t* __restrict__ C, int ldc,
                                                                  const bf16_t* __restrict__ R, int M, int N, int K,
-                                                                 int tiles_m, int tiles_n, int per_xcd) {
+                                                                 int tiles_m, int tiles_n, int per_xcd, int ksplit) {
     constexpr int NT = 64 * WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;   // 16-byte chunks per thread per slice
@@ -94,14 +95,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nk = K / 64;
+    // split-K: blockIdx.y owns K slices [kt0, kt0 + nk)
+    const int nk = K / 64 / ksplit;
+    const int kt0 = blockIdx.y * nk;
     const int lrow = lane & 31, lgrp = lane >> 5;
 
     auto fetch = [&](int kt) {
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const u32x4_t*>(a_src[i] + (size_t)kt * 64);
+        for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const u32x4_t*>(a_src[i] + (size_t)(kt0 + kt) * 64);
 #pragma unroll
-        for (int i = 0; i < B_CH; ++i) b_reg[i] = *reinterpret_cast<const u32x4_t*>(b_src[i] + (size_t)kt * 64);
+        for (int i = 0; i < B_CH; ++i) b_reg[i] = *reinterpret_cast<const u32x4_t*>(b_src[i] + (size_t)(kt0 + kt) * 64);
     };
     auto stash = [&](int buf) {
         uint8_t* An = As + buf * BM * 128;
@@ -153,6 +156,24 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
 
     // ---- epilogue
     const int col_in = lane & 31;
+    if (EPI == EPI_PARTIAL) {      // fp32 partial sums of this K range: [split][M][N]
+        float* P = reinterpret_cast<float*>(C) + (size_t)blockIdx.y * M * N;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int rbase = m0 + wm * (BM / WM) + i * 32 + 4 * lgrp;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int c = n0 + wn * (BN / WN) + j * 32 + col_in;
+                if (c >= N) continue;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = rbase + 8 * (v >> 2) + (v & 3);
+                    if (r < M) P[(size_t)r * N + c] = acc[i][j][v];
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int rbase = m0 + wm * (BM / WM) + i * 32 + 4 * lgrp;
@@ -188,34 +209,233 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
     }
 }
 
-bool gemm_mfma_supported(int M, int N, int K, int lda, int ldc, int epi) {
-    if (K % 64 != 0 || lda % 8 != 0) return false;
-    if (epi == EPI_STORE_F32) return false;
-    if (epi == EPI_SWIGLU && (N % 64 != 0)) return false;
-    (void)M; (void)ldc;
-    return true;
+
+// ----------------------------------------------------------------------------
+// Large-tile kernel with direct global->LDS loads and a multi-stage LDS ring.
+//
+// 256 x 256 tile, 8 waves (2 x 4, wave tile 128 x 64), K slices of 32, NS ring
+// stages of 32 KB.  `global_load_lds_dwordx4` moves 16 bytes per lane straight
+// into LDS (lane j of a wave lands at M0 + 16*j), so no registers are spent on
+// staging and slices can be requested NS-1 iterations ahead: an L2 miss (about
+// one in five requests here, served by the memory-side cache or HBM) has
+// several thousand cycles to arrive instead of one iteration.  Completion is
+// tracked with vmcnt by hand (the loads are issued from inline asm), and a
+// bare s_barrier publishes a stage; the fence form of the barrier would drain
+// every outstanding load.
+//
+// LDS rows are 64 bytes (4 chunks of 16 bytes); chunk position = kc ^ sw(row)
+// with sw(row) = ((row>>1)&3) ^ ((row>>3)&1), which spreads the 16 rows that one
+// pass of a 16-byte fragment read touches over all banks.  A wave-level load
+// covers 16 consecutive rows: lane j supplies row j/4, position j%4, and
+// therefore fetches global chunk (j%4) ^ sw(row) of that row.
+// ----------------------------------------------------------------------------
+__device__ __forceinline__ int lds64_off(int row, int kc) {
+    const int sw = ((row >> 1) & 3) ^ ((row >> 3) & 1);
+    return row * 64 + ((kc ^ sw) << 4);
 }
 
-template <int BM, int BN, int WM, int WN>
-static hipError_t launch_cfg(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
+
+template <int EPI, int NS, int PROBE = 0>
+__global__ __launch_bounds__(512) void gemm_mfma_dma_kernel(const bf16_t* __restrict__ A, int lda,
+                                                            const bf16_t* __restrict__ Wt, bf16_t* __restrict__ C,
+                                                            int ldc, const bf16_t* __restrict__ R, int M, int N, int K,
+                                                            int tiles_m, int tiles_n, int per_xcd) {
+    constexpr int BM = 256, BN = 256, WN = 4, TM = 4, TN = 2;
+    constexpr int STAGE = (BM + BN) * 64;        // bytes per ring stage
+    constexpr int LPS = 4;                       // DMA loads per wave per stage
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    const int xcd = blockIdx.x & 7;
+    const int logical = xcd * per_xcd + (blockIdx.x >> 3);
+    if ((blockIdx.x >> 3) >= per_xcd || logical >= tiles_m * tiles_n) return;
+    constexpr int GM = 8;
+    const int group_size = GM * tiles_n;
+    const int group = logical / group_size;
+    const int first_m = group * GM;
+    const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+    const int in_group = logical - group * group_size;
+    const int m0 = (first_m + in_group % gm) * BM, n0 = (in_group / gm) * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
+
+    // ---- DMA assignment: waves 0-3 bring A rows [64w, 64w+64), waves 4-7 bring Wt rows [64(w-4), ...)
+    const bool isA = wave < 4;
+    const int row_base = (wave & 3) * 64;
+    const uint8_t* src[LPS];
+#pragma unroll
+    for (int i = 0; i < LPS; ++i) {
+        const int row = (PROBE & 4) ? row_base + i * 8 + (lane >> 3) : row_base + i * 16 + (lane >> 2);
+        const int kc = (PROBE & 4) ? (lane & 7) : (lane & 3) ^ (((row >> 1) & 3) ^ ((row >> 3) & 1));
+        if (isA) {
+            int gr = ((PROBE & 8) ? 0 : m0) + row;
+            gr = gr < M ? gr : M - 1;
+            src[i] = reinterpret_cast<const uint8_t*>(A + (size_t)gr * lda + kc * 8);
+        } else {
+            int gr = ((PROBE & 8) ? 0 : n0) + row;
+            gr = gr < N ? gr : N - 1;
+            src[i] = reinterpret_cast<const uint8_t*>(Wt + (size_t)gr * K + kc * 8);
+        }
+    }
+    const uint32_t dst0 = lds_base + (isA ? 0 : BM * 64) + row_base * 64;
+    const int nk = K / 32;
+    // one DMA load (1 KB per wave) of a slice; slices past the end repeat the last one, which is
+    // harmless and keeps the vmcnt bookkeeping uniform
+    auto issue1 = [&](int slice, int i) {
+        const int sl = slice < nk ? slice : nk - 1;
+        const uint32_t d = dst0 + (uint32_t)(slice % NS) * STAGE;
+        dma16(src[i] + (size_t)sl * 64, d + i * 1024);
+    };
+    auto issue = [&](int slice) {
+#pragma unroll
+        for (int i = 0; i < LPS; ++i) issue1(slice, i);
+    };
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int lrow = lane & 31, lgrp = lane >> 5;
+    int a_off[TM][2], b_off[TN][2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a_off[i][ks] = lds64_off(wm * 128 + i * 32 + lrow, ks * 2 + lgrp);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b_off[j][ks] = BM * 64 + lds64_off(wn * 64 + j * 32 + lrow, ks * 2 + lgrp);
+    }
+
+    // Pipeline (per K slice kt, two MFMA groups G0 = k-step 0, G1 = k-step 1):
+    //   [A] read fragments F1(kt) from LDS; issue G0 with F0(kt)
+    //   [B] wait until slice kt+1 has landed and F1(kt) has arrived; barrier
+    //       -> stage kt+1 is readable by everyone, stage kt is no longer read by anyone
+    //   [C] request slice kt+NS into stage kt; read F0(kt+1); issue G1 with F1(kt)
+    // so every MFMA group has its operands requested one group ahead, and the
+    // barrier falls between two groups whose MFMAs keep the pipe busy meanwhile.
+    auto wait_landed = [&](int younger) {     // vmcnt <= 4 * younger (immediates only)
+        if (younger >= 4) __builtin_amdgcn_s_waitcnt(0x4F70);       // 16
+        else if (younger == 3) __builtin_amdgcn_s_waitcnt(0x0F7C);  // 12
+        else if (younger == 2) __builtin_amdgcn_s_waitcnt(0x0F78);  // 8
+        else if (younger == 1) __builtin_amdgcn_s_waitcnt(0x0F74);  // 4
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+    };
+    bf16x8_t af[2][TM], bfr[2][TN];
+    auto read_frags = [&](const uint8_t* st, int ks) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[ks][i] = *reinterpret_cast<const bf16x8_t*>(st + a_off[i][ks]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[ks][j] = *reinterpret_cast<const bf16x8_t*>(st + b_off[j][ks]);
+    };
+    // The L1 -> LDS path moves 64 bytes per clock at best, so a slice (32 KB per block) needs at least
+    // 512 of the ~1024 cycles its MFMAs take: the DMA loads are spread between the MFMAs instead of
+    // being queued in one burst that would hold up the fragment reads issued behind them.
+    auto mfma_half = [&](int ks, int h) {
+#pragma unroll
+        for (int i = 2 * h; i < 2 * h + 2; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
+    };
+
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue(s);
+    wait_landed(NS - 2);           // slice 0 has landed (slices 1 .. NS-2 may still fly)
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    issue1(NS - 1, 0);
+    issue1(NS - 1, 1);
+    read_frags(smem, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+        const uint8_t* st = smem + (kt % NS) * STAGE;
+        const uint8_t* stn = smem + ((kt + 1) % NS) * STAGE;
+        read_frags(st, 1);                                   // [A]
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_half(0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!(PROBE & 1)) issue1(kt + NS - 1, 2);            // second half of the slice whose stage was freed one barrier ago
+        mfma_half(0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!(PROBE & 1)) issue1(kt + NS - 1, 3);
+        wait_landed(NS - 2);                                 // [B] slice kt+1 complete (4 * (NS-2) younger loads may fly)
+        __builtin_amdgcn_s_waitcnt(0xC07F);                  // lgkmcnt(0): F1(kt) is in registers
+        if (!(PROBE & 2)) __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(stn, 0);                                  // [C]
+        __builtin_amdgcn_sched_barrier(0);
+        if (!(PROBE & 1)) issue1(kt + NS, 0);
+        mfma_half(1, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!(PROBE & 1)) issue1(kt + NS, 1);
+        mfma_half(1, 1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the repeats issued past the end
+
+    const int col_in = lane & 31;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int rbase = m0 + wm * 128 + i * 32 + 4 * lgrp;
+        if (EPI == EPI_SWIGLU) {
+#pragma unroll
+            for (int j = 0; j < TN; j += 2) {
+                const int nb = n0 + wn * 64 + j * 32;
+                const int oc = (nb >> 1) + col_in;
+                if (nb + col_in >= N) continue;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = rbase + 8 * (v >> 2) + (v & 3);
+                    if (r >= M) continue;
+                    const float g = acc[i][j][v], u = acc[i][j + 1][v];
+                    C[(size_t)r * ldc + oc] = f2bf(g / (1.0f + __expf(-g)) * u);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int c = n0 + wn * 64 + j * 32 + col_in;
+                if (c >= N) continue;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = rbase + 8 * (v >> 2) + (v & 3);
+                    if (r >= M) continue;
+                    float o = acc[i][j][v];
+                    if (EPI == EPI_RESIDUAL) o += bf2f(R[(size_t)r * ldc + c]);
+                    C[(size_t)r * ldc + c] = f2bf(o);
+                }
+            }
+        }
+    }
+}
+
+template <int NS, int PROBE = 0>
+static hipError_t launch_dma(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
                              int N, int K, int epi, hipStream_t s) {
-    constexpr int NT = 64 * WM * WN;
-    constexpr size_t LDS = (size_t)2 * (BM + BN) * 128;
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    constexpr size_t LDS = (size_t)NS * 512 * 64;
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     const long long n_tiles = (long long)tiles_m * tiles_n;
-    if (n_tiles > (1ll << 30)) return hipErrorInvalidValue;
+    if (n_tiles > (1ll << 30) || K % 32 != 0) return hipErrorInvalidValue;
     const int per_xcd = (int)((n_tiles + 7) / 8);
     const unsigned grid = (unsigned)per_xcd * 8;
 #define SS_LAUNCH(E)                                                                                            \
     {                                                                                                           \
-        auto kfn = gemm_mfma_kernel<BM, BN, WM, WN, E>;                                                         \
+        auto kfn = gemm_mfma_dma_kernel<E, NS, PROBE>;                                                                 \
         static bool attr_set = false;                                                                           \
         if (!attr_set) {                                                                                        \
             hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS); \
             if (e != hipSuccess) return e;                                                                      \
             attr_set = true;                                                                                    \
         }                                                                                                       \
-        kfn<<<grid, NT, LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd);                   \
+        kfn<<<grid, 512, LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd);                  \
     }
     switch (epi) {
         case EPI_STORE: SS_LAUNCH(EPI_STORE) break;
@@ -229,19 +449,102 @@ static hipError_t launch_cfg(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t*
     return hipGetLastError();
 }
 
+bool gemm_mfma_supported(int M, int N, int K, int lda, int ldc, int epi) {
+    if (K % 64 != 0 || lda % 8 != 0) return false;
+    if (epi == EPI_STORE_F32) return false;
+    if (epi == EPI_SWIGLU && (N % 64 != 0)) return false;
+    (void)M; (void)ldc;
+    return true;
+}
+
+// Sums the split-K partials [S][M][N] and applies the epilogue.
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ P, int S, bf16_t* __restrict__ C,
+                                                            int ldc, const bf16_t* __restrict__ R, int M, int N) {
+    const int n_out = (EPI == EPI_SWIGLU) ? N / 2 : N;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)M * n_out) return;
+    const int m = (int)(idx / n_out), j = (int)(idx % n_out);
+    const size_t plane = (size_t)M * N;
+    if (EPI == EPI_SWIGLU) {
+        const int ng = (j >> 5) * 64 + (j & 31);
+        float g = 0.f, u = 0.f;
+        for (int s = 0; s < S; ++s) { g += P[s * plane + (size_t)m * N + ng]; u += P[s * plane + (size_t)m * N + ng + 32]; }
+        C[(size_t)m * ldc + j] = f2bf(g / (1.0f + __expf(-g)) * u);
+    } else {
+        float o = 0.f;
+        for (int s = 0; s < S; ++s) o += P[s * plane + (size_t)m * N + j];
+        if (EPI == EPI_RESIDUAL) o += bf2f(R[(size_t)m * ldc + j]);
+        C[(size_t)m * ldc + j] = f2bf(o);
+    }
+}
+
+template <int BM, int BN, int WM, int WN>
+static hipError_t launch_cfg(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
+                             int N, int K, int epi, hipStream_t s, int ksplit = 1, float* ws = nullptr) {
+    constexpr int NT = 64 * WM * WN;
+    constexpr size_t LDS = (size_t)2 * (BM + BN) * 128;
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const long long n_tiles = (long long)tiles_m * tiles_n;
+    if (n_tiles > (1ll << 30)) return hipErrorInvalidValue;
+    if (ksplit < 1 || (K / 64) % ksplit != 0 || (ksplit > 1 && !ws)) return hipErrorInvalidValue;
+    const int per_xcd = (int)((n_tiles + 7) / 8);
+    const dim3 grid((unsigned)per_xcd * 8, ksplit);
+#define SS_LAUNCH(E, OUT)                                                                                       \
+    {                                                                                                           \
+        auto kfn = gemm_mfma_kernel<BM, BN, WM, WN, E>;                                                         \
+        static bool attr_set = false;                                                                           \
+        if (!attr_set) {                                                                                        \
+            hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS); \
+            if (e != hipSuccess) return e;                                                                      \
+            attr_set = true;                                                                                    \
+        }                                                                                                       \
+        kfn<<<grid, NT, LDS, s>>>(A, lda, Wt, OUT, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd, ksplit);         \
+    }
+    if (ksplit > 1) {
+        SS_LAUNCH(EPI_PARTIAL, reinterpret_cast<bf16_t*>(ws))
+        const size_t n_out = (size_t)M * (epi == EPI_SWIGLU ? N / 2 : N);
+        const unsigned rgrid = (unsigned)((n_out + 255) / 256);
+        switch (epi) {
+            case EPI_STORE: splitk_reduce_kernel<EPI_STORE><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N); break;
+            case EPI_RESIDUAL:
+                if (!R) return hipErrorInvalidValue;
+                splitk_reduce_kernel<EPI_RESIDUAL><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N);
+                break;
+            case EPI_SWIGLU: splitk_reduce_kernel<EPI_SWIGLU><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N); break;
+            default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
+    switch (epi) {
+        case EPI_STORE: SS_LAUNCH(EPI_STORE, C) break;
+        case EPI_RESIDUAL:
+            if (!R) return hipErrorInvalidValue;
+            SS_LAUNCH(EPI_RESIDUAL, C) break;
+        case EPI_SWIGLU: SS_LAUNCH(EPI_SWIGLU, C) break;
+        default: return hipErrorInvalidValue;
+    }
+#undef SS_LAUNCH
+    return hipGetLastError();
+}
+
 hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int ldc, const void* R, int M, int N,
-                          int K, int epi, hipStream_t s) {
+                          int K, int epi, hipStream_t s, float* ws, size_t ws_bytes) {
     const bf16_t* a = (const bf16_t*)A;
     const bf16_t* w = (const bf16_t*)Wt;
     bf16_t* c = (bf16_t*)C;
     const bf16_t* r = (const bf16_t*)R;
-    // Tile choice: the large tile when it still yields a few waves of blocks per
-    // CU, smaller tiles to keep all 256 CUs streaming weights at decode sizes.
+    // Prefill-sized outputs: the 256 x 256 direct-to-LDS kernel.  Smaller outputs (decode batches)
+    // are bound by streaming the weights: 128 x 128 tiles, and K split until at least ~512 blocks
+    // keep all 256 CUs pulling from HBM (partials in fp32, summed by a small second kernel).
     const long long big = (long long)((M + 255) / 256) * ((N + 255) / 256);
+    if (big >= 512) return launch_dma<4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
     const long long mid = (long long)((M + 127) / 128) * ((N + 127) / 128);
-    if (big >= 512) return launch_cfg<256, 256, 2, 4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-    if (mid >= 512) return launch_cfg<128, 128, 2, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-    return launch_cfg<64, 64, 2, 1>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+    int split = 1;
+    while (split < 8 && mid * split < 512 && (K / 64) % (split * 2) == 0 &&
+           (size_t)(split * 2) * M * N * sizeof(float) <= ws_bytes && ws)
+        split *= 2;
+    return launch_cfg<128, 128, 2, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s, split, ws);
 }
 
 }  // namespace ssk
@@ -249,15 +552,23 @@ hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int l
 // Tuning hook (not part of the C ABI): run one named tile configuration.
 namespace ssk {
 hipError_t gemm_mfma_bf16_cfg(int cfg, const void* A, int lda, const void* Wt, void* C, int ldc, const void* R,
-                              int M, int N, int K, int epi, hipStream_t s) {
+                              int M, int N, int K, int epi, hipStream_t s, int ksplit, float* ws) {
     const bf16_t* a = (const bf16_t*)A;
     const bf16_t* w = (const bf16_t*)Wt;
     bf16_t* c = (bf16_t*)C;
     const bf16_t* r = (const bf16_t*)R;
     switch (cfg) {
-        case 0: return launch_cfg<256, 256, 2, 4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-        case 1: return launch_cfg<128, 128, 2, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-        case 2: return launch_cfg<64, 64, 2, 1>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        case 0: return launch_cfg<256, 256, 2, 4>(a, lda, w, c, ldc, r, M, N, K, epi, s, ksplit, ws);
+        case 1: return launch_cfg<128, 128, 2, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s, ksplit, ws);
+        case 2: return launch_cfg<64, 64, 2, 1>(a, lda, w, c, ldc, r, M, N, K, epi, s, ksplit, ws);
+        case 3: return launch_dma<4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        case 4: return launch_dma<5>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        case 5: return launch_dma<3>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        case 6: return launch_dma<4, 1>(a, lda, w, c, ldc, r, M, N, K, epi, s);   // timing probes: wrong results
+        case 7: return launch_dma<4, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        case 8: return launch_dma<4, 3>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        case 9: return launch_dma<4, 4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        case 10: return launch_dma<4, 8>(a, lda, w, c, ldc, r, M, N, K, epi, s);
         default: return hipErrorInvalidValue;
     }
 }

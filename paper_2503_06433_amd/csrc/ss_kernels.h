@@ -23,9 +23,11 @@ enum Epilogue {
 // row-major [N,K] (K contiguous), C row-major with leading dimension ldc.
 // force_generic selects the plain LDS-tiled FMA kernel (any shape, any dtype);
 // otherwise bf16 with K % 64 == 0 runs on the MFMA kernel.
+// `ws` is an optional float workspace of ws_bytes for split-K partial sums (used
+// when the output has too few tiles to occupy the chip, as at decode batch sizes).
 hipError_t gemm_nt(int dt, const void* A, int lda, const void* Wt, void* C, int ldc,
                    const void* R, int M, int N, int K, int epi, bool force_generic,
-                   hipStream_t s);
+                   hipStream_t s, float* ws = nullptr, size_t ws_bytes = 0);
 
 // out[t,:] = x[t,:] * rsqrt(mean(x[t,:]^2) + eps) * g
 hipError_t rmsnorm(int dt, const void* x, const void* g, void* out, int T, int H, float eps,

@@ -89,6 +89,24 @@ struct Job {
     Shard* sh;
     std::vector<SeqJob> seqs;
     hipEvent_t after = nullptr;
+    int64_t id = 0;            // 1-based issue order over both lanes
+    int64_t needs_out = 0;     // swap-in: number of swap-out jobs that must have completed first
+};
+
+// One mover lane: a host thread, a side stream, a two-slot pinned ring with its
+// device staging twin, and a metadata region.  Lane 0 carries swap-outs, lane 1
+// swap-ins, so that the two PCIe directions (and their host copies) overlap.
+struct Lane {
+    hipStream_t side = nullptr;
+    uint8_t* pinned = nullptr;
+    uint8_t* dev_staging = nullptr;
+    uint8_t* mv_meta_host = nullptr;
+    uint8_t* mv_meta_dev = nullptr;
+    hipEvent_t mv_ev[2] = {nullptr, nullptr};
+    std::thread worker;
+    std::deque<Job> jobs;
+    bool busy = false;
+    const Job* running = nullptr;
 };
 
 struct TierSlot {
@@ -109,10 +127,11 @@ struct ss_ctx {
     int dt = 0;
     size_t es = 2;
     bool force_generic = false;
+    int copy_threads = 4;
     std::string err;
     std::map<DescKey, Shard*> shards;
     float* d_rope = nullptr;
-    DevBuf ws_h, ws_qkv, ws_attn, ws_gu, ws_act, ws_x1, ws_scratch;
+    DevBuf ws_h, ws_qkv, ws_attn, ws_gu, ws_act, ws_x1, ws_scratch, ws_splitk;
     MetaSlot meta[4];
     int meta_next = 0;
     void *d_embed = nullptr, *d_gf = nullptr, *d_wlm_t = nullptr;
@@ -120,22 +139,19 @@ struct ss_ctx {
     size_t d_ids_cap = 0;
     // host tier
     uint8_t* tier = nullptr;
-    size_t tier_cap = 0, tier_top = 0;
+    size_t tier_cap = 0, tier_used = 0;
+    std::map<size_t, size_t> tier_free;          // offset -> length of every free block (coalesced)
     std::unordered_map<int64_t, TierSlot> tier_slots;
     // mover
-    hipStream_t side = nullptr;
-    uint8_t* pinned = nullptr;
-    uint8_t* dev_staging = nullptr;
-    size_t slot_bytes = 0;
-    uint8_t* mv_meta_host = nullptr;   // 2 slots
-    uint8_t* mv_meta_dev = nullptr;
-    size_t mv_meta_cap = 0;
-    hipEvent_t mv_ev[2] = {nullptr, nullptr};
-    std::thread worker;
-    std::mutex mu;
+    Lane lane[2];
+    size_t slot_bytes = 0;             // per lane: two slots of this size
+    size_t mv_meta_cap = 0;            // per lane
+    std::mutex mu;                     // guards the lanes' queues and the counters below
     std::condition_variable cv, cv_idle;
-    std::deque<Job> jobs;
-    bool busy = false, stop = false;
+    bool stop = false;
+    int64_t jobs_issued = 0, jobs_done = 0;      // jobs_done: all jobs with id <= jobs_done completed
+    std::vector<int64_t> done_ids;               // completed out of order, above jobs_done
+    int64_t out_issued = 0, out_done = 0;
     std::string worker_err;
     int worker_rc = 0;
     // profiling
@@ -468,6 +484,7 @@ int run_attn_phase(ss_ctx* c, Shard* s, int ll, const ss_batch* b, bool decode, 
         size_t fl = ssk::attn_decode_scratch_floats(ms->wk.n_items, s->nq_l, d);
         if ((rc = ensure_buf(c, c->ws_scratch, fl * sizeof(float)))) return rc;
     }
+    if (c->dt == SS_BF16 && T <= 2048 && (rc = ensure_buf(c, c->ws_splitk, (size_t)128 << 20))) return rc;
     const ssk::KvLayer kv = kv_layer(c, s, ll);
     {
         ProfScope ps(c, 4, st);
@@ -476,7 +493,7 @@ int run_attn_phase(ss_ctx* c, Shard* s, int ll, const ss_batch* b, bool decode, 
     {
         ProfScope ps(c, 0, st);
         K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, H, w.wqkv_t, c->ws_qkv.p, nqkv, nullptr, T, nqkv, H, ssk::EPI_STORE,
-                              c->force_generic, st));
+                              c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
     }
     {
         ProfScope ps(c, 4, st);
@@ -494,7 +511,7 @@ int run_attn_phase(ss_ctx* c, Shard* s, int ll, const ss_batch* b, bool decode, 
     {
         ProfScope ps(c, 0, st);
         K_TRY(c, ssk::gemm_nt(c->dt, c->ws_attn.p, s->nq_l * d, w.wo_t, out, H, residual ? x_in : nullptr, T, H,
-                              s->nq_l * d, residual ? ssk::EPI_RESIDUAL : ssk::EPI_STORE, c->force_generic, st));
+                              s->nq_l * d, residual ? ssk::EPI_RESIDUAL : ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
     }
     return mark_meta_used(c, ms, st);
 }
@@ -506,6 +523,7 @@ int run_mlp_phase(ss_ctx* c, Shard* s, int ll, int T, const void* x1, void* out,
     int rc;
     if ((rc = ensure_buf(c, c->ws_h, (size_t)T * H * c->es))) return rc;
     if ((rc = ensure_buf(c, c->ws_act, (size_t)T * F * c->es))) return rc;
+    if (c->dt == SS_BF16 && T <= 2048 && (rc = ensure_buf(c, c->ws_splitk, (size_t)128 << 20))) return rc;
     {
         ProfScope ps(c, 4, st);
         K_TRY(c, ssk::rmsnorm(c->dt, x1, w.g2, c->ws_h.p, T, H, m.rms_eps, st));
@@ -513,13 +531,13 @@ int run_mlp_phase(ss_ctx* c, Shard* s, int ll, int T, const void* x1, void* out,
     if (w.gu_interleaved) {
         ProfScope ps(c, 0, st);
         K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, H, w.wgu_t, c->ws_act.p, F, nullptr, T, 2 * F, H, ssk::EPI_SWIGLU,
-                              false, st));
+                              false, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
     } else {
         if ((rc = ensure_buf(c, c->ws_gu, (size_t)T * 2 * F * c->es))) return rc;
         {
             ProfScope ps(c, 0, st);
             K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, H, w.wgu_t, c->ws_gu.p, 2 * F, nullptr, T, 2 * F, H,
-                                  ssk::EPI_STORE, c->force_generic, st));
+                                  ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
         }
         ProfScope ps(c, 4, st);
         K_TRY(c, ssk::swiglu(c->dt, c->ws_gu.p, c->ws_act.p, T, F, st));
@@ -527,7 +545,7 @@ int run_mlp_phase(ss_ctx* c, Shard* s, int ll, int T, const void* x1, void* out,
     {
         ProfScope ps(c, 0, st);
         K_TRY(c, ssk::gemm_nt(c->dt, c->ws_act.p, F, w.wd_t, out, H, residual ? x1 : nullptr, T, H, F,
-                              residual ? ssk::EPI_RESIDUAL : ssk::EPI_STORE, c->force_generic, st));
+                              residual ? ssk::EPI_RESIDUAL : ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
     }
     return SS_OK;
 }
@@ -640,10 +658,10 @@ uint8_t* tier_run(ss_ctx* c, Shard* s, const SeqJob& sj, int ll, int kv) {
     return c->tier + sj.tier_off + elems * c->es;
 }
 
-int worker_job(ss_ctx* c, Job& job) {
+int worker_job(ss_ctx* c, Lane& L, Job& job) {
     Shard* s = job.sh;
     if (job.after) {
-        HIP_TRY(c, hipStreamWaitEvent(c->side, job.after, 0));
+        HIP_TRY(c, hipStreamWaitEvent(L.side, job.after, 0));
     }
     const std::vector<Unit> units = make_units(c, s, job.seqs);
     const size_t run_elems_bytes = c->es * c->m.head_dim;   // per token per head
@@ -657,18 +675,45 @@ int worker_job(ss_ctx* c, Job& job) {
         chunks.push_back({u, v});
         u = v;
     }
+    // Stage two (pinned <-> tier) is plain host memcpy; large chunks are split over a few helper
+    // threads so that one core's copy rate does not become the ceiling of the whole movement.
     auto host_copy = [&](size_t ci, bool to_tier) {
         const int slot = (int)(ci & 1);
-        uint8_t* p = c->pinned + (size_t)slot * c->slot_bytes;
+        struct Piece { uint8_t* tier; uint8_t* pin; size_t bytes; };
+        std::vector<Piece> pieces;
+        uint8_t* p = L.pinned + (size_t)slot * c->slot_bytes;
+        size_t total = 0;
         for (size_t u = chunks[ci].first; u < chunks[ci].second; ++u) {
             const SeqJob& sj = job.seqs[units[u].seq_idx];
             const size_t run = (size_t)s->nkv_l * sj.len * run_elems_bytes;
             for (int kv = 0; kv < 2; ++kv) {
-                uint8_t* t = tier_run(c, s, sj, units[u].ll, kv);
-                if (to_tier) memcpy(t, p, run); else memcpy(p, t, run);
+                pieces.push_back({tier_run(c, s, sj, units[u].ll, kv), p, run});
                 p += run;
+                total += run;
             }
         }
+        auto work = [&](size_t b, size_t e) {
+            for (size_t i = b; i < e; ++i) {
+                if (to_tier) memcpy(pieces[i].tier, pieces[i].pin, pieces[i].bytes);
+                else memcpy(pieces[i].pin, pieces[i].tier, pieces[i].bytes);
+            }
+        };
+        const int nth = (total >= ((size_t)8 << 20)) ? std::min<int>(c->copy_threads, (int)pieces.size()) : 1;
+        if (nth <= 1) { work(0, pieces.size()); return; }
+        std::vector<std::thread> th;
+        // contiguous ranges of pieces with roughly equal bytes
+        size_t begin = 0, acc = 0;
+        int made = 0;
+        for (size_t i = 0; i < pieces.size(); ++i) {
+            acc += pieces[i].bytes;
+            const bool last = i + 1 == pieces.size();
+            if (last || (acc >= total / nth * (made + 1) && made + 1 < nth)) {
+                th.emplace_back(work, begin, i + 1);
+                begin = i + 1;
+                ++made;
+            }
+        }
+        for (auto& t : th) t.join();
     };
     auto chunk_bytes = [&](size_t ci) {
         size_t b = 0;
@@ -678,51 +723,52 @@ int worker_job(ss_ctx* c, Job& job) {
     const size_t meta_half = c->mv_meta_cap / 2;
     for (size_t ci = 0; ci < chunks.size(); ++ci) {
         const int slot = (int)(ci & 1);
-        uint8_t* mh = c->mv_meta_host + slot * meta_half;
-        uint8_t* md = c->mv_meta_dev + slot * meta_half;
-        uint8_t* dst = c->dev_staging + (size_t)slot * c->slot_bytes;
-        uint8_t* pin = c->pinned + (size_t)slot * c->slot_bytes;
+        uint8_t* mh = L.mv_meta_host + slot * meta_half;
+        uint8_t* md = L.mv_meta_dev + slot * meta_half;
+        uint8_t* dst = L.dev_staging + (size_t)slot * c->slot_bytes;
+        uint8_t* pin = L.pinned + (size_t)slot * c->slot_bytes;
         ssk::RepackUnits ru{};
-        if (ci >= 2) HIP_TRY(c, hipEventSynchronize(c->mv_ev[slot]));   // slot's previous DMA and metadata are done
+        if (ci >= 2) HIP_TRY(c, hipEventSynchronize(L.mv_ev[slot]));   // slot's previous DMA and metadata are done
         const size_t mbytes = build_units(c, s, job.seqs, units, chunks[ci].first, chunks[ci].second, mh, md, meta_half, &ru);
         if (!mbytes) return fail(c, SS_ENOMEM, "KV mover metadata region too small");
         const size_t bytes = chunk_bytes(ci);
         if (job.dir == SS_OUT) {
-            HIP_TRY(c, hipMemcpyAsync(md, mh, mbytes, hipMemcpyHostToDevice, c->side));
+            HIP_TRY(c, hipMemcpyAsync(md, mh, mbytes, hipMemcpyHostToDevice, L.side));
             {
-                ProfScope ps(c, 3, c->side);
+                ProfScope ps(c, 3, L.side);
                 K_TRY(c, ssk::kv_gather(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru,
-                                        dst, c->side));
+                                        dst, L.side));
             }
-            HIP_TRY(c, hipMemcpyAsync(pin, dst, bytes, hipMemcpyDeviceToHost, c->side));
-            HIP_TRY(c, hipEventRecord(c->mv_ev[slot], c->side));
+            HIP_TRY(c, hipMemcpyAsync(pin, dst, bytes, hipMemcpyDeviceToHost, L.side));
+            HIP_TRY(c, hipEventRecord(L.mv_ev[slot], L.side));
             if (ci >= 1) {   // stage two of the previous chunk overlaps this chunk's gather + DMA
-                HIP_TRY(c, hipEventSynchronize(c->mv_ev[slot ^ 1]));
+                HIP_TRY(c, hipEventSynchronize(L.mv_ev[slot ^ 1]));
                 host_copy(ci - 1, true);
             }
         } else {
             host_copy(ci, false);   // overlaps the previous chunk's DMA + scatter
-            HIP_TRY(c, hipMemcpyAsync(md, mh, mbytes, hipMemcpyHostToDevice, c->side));
-            HIP_TRY(c, hipMemcpyAsync(dst, pin, bytes, hipMemcpyHostToDevice, c->side));
+            HIP_TRY(c, hipMemcpyAsync(md, mh, mbytes, hipMemcpyHostToDevice, L.side));
+            HIP_TRY(c, hipMemcpyAsync(dst, pin, bytes, hipMemcpyHostToDevice, L.side));
             {
-                ProfScope ps(c, 3, c->side);
+                ProfScope ps(c, 3, L.side);
                 K_TRY(c, ssk::kv_scatter(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size,
-                                         ru, dst, c->side));
+                                         ru, dst, L.side));
             }
-            HIP_TRY(c, hipEventRecord(c->mv_ev[slot], c->side));
+            HIP_TRY(c, hipEventRecord(L.mv_ev[slot], L.side));
         }
     }
     if (job.dir == SS_OUT && !chunks.empty()) {
         const size_t last = chunks.size() - 1;
-        HIP_TRY(c, hipEventSynchronize(c->mv_ev[last & 1]));
+        HIP_TRY(c, hipEventSynchronize(L.mv_ev[last & 1]));
         host_copy(last, true);
     } else {
-        HIP_TRY(c, hipStreamSynchronize(c->side));
+        HIP_TRY(c, hipStreamSynchronize(L.side));
     }
     return SS_OK;
 }
 
-void worker_main(ss_ctx* c) {
+void worker_main(ss_ctx* c, int li) {
+    Lane& L = c->lane[li];
     (void)hipSetDevice(c->rt.device);
     std::string local_err;
     tl_err = &local_err;
@@ -730,14 +776,19 @@ void worker_main(ss_ctx* c) {
         Job job;
         {
             std::unique_lock<std::mutex> lk(c->mu);
-            c->cv.wait(lk, [&] { return c->stop || !c->jobs.empty(); });
-            if (c->jobs.empty()) return;   // stop requested and queue drained
-            job = std::move(c->jobs.front());
-            c->jobs.pop_front();
-            c->busy = true;
+            // a swap-in starts only after the swap-outs issued before it have filled the tier
+            c->cv.wait(lk, [&] { return c->stop || (!L.jobs.empty() && c->out_done >= L.jobs.front().needs_out); });
+            if (L.jobs.empty()) return;                      // stop requested and queue drained
+            if (c->out_done < L.jobs.front().needs_out) {    // stopping: the other lane drains first
+                c->cv.wait(lk, [&] { return c->out_done >= L.jobs.front().needs_out; });
+            }
+            job = std::move(L.jobs.front());
+            L.jobs.pop_front();
+            L.busy = true;
+            L.running = &job;
         }
         local_err.clear();
-        const int rc = worker_job(c, job);
+        const int rc = worker_job(c, L, job);
         if (job.after) (void)hipEventDestroy(job.after);
         {
             std::lock_guard<std::mutex> lk(c->mu);
@@ -745,9 +796,23 @@ void worker_main(ss_ctx* c) {
                 c->worker_rc = rc;
                 c->worker_err = local_err;
             }
-            c->busy = false;
+            L.busy = false;
+            L.running = nullptr;
+            if (job.dir == SS_OUT) c->out_done++;
+            c->done_ids.push_back(job.id);
+            for (bool moved = true; moved;) {
+                moved = false;
+                for (size_t i = 0; i < c->done_ids.size(); ++i)
+                    if (c->done_ids[i] == c->jobs_done + 1) {
+                        c->jobs_done++;
+                        c->done_ids.erase(c->done_ids.begin() + i);
+                        moved = true;
+                        break;
+                    }
+            }
         }
         c->cv_idle.notify_all();
+        c->cv.notify_all();
     }
 }
 
@@ -760,7 +825,9 @@ namespace {
 
 void wait_idle(ss_ctx* c) {
     std::unique_lock<std::mutex> lk(c->mu);
-    c->cv_idle.wait(lk, [&] { return c->jobs.empty() && !c->busy; });
+    c->cv_idle.wait(lk, [&] {
+        return c->lane[0].jobs.empty() && !c->lane[0].busy && c->lane[1].jobs.empty() && !c->lane[1].busy;
+    });
 }
 
 int upload_matrix(ss_ctx* c, const void* src, int location, size_t bytes, void** tmp_out, const void** dev_src) {
@@ -799,14 +866,70 @@ int enqueue_job(ss_ctx* c, Job&& job, hipStream_t stream) {
     HIP_TRY(c, hipEventRecord(job.after, stream));
     {
         std::lock_guard<std::mutex> lk(c->mu);
-        c->jobs.push_back(std::move(job));
+        job.id = ++c->jobs_issued;
+        if (job.dir == SS_OUT) c->out_issued++;
+        else job.needs_out = c->out_issued;
+        c->lane[job.dir == SS_OUT ? 0 : 1].jobs.push_back(std::move(job));
     }
-    c->cv.notify_one();
+    c->cv.notify_all();
     return SS_OK;
+}
+
+// Blocks until no queued or running mover job touches any of the listed sequences
+// (of shard `sh`, or of any shard when sh is null).
+void wait_seqs_idle(ss_ctx* c, const Shard* sh, const int64_t* ids, int n) {
+    std::unique_lock<std::mutex> lk(c->mu);
+    auto touches = [&](const Job& j) {
+        if (sh && j.sh != sh) return false;
+        for (const SeqJob& sj : j.seqs)
+            for (int i = 0; i < n; ++i)
+                if (sj.seq == ids[i]) return true;
+        return false;
+    };
+    c->cv_idle.wait(lk, [&] {
+        for (const Lane& L : c->lane) {
+            if (L.running && touches(*L.running)) return false;
+            for (const Job& j : L.jobs)
+                if (touches(j)) return false;
+        }
+        return true;
+    });
 }
 
 size_t seq_tier_bytes(ss_ctx* c, int32_t len) {
     return (size_t)c->m.n_layers * 2 * c->m.n_kv_heads * (size_t)len * c->m.head_dim * c->es;
+}
+
+// Host tier slots: first fit at the lowest address; freed blocks merge with their
+// neighbours, so an empty tier is one block again and allocation restarts at 0.
+bool tier_alloc(ss_ctx* c, size_t bytes, size_t* off) {
+    for (auto it = c->tier_free.begin(); it != c->tier_free.end(); ++it) {
+        if (it->second < bytes) continue;
+        *off = it->first;
+        const size_t rest = it->second - bytes;
+        c->tier_free.erase(it);
+        if (rest) c->tier_free[*off + bytes] = rest;
+        c->tier_used += bytes;
+        return true;
+    }
+    return false;
+}
+
+void tier_release(ss_ctx* c, size_t off, size_t bytes) {
+    auto it = c->tier_free.emplace(off, bytes).first;
+    auto nx = std::next(it);
+    if (nx != c->tier_free.end() && it->first + it->second == nx->first) {
+        it->second += nx->second;
+        c->tier_free.erase(nx);
+    }
+    if (it != c->tier_free.begin()) {
+        auto pv = std::prev(it);
+        if (pv->first + pv->second == it->first) {
+            pv->second += it->second;
+            c->tier_free.erase(it);
+        }
+    }
+    c->tier_used -= bytes;
 }
 
 }  // namespace
@@ -832,6 +955,7 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
     c->es = m.dtype == SS_F32 ? 4 : 2;
     const char* fg = getenv("SS_FORCE_GENERIC");
     c->force_generic = fg && fg[0] == '1';
+    if (const char* ct = getenv("SS_COPY_THREADS")) c->copy_threads = std::max(1, std::min(16, atoi(ct)));
     int rc = SS_OK;
     auto boot = [&]() -> int {
         // rotary table: cos/sin of p * base^(-2i/d), evaluated in double, stored as float pairs
@@ -849,22 +973,25 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
             c->tier = (uint8_t*)malloc((size_t)rt->host_tier_bytes);
             if (!c->tier) return fail(c, SS_ENOMEM, "host tier allocation failed");
             c->tier_cap = (size_t)rt->host_tier_bytes;
+            c->tier_free[0] = c->tier_cap;
         }
-        c->slot_bytes = ((size_t)rt->pinned_bytes / 2) & ~(size_t)255;
-        if (c->slot_bytes) {
-            HIP_TRY(c, hipHostMalloc((void**)&c->pinned, 2 * c->slot_bytes, hipHostMallocDefault));
-            HIP_TRY(c, hipMalloc((void**)&c->dev_staging, 2 * c->slot_bytes));
-        }
+        c->slot_bytes = ((size_t)rt->pinned_bytes / 4) & ~(size_t)255;
         c->mv_meta_cap = 16u << 20;
-        HIP_TRY(c, hipHostMalloc((void**)&c->mv_meta_host, c->mv_meta_cap, hipHostMallocDefault));
-        HIP_TRY(c, hipMalloc((void**)&c->mv_meta_dev, c->mv_meta_cap));
-        HIP_TRY(c, hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
-        for (int i = 0; i < 2; ++i) HIP_TRY(c, hipEventCreateWithFlags(&c->mv_ev[i], hipEventDisableTiming));
+        for (Lane& L : c->lane) {
+            if (c->slot_bytes) {
+                HIP_TRY(c, hipHostMalloc((void**)&L.pinned, 2 * c->slot_bytes, hipHostMallocDefault));
+                HIP_TRY(c, hipMalloc((void**)&L.dev_staging, 2 * c->slot_bytes));
+            }
+            HIP_TRY(c, hipHostMalloc((void**)&L.mv_meta_host, c->mv_meta_cap, hipHostMallocDefault));
+            HIP_TRY(c, hipMalloc((void**)&L.mv_meta_dev, c->mv_meta_cap));
+            HIP_TRY(c, hipStreamCreateWithFlags(&L.side, hipStreamNonBlocking));
+            for (int i = 0; i < 2; ++i) HIP_TRY(c, hipEventCreateWithFlags(&L.mv_ev[i], hipEventDisableTiming));
+        }
         return SS_OK;
     };
     rc = boot();
     if (rc) { fprintf(stderr, "ss_create: %s\n", c->err.c_str()); delete c; return rc; }
-    c->worker = std::thread(worker_main, c);
+    for (int li = 0; li < 2; ++li) c->lane[li].worker = std::thread(worker_main, c, li);
     *out = c;
     return SS_OK;
 }
@@ -876,7 +1003,8 @@ int ss_destroy(ss_ctx* c) {
         c->stop = true;
     }
     c->cv.notify_all();
-    if (c->worker.joinable()) c->worker.join();
+    for (Lane& L : c->lane)
+        if (L.worker.joinable()) L.worker.join();
     (void)hipSetDevice(c->rt.device);
     (void)hipDeviceSynchronize();
     for (auto& kv : c->shards) {
@@ -891,20 +1019,23 @@ int ss_destroy(ss_ctx* c) {
         if (s->d_v_pools) (void)hipFree(s->d_v_pools);
         delete s;
     }
-    for (DevBuf* b : {&c->ws_h, &c->ws_qkv, &c->ws_attn, &c->ws_gu, &c->ws_act, &c->ws_x1, &c->ws_scratch})
+    for (DevBuf* b : {&c->ws_h, &c->ws_qkv, &c->ws_attn, &c->ws_gu, &c->ws_act, &c->ws_x1, &c->ws_scratch, &c->ws_splitk})
         if (b->p) (void)hipFree(b->p);
     for (auto& ms : c->meta) {
         if (ms.host) (void)hipHostFree(ms.host);
         if (ms.dev) (void)hipFree(ms.dev);
         if (ms.done) (void)hipEventDestroy(ms.done);
     }
-    for (void* p : {(void*)c->d_rope, c->d_embed, c->d_gf, c->d_wlm_t, (void*)c->d_ids, (void*)c->dev_staging,
-                    (void*)c->mv_meta_dev})
+    for (Lane& L : c->lane) {
+        if (L.dev_staging) (void)hipFree(L.dev_staging);
+        if (L.mv_meta_dev) (void)hipFree(L.mv_meta_dev);
+        if (L.pinned) (void)hipHostFree(L.pinned);
+        if (L.mv_meta_host) (void)hipHostFree(L.mv_meta_host);
+        for (int i = 0; i < 2; ++i) if (L.mv_ev[i]) (void)hipEventDestroy(L.mv_ev[i]);
+        if (L.side) (void)hipStreamDestroy(L.side);
+    }
+    for (void* p : {(void*)c->d_rope, c->d_embed, c->d_gf, c->d_wlm_t, (void*)c->d_ids})
         if (p) (void)hipFree(p);
-    if (c->pinned) (void)hipHostFree(c->pinned);
-    if (c->mv_meta_host) (void)hipHostFree(c->mv_meta_host);
-    for (int i = 0; i < 2; ++i) if (c->mv_ev[i]) (void)hipEventDestroy(c->mv_ev[i]);
-    if (c->side) (void)hipStreamDestroy(c->side);
     for (auto& r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     free(c->tier);
     delete c;
@@ -982,26 +1113,35 @@ int ss_kv_swap(ss_ctx* c, const ss_shard_desc* d, int dir, const int64_t* seq_id
     job.dir = dir;
     job.sh = s;
     if (dir == SS_OUT) {
-        size_t need = 0;
         for (int i = 0; i < n; ++i) {
             auto it = s->seqs.find(seq_ids[i]);
             if (it == s->seqs.end()) return fail(c, SS_ENOENT, "sequence %lld not resident in this shard", (long long)seq_ids[i]);
             auto ts = c->tier_slots.find(seq_ids[i]);
-            if (ts == c->tier_slots.end()) need += seq_tier_bytes(c, it->second.len);
-            else if (ts->second.len != it->second.len)
+            if (ts != c->tier_slots.end() && ts->second.len != it->second.len)
                 return fail(c, SS_EINVAL, "sequence %lld is in the tier with length %d, shard holds %d",
                             (long long)seq_ids[i], ts->second.len, it->second.len);
         }
-        if (c->tier_top + need > c->tier_cap)
-            return fail(c, SS_ENOMEM, "host tier full: need %zu more bytes, %zu free", need, c->tier_cap - c->tier_top);
+        std::vector<int64_t> placed;
         for (int i = 0; i < n; ++i) {
             const SeqState& st = s->seqs[seq_ids[i]];
             auto ts = c->tier_slots.find(seq_ids[i]);
             if (ts == c->tier_slots.end()) {
-                ts = c->tier_slots.emplace(seq_ids[i], TierSlot{c->tier_top, st.len}).first;
-                c->tier_top += seq_tier_bytes(c, st.len);
+                size_t off = 0;
+                if (!tier_alloc(c, seq_tier_bytes(c, st.len), &off)) {
+                    for (int64_t id : placed) {     // all or nothing
+                        tier_release(c, c->tier_slots[id].off, seq_tier_bytes(c, c->tier_slots[id].len));
+                        c->tier_slots.erase(id);
+                    }
+                    return fail(c, SS_ENOMEM, "host tier full: sequence %lld needs %zu bytes, %zu in use of %zu",
+                                (long long)seq_ids[i], seq_tier_bytes(c, st.len), c->tier_used, c->tier_cap);
+                }
+                ts = c->tier_slots.emplace(seq_ids[i], TierSlot{off, st.len}).first;
+                placed.push_back(seq_ids[i]);
             }
-            job.seqs.push_back({seq_ids[i], st.len, st.pages, ts->second.off});
+        }
+        for (int i = 0; i < n; ++i) {
+            const SeqState& st = s->seqs[seq_ids[i]];
+            job.seqs.push_back({seq_ids[i], st.len, st.pages, c->tier_slots[seq_ids[i]].off});
         }
     } else {
         for (int i = 0; i < n; ++i) {
@@ -1030,8 +1170,28 @@ int ss_kv_reshard(ss_ctx* c, const ss_shard_desc* from, const ss_shard_desc* to,
 int ss_sync(ss_ctx* c) {
     if (!c) return SS_EINVAL;
     wait_idle(c);
-    HIP_TRY(c, hipStreamSynchronize(c->side));
+    for (Lane& L : c->lane) HIP_TRY(c, hipStreamSynchronize(L.side));
     std::lock_guard<std::mutex> lk(c->mu);
+    if (c->worker_rc) {
+        const int rc = c->worker_rc;
+        c->err = "KV mover: " + c->worker_err;
+        c->worker_rc = 0;
+        c->worker_err.clear();
+        return rc;
+    }
+    return SS_OK;
+}
+
+int64_t ss_kv_jobs_issued(ss_ctx* c) {
+    if (!c) return SS_EINVAL;
+    std::lock_guard<std::mutex> lk(c->mu);
+    return c->jobs_issued;
+}
+
+int ss_kv_wait(ss_ctx* c, int64_t n_jobs) {
+    if (!c) return SS_EINVAL;
+    std::unique_lock<std::mutex> lk(c->mu);
+    c->cv_idle.wait(lk, [&] { return c->jobs_done >= n_jobs || c->jobs_done >= c->jobs_issued; });
     if (c->worker_rc) {
         const int rc = c->worker_rc;
         c->err = "KV mover: " + c->worker_err;
@@ -1047,7 +1207,7 @@ int ss_kv_free(ss_ctx* c, const ss_shard_desc* d, const int64_t* seq_ids, int n)
     Shard* s = nullptr;
     int rc = get_shard(c, d, &s);
     if (rc) return rc;
-    wait_idle(c);
+    wait_seqs_idle(c, s, seq_ids, n);
     for (int i = 0; i < n; ++i)
         if (!s->seqs.count(seq_ids[i])) return fail(c, SS_ENOENT, "sequence %lld not resident", (long long)seq_ids[i]);
     for (int i = 0; i < n; ++i) {
@@ -1062,11 +1222,15 @@ int ss_kv_free(ss_ctx* c, const ss_shard_desc* d, const int64_t* seq_ids, int n)
 
 int ss_host_tier_release(ss_ctx* c, const int64_t* seq_ids, int n) {
     if (!c) return SS_EINVAL;
-    wait_idle(c);
+    wait_seqs_idle(c, nullptr, seq_ids, n);
     for (int i = 0; i < n; ++i)
         if (!c->tier_slots.count(seq_ids[i])) return fail(c, SS_ENOENT, "sequence %lld not in the host tier", (long long)seq_ids[i]);
-    for (int i = 0; i < n; ++i) c->tier_slots.erase(seq_ids[i]);
-    if (c->tier_slots.empty()) c->tier_top = 0;
+    for (int i = 0; i < n; ++i) {
+        auto it = c->tier_slots.find(seq_ids[i]);
+        if (it == c->tier_slots.end()) continue;   // listed twice
+        tier_release(c, it->second.off, seq_tier_bytes(c, it->second.len));
+        c->tier_slots.erase(it);
+    }
     return SS_OK;
 }
 
@@ -1105,7 +1269,7 @@ static int xfer_dev(ss_ctx* c, const ss_shard_desc* d, const int64_t* seq_ids, c
     std::vector<uint8_t> img(c->mv_meta_cap / 2);
     static_assert(sizeof(size_t) == 8, "64-bit only");
     wait_idle(c);   // shares the mover's device metadata region (second half)
-    uint8_t* md = c->mv_meta_dev;
+    uint8_t* md = c->lane[0].mv_meta_dev;
     size_t stage_off = 0;
     for (size_t u0 = 0; u0 < units.size(); u0 += 32768) {
         const size_t u1 = std::min(units.size(), u0 + 32768);
@@ -1175,9 +1339,9 @@ int ss_kv_read(ss_ctx* c, const ss_shard_desc* d, int64_t seq, int layer, void* 
     std::vector<Unit> units{{0, layer - d->layer_begin, (size_t)2 * s->nkv_l * it->second.len * c->m.head_dim * c->es}};
     std::vector<uint8_t> img(1 << 20);
     ssk::RepackUnits ru{};
-    const size_t mbytes = build_units(c, s, seqs, units, 0, 1, img.data(), c->mv_meta_dev, img.size(), &ru);
+    const size_t mbytes = build_units(c, s, seqs, units, 0, 1, img.data(), c->lane[0].mv_meta_dev, img.size(), &ru);
     if (!mbytes) return fail(c, SS_ENOMEM, "sequence too long for the inspection path");
-    HIP_TRY(c, hipMemcpy(c->mv_meta_dev, img.data(), mbytes, hipMemcpyHostToDevice));
+    HIP_TRY(c, hipMemcpy(c->lane[0].mv_meta_dev, img.data(), mbytes, hipMemcpyHostToDevice));
     void* tmp = nullptr;
     HIP_TRY(c, hipMalloc(&tmp, units[0].bytes));
     hipError_t e = ssk::kv_gather(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru, tmp, 0);
@@ -1198,7 +1362,7 @@ int ss_host_tier_read(ss_ctx* c, int64_t seq, int layer, void* host_out) {
     return SS_OK;
 }
 
-int64_t ss_host_tier_used_bytes(ss_ctx* c) { return c ? (int64_t)c->tier_top : -1; }
+int64_t ss_host_tier_used_bytes(ss_ctx* c) { return c ? (int64_t)c->tier_used : -1; }
 
 int64_t ss_kv_free_pages(ss_ctx* c, const ss_shard_desc* d) {
     if (!c) return SS_EINVAL;

@@ -399,11 +399,17 @@ def test_tier_allocator_full_and_empty_cycle():
     t = kt.TierAllocator(100)
     assert t.place(5, 40) == 0 and t.place(6, 50) == 40 and t.place(5, 40) == 0
     with pytest.raises(MemoryError):
-        t.place(7, 20)
+        t.place(7, 20)                        # 10 free: full
     t.release(5)
-    assert t.top == 90                        # no compaction while sequences are live
+    assert t.used == 50 and t.free == [(0, 40), (90, 10)]
+    assert t.place(9, 30) == 0                # first fit, lowest address
+    with pytest.raises(MemoryError):
+        t.place(10, 15)                       # holes of 10 and 10 do not add up
+    assert t.place(11, 10) == 30
     t.release(6)
-    assert t.top == 0 and t.place(8, 100) == 0
+    t.release(9)
+    t.release(11)
+    assert t.used == 0 and t.free == [(0, 100)] and t.place(8, 100) == 0   # empty again: restart at 0
 
 
 def test_reshard_pp_to_tp_union_is_identity():
