@@ -102,8 +102,9 @@ def main():
     Tp, B = sum(p_lens), len(d_lens)
     kv_tok_bytes = 2 * cfg.n_kv_heads * cfg.head_dim * 2          # K and V, bf16, per token per layer
     decode_tokens = sum(d_lens)
-    pages = sum(-(-(n + 1) // 16) for n in d_lens) + 2 * sum(-(-n // 16) for n in p_lens) + 64
-    tier_bytes = 2 * Tp * kv_tok_bytes * cfg.n_layers + (1 << 20)
+    N_SETS = 3
+    pages = sum(-(-(n + 1) // 16) for n in d_lens) + N_SETS * sum(-(-n // 16) for n in p_lens) + 64
+    tier_bytes = N_SETS * Tp * kv_tok_bytes * cfg.n_layers + (1 << 20)
     ctx = hz.make_context(cfg, pages=pages, tier_bytes=tier_bytes, pinned_bytes=256 << 20, max_seq_len=4096)
     vals, raws = wl.make_layer_weights(cfg, 2001)
     pp = hz.pp_desc(cfg)
@@ -122,11 +123,13 @@ def main():
     ctx.kv_import_dev(tp, d_ids, d_lens, stg)
     torch.cuda.synchronize()
     del stg
-    # Two alternating id sets for the prefill batch: the re-shard of batch i (swap-out, host tier,
-    # swap-in) runs on the side stream and the mover thread while batch i+1 is prefilled, as the
-    # KV of a prefilled batch is not needed until its decode begins (paper section 5.2).
-    id_sets = [list(range(16)), list(range(16, 32))]
-    tickets = [None, None]
+    # Alternating id sets for the prefill batch: the re-shard of batch i (swap-out, host tier, swap-in)
+    # runs on the side streams and the mover threads while the following batches are prefilled, as the
+    # KV of a prefilled batch is not needed until its decode begins (paper section 5.2).  The swap-out
+    # is requested as soon as the attention half of the layer has written the cache.
+    id_sets = [list(range(16 * j, 16 * j + 16)) for j in range(N_SETS)]
+    tickets = [None] * N_SETS
+    x1_p = torch.empty_like(x_p)
     p_ids = id_sets[0]
     zeros = [0] * len(p_ids)
     stream = torch.cuda.current_stream().cuda_stream
@@ -140,14 +143,16 @@ def main():
             tickets[s] = None
 
     def step(i, reshard=True):
-        s = i % 2
+        s = i % N_SETS
         ids = id_sets[s]
         if reshard:
             retire(s)
-        ctx.layer_prefill(pp, 0, ss.SS_BOTH, ids, p_lens, zeros, x_p, y_p, stream)
-        if reshard:
+            ctx.layer_prefill(pp, 0, ss.SS_ATTN, ids, p_lens, zeros, x_p, x1_p, stream)
             ctx.kv_reshard(pp, tp, ids, stream)
             tickets[s] = ctx.kv_jobs_issued()
+            ctx.layer_prefill(pp, 0, ss.SS_MLP, ids, p_lens, zeros, x1_p, y_p, stream)
+        else:
+            ctx.layer_prefill(pp, 0, ss.SS_BOTH, ids, p_lens, zeros, x_p, y_p, stream)
         ctx.layer_decode(tp, 0, ss.SS_BOTH, d_ids, d_lens, x_d, y_d, stream)
         if not reshard:
             ctx.kv_free(pp, ids)
@@ -163,8 +168,8 @@ def main():
     torch.cuda.synchronize()
     ctx.sync()                      # every re-shard issued in the timed region has completed
     elapsed = time.perf_counter() - t0
-    retire(0)
-    retire(1)
+    for j in range(N_SETS):
+        retire(j)
     ms_per_step = elapsed * 1e3 / args.steps
     value = (Tp + B) * args.steps / elapsed
 

@@ -417,6 +417,201 @@ __global__ __launch_bounds__(512) void gemm_mfma_dma_kernel(const bf16_t* __rest
     }
 }
 
+
+// Same ring, four waves (2 x 2), wave tile 128 x 128: every fragment read from LDS feeds four MFMAs
+// instead of two or four (8 fragment reads per 16 MFMAs, against 6 per 8 above), which takes a third
+// off the LDS read traffic that competes with the incoming DMA writes.  One wave per SIMD, 256
+// accumulator registers per lane.
+template <int V> struct VmcntImm { static constexpr int value = (V & 15) | ((V >> 4) << 14) | 0x0F70; };
+
+template <int EPI, int NS>
+__global__ __launch_bounds__(256) void gemm_mfma_dma4_kernel(const bf16_t* __restrict__ A, int lda,
+                                                             const bf16_t* __restrict__ Wt, bf16_t* __restrict__ C,
+                                                             int ldc, const bf16_t* __restrict__ R, int M, int N, int K,
+                                                             int tiles_m, int tiles_n, int per_xcd) {
+    constexpr int BM = 256, BN = 256, TM = 4, TN = 4;
+    constexpr int STAGE = (BM + BN) * 64;
+    constexpr int LPS = 8;                       // DMA loads per wave per stage
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    const int xcd = blockIdx.x & 7;
+    const int logical = xcd * per_xcd + (blockIdx.x >> 3);
+    if ((blockIdx.x >> 3) >= per_xcd || logical >= tiles_m * tiles_n) return;
+    constexpr int GM = 8;
+    const int group_size = GM * tiles_n;
+    const int group = logical / group_size;
+    const int first_m = group * GM;
+    const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+    const int in_group = logical - group * group_size;
+    const int m0 = (first_m + in_group % gm) * BM, n0 = (in_group / gm) * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
+
+    // waves 0-1 bring A rows [128w, 128w+128), waves 2-3 bring Wt rows [128(w-2), ...)
+    const bool isA = wave < 2;
+    const int row_base = (wave & 1) * 128;
+    const uint8_t* src[LPS];
+#pragma unroll
+    for (int i = 0; i < LPS; ++i) {
+        const int row = row_base + i * 16 + (lane >> 2);
+        const int kc = (lane & 3) ^ (((row >> 1) & 3) ^ ((row >> 3) & 1));
+        if (isA) {
+            int gr = m0 + row;
+            gr = gr < M ? gr : M - 1;
+            src[i] = reinterpret_cast<const uint8_t*>(A + (size_t)gr * lda + kc * 8);
+        } else {
+            int gr = n0 + row;
+            gr = gr < N ? gr : N - 1;
+            src[i] = reinterpret_cast<const uint8_t*>(Wt + (size_t)gr * K + kc * 8);
+        }
+    }
+    const uint32_t dst0 = lds_base + (isA ? 0 : BM * 64) + row_base * 64;
+    const int nk = K / 32;
+    auto issue1 = [&](int slice, int i) {
+        const int sl = slice < nk ? slice : nk - 1;
+        const uint32_t d = dst0 + (uint32_t)(slice % NS) * STAGE;
+        dma16(src[i] + (size_t)sl * 64, d + i * 1024);
+    };
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int lrow = lane & 31, lgrp = lane >> 5;
+    int a_off[TM][2], b_off[TN][2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a_off[i][ks] = lds64_off(wm * 128 + i * 32 + lrow, ks * 2 + lgrp);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b_off[j][ks] = BM * 64 + lds64_off(wn * 128 + j * 32 + lrow, ks * 2 + lgrp);
+    }
+    bf16x8_t af[2][TM], bfr[2][TN];
+    auto read_frags = [&](const uint8_t* st, int ks) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) af[ks][i] = *reinterpret_cast<const bf16x8_t*>(st + a_off[i][ks]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) bfr[ks][j] = *reinterpret_cast<const bf16x8_t*>(st + b_off[j][ks]);
+    };
+    auto mfma_row = [&](int ks, int i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
+    };
+
+    // same pipeline as the eight-wave kernel ([A] / [B] / [C] per slice), 8 loads per wave per slice
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+#pragma unroll
+        for (int i = 0; i < LPS; ++i) issue1(s, i);
+    __builtin_amdgcn_s_waitcnt(VmcntImm<LPS * (NS - 2)>::value);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) issue1(NS - 1, i);
+    read_frags(smem, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+        const uint8_t* st = smem + (kt % NS) * STAGE;
+        const uint8_t* stn = smem + ((kt + 1) % NS) * STAGE;
+        read_frags(st, 1);                                   // [A]
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            mfma_row(0, q);
+            __builtin_amdgcn_sched_barrier(0);
+            issue1(kt + NS - 1, 4 + q);
+        }
+        __builtin_amdgcn_s_waitcnt(VmcntImm<LPS * (NS - 2)>::value);   // [B]
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(stn, 0);                                  // [C]
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            issue1(kt + NS, q);
+            mfma_row(1, q);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+
+    const int col_in = lane & 31;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int rbase = m0 + wm * 128 + i * 32 + 4 * lgrp;
+        if (EPI == EPI_SWIGLU) {
+#pragma unroll
+            for (int j = 0; j < TN; j += 2) {
+                const int nb = n0 + wn * 128 + j * 32;
+                const int oc = (nb >> 1) + col_in;
+                if (nb + col_in >= N) continue;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = rbase + 8 * (v >> 2) + (v & 3);
+                    if (r >= M) continue;
+                    const float g = acc[i][j][v], u = acc[i][j + 1][v];
+                    C[(size_t)r * ldc + oc] = f2bf(g / (1.0f + __expf(-g)) * u);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int c = n0 + wn * 128 + j * 32 + col_in;
+                if (c >= N) continue;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = rbase + 8 * (v >> 2) + (v & 3);
+                    if (r >= M) continue;
+                    float o = acc[i][j][v];
+                    if (EPI == EPI_RESIDUAL) o += bf2f(R[(size_t)r * ldc + c]);
+                    C[(size_t)r * ldc + c] = f2bf(o);
+                }
+            }
+        }
+    }
+}
+
+template <int NS>
+static hipError_t launch_dma4(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
+                              int N, int K, int epi, hipStream_t s) {
+    constexpr size_t LDS = (size_t)NS * 512 * 64;
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    const long long n_tiles = (long long)tiles_m * tiles_n;
+    if (n_tiles > (1ll << 30) || K % 32 != 0) return hipErrorInvalidValue;
+    const int per_xcd = (int)((n_tiles + 7) / 8);
+    const unsigned grid = (unsigned)per_xcd * 8;
+#define SS_LAUNCH(E)                                                                                            \
+    {                                                                                                           \
+        auto kfn = gemm_mfma_dma4_kernel<E, NS>;                                                                \
+        static bool attr_set = false;                                                                           \
+        if (!attr_set) {                                                                                        \
+            hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS); \
+            if (e != hipSuccess) return e;                                                                      \
+            attr_set = true;                                                                                    \
+        }                                                                                                       \
+        kfn<<<grid, 256, LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd);                  \
+    }
+    switch (epi) {
+        case EPI_STORE: SS_LAUNCH(EPI_STORE) break;
+        case EPI_RESIDUAL:
+            if (!R) return hipErrorInvalidValue;
+            SS_LAUNCH(EPI_RESIDUAL) break;
+        case EPI_SWIGLU: SS_LAUNCH(EPI_SWIGLU) break;
+        default: return hipErrorInvalidValue;
+    }
+#undef SS_LAUNCH
+    return hipGetLastError();
+}
+
 template <int NS, int PROBE = 0>
 static hipError_t launch_dma(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
                              int N, int K, int epi, hipStream_t s) {
@@ -569,6 +764,8 @@ hipError_t gemm_mfma_bf16_cfg(int cfg, const void* A, int lda, const void* Wt, v
         case 8: return launch_dma<4, 3>(a, lda, w, c, ldc, r, M, N, K, epi, s);
         case 9: return launch_dma<4, 4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
         case 10: return launch_dma<4, 8>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        case 11: return launch_dma4<4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        case 12: return launch_dma4<3>(a, lda, w, c, ldc, r, M, N, K, epi, s);
         default: return hipErrorInvalidValue;
     }
 }

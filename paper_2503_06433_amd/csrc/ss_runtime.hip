@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <condition_variable>
 #include <cmath>
 #include <cstdarg>
@@ -128,6 +129,7 @@ struct ss_ctx {
     size_t es = 2;
     bool force_generic = false;
     int copy_threads = 4;
+    bool trace_mover = false;
     std::string err;
     std::map<DescKey, Shard*> shards;
     float* d_rope = nullptr;
@@ -788,7 +790,16 @@ void worker_main(ss_ctx* c, int li) {
             L.running = &job;
         }
         local_err.clear();
+        const auto t_job0 = std::chrono::steady_clock::now();
         const int rc = worker_job(c, L, job);
+        if (c->trace_mover) {
+            const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t_job0).count();
+            size_t bytes = 0;
+            for (const SeqJob& sj : job.seqs)
+                bytes += (size_t)2 * job.sh->nkv_l * sj.len * c->m.head_dim * c->es * job.sh->n_layers_l;
+            fprintf(stderr, "[mover] job %lld %s: %.2f ms, %.1f MB, %.1f GB/s\n", (long long)job.id,
+                    job.dir == SS_OUT ? "out" : "in", ms, bytes / 1e6, bytes / ms / 1e6);
+        }
         if (job.after) (void)hipEventDestroy(job.after);
         {
             std::lock_guard<std::mutex> lk(c->mu);
@@ -955,6 +966,7 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
     c->es = m.dtype == SS_F32 ? 4 : 2;
     const char* fg = getenv("SS_FORCE_GENERIC");
     c->force_generic = fg && fg[0] == '1';
+    c->trace_mover = getenv("SS_TRACE_MOVER") != nullptr;
     if (const char* ct = getenv("SS_COPY_THREADS")) c->copy_threads = std::max(1, std::min(16, atoi(ct)));
     int rc = SS_OK;
     auto boot = [&]() -> int {
