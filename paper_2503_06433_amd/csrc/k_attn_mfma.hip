@@ -5,7 +5,7 @@
 // so that the accumulator of the first product is already in the register
 // layout the second product wants for its B operand (each lane owns one query
 // column and a run of tokens): P never travels through LDS or across lanes.
-// K pages are [head][16][D] and V pages are stored transposed, [head][D][16],
+// K pages are [head][16][D] and V pages are stored transposed, [head][D][16] (token order 0-3, 8-11, 4-7, 12-15),
 // so both MFMA A operands are plain vector loads straight from the pages.
 //
 // The contraction order inside one MFMA is free as long as both operands agree:
@@ -34,12 +34,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
 }
 
 // ======================================================================
-// Prefill.  Block = 4 waves = 128 consecutive queries of one (sequence, q head);
-// each wave owns 32 queries and walks the pages its queries can see, two pages
-// (32 tokens) per step, with v_mfma_f32_32x32x16_bf16:
+// Prefill.  Block = 4 waves = 256 consecutive queries of one (sequence, q head);
+// each wave owns QT = 2 tiles of 32 queries and walks the pages its queries can
+// see, two pages (32 tokens) per step, with v_mfma_f32_32x32x16_bf16:
 //   accumulator register v of lane l <-> token 8*(v/4) + 4*(l/32) + v%4, query l%32.
+// Every K and V^T fragment loaded from the pages feeds both query tiles.
 // ======================================================================
-template <int D>
+template <int D, int QT>
 __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const bf16_t* __restrict__ qkv,
                                                                 bf16_t* __restrict__ out, int n_q, int n_kv,
                                                                 BatchMeta bm, const bf16_t* __restrict__ k_pool,
@@ -50,30 +51,38 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const bf16_t* __
     const int sq = blockIdx.z, a = blockIdx.y;
     const int q_begin = bm.cu_q[sq], q_len = bm.cu_q[sq + 1] - q_begin;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int q0 = blockIdx.x * 128 + wave * 32;
+    const int q0 = blockIdx.x * (128 * QT) + wave * (32 * QT);
     if (q0 >= q_len) return;
     const int before = bm.kv_before[sq];
     const int g = a / (n_q / n_kv);
     const int lq = lane & 31, g2 = lane >> 5;
-    const int qi = q0 + lq;
-    const bool valid = qi < q_len;
-    const int p = before + (valid ? qi : 0);
-    const int last_q = (q0 + 31 < q_len) ? q0 + 31 : q_len - 1;
+    const int last_q = (q0 + 32 * QT - 1 < q_len) ? q0 + 32 * QT - 1 : q_len - 1;
     const int n_pages = (before + last_q) / 16 + 1;
     const size_t row_stride = (size_t)(n_q + 2 * n_kv) * D;
 
-    Frag qf[KS];
-    {
-        const bf16_t* qp = qkv + (size_t)(q_begin + (valid ? qi : 0)) * row_stride + (size_t)a * D + g2 * 8;
+    Frag qf[QT][KS];
+    int p[QT];
+    bool valid[QT];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks].q = *reinterpret_cast<const vec16*>(qp + ks * 16);
+    for (int t = 0; t < QT; ++t) {
+        const int qi = q0 + t * 32 + lq;
+        valid[t] = qi < q_len;
+        p[t] = before + (valid[t] ? qi : 0);
+        const bf16_t* qp = qkv + (size_t)(q_begin + (valid[t] ? qi : 0)) * row_stride + (size_t)a * D + g2 * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[t][ks].q = *reinterpret_cast<const vec16*>(qp + ks * 16);
     }
-    f32x16_t o[DT];
+    f32x16_t o[QT][DT];
+    float m[QT], l[QT];
 #pragma unroll
-    for (int t = 0; t < DT; ++t)
+    for (int t = 0; t < QT; ++t) {
+        m[t] = -INFINITY;
+        l[t] = 0.f;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[t][v] = 0.f;
-    float m = -INFINITY, l = 0.f;
+        for (int u = 0; u < DT; ++u)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[t][u][v] = 0.f;
+    }
 
     const int32_t* pt = bm.page_tables + (size_t)sq * bm.pt_stride;
     const size_t page_elems = (size_t)n_kv * 16 * D;
@@ -82,70 +91,82 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const bf16_t* __
     for (int pi = 0; pi < n_pages; pi += 2) {
         const int pA = pt[pi];
         const int pB = pt[(pi + 1 < n_pages) ? pi + 1 : pi];
-        // ---- S^T = K Q^T
+        // ---- S^T = K Q^T for both query tiles
         const bf16_t* kp = k_pool + (size_t)(tok < 16 ? pA : pB) * page_elems + head_off + (size_t)(tok & 15) * D + g2 * 8;
-        f32x16_t s;
+        f32x16_t s[QT];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[v] = 0.f;
+        for (int t = 0; t < QT; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[t][v] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             Frag kf;
             kf.q = *reinterpret_cast<const vec16*>(kp + ks * 16);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s, 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < QT; ++t) s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[t][ks].v, s[t], 0, 0, 0);
         }
         // ---- mask + streaming softmax (per query column = per lane pair l, l^32)
         const int t0 = pi * 16;
-        float mx = m;
+        Frag pfA[QT], pfB[QT];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int tpos = t0 + 8 * (v >> 2) + 4 * g2 + (v & 3);
-            s[v] = (tpos <= p) ? s[v] * scale_log2e : -INFINITY;
-            mx = fmaxf(mx, s[v]);
+        for (int t = 0; t < QT; ++t) {
+            float mx = m[t];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int tpos = t0 + 8 * (v >> 2) + 4 * g2 + (v & 3);
+                s[t][v] = (tpos <= p[t]) ? s[t][v] * scale_log2e : -INFINITY;
+                mx = fmaxf(mx, s[t][v]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float alpha = exp2f(m[t] - mx);
+            m[t] = mx;
+            float rs = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { s[t][v] = exp2f(s[t][v] - mx); rs += s[t][v]; }
+            l[t] = l[t] * alpha + rs;
+#pragma unroll
+            for (int u = 0; u < DT; ++u)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[t][u][v] *= alpha;
+            // k-slots of step A: tokens {4*g2 + i, 8 + 4*g2 + i} of page A; step B: the same of page B
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                pfA[t].w[i] = pack_bf16x2(s[t][2 * i], s[t][2 * i + 1]);
+                pfB[t].w[i] = pack_bf16x2(s[t][8 + 2 * i], s[t][8 + 2 * i + 1]);
+            }
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float alpha = exp2f(m - mx);
-        m = mx;
-        float rs = 0.f;
+        // ---- O^T += V^T P^T
+        // the page keeps each row as [0-3, 8-11, 4-7, 12-15]: lane group g2's eight tokens are 16 contiguous bytes
+        const bf16_t* vA = v_pool + (size_t)pA * page_elems + head_off + (size_t)lq * 16 + 8 * g2;
+        const bf16_t* vB = v_pool + (size_t)pB * page_elems + head_off + (size_t)lq * 16 + 8 * g2;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { s[v] = exp2f(s[v] - mx); rs += s[v]; }
-        l = l * alpha + rs;
-#pragma unroll
-        for (int t = 0; t < DT; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[t][v] *= alpha;
-        // ---- O^T += V^T P^T ; k-slots of step A: tokens {4*g2 + i, 8 + 4*g2 + i}, page A; step B: same of page B
-        Frag pfA, pfB;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            pfA.w[i] = pack_bf16x2(s[2 * i], s[2 * i + 1]);
-            pfB.w[i] = pack_bf16x2(s[8 + 2 * i], s[8 + 2 * i + 1]);
-        }
-        const bf16_t* vA = v_pool + (size_t)pA * page_elems + head_off + (size_t)lq * 16 + 4 * g2;
-        const bf16_t* vB = v_pool + (size_t)pB * page_elems + head_off + (size_t)lq * 16 + 4 * g2;
-#pragma unroll
-        for (int t = 0; t < DT; ++t) {
+        for (int u = 0; u < DT; ++u) {
             Frag va, vb;
-            va.h[0] = *reinterpret_cast<const vec8*>(vA + t * 32 * 16);
-            va.h[1] = *reinterpret_cast<const vec8*>(vA + t * 32 * 16 + 8);
-            vb.h[0] = *reinterpret_cast<const vec8*>(vB + t * 32 * 16);
-            vb.h[1] = *reinterpret_cast<const vec8*>(vB + t * 32 * 16 + 8);
-            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pfA.v, o[t], 0, 0, 0);
-            o[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb.v, pfB.v, o[t], 0, 0, 0);
+            va.q = *reinterpret_cast<const vec16*>(vA + u * 32 * 16);
+            vb.q = *reinterpret_cast<const vec16*>(vB + u * 32 * 16);
+#pragma unroll
+            for (int t = 0; t < QT; ++t) {
+                o[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pfA[t].v, o[t][u], 0, 0, 0);
+                o[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb.v, pfB[t].v, o[t][u], 0, 0, 0);
+            }
         }
     }
-    l += __shfl_xor(l, 32, 64);
-    if (valid) {
-        const float inv = 1.0f / l;
-        bf16_t* op = out + (size_t)(q_begin + qi) * ((size_t)n_q * D) + (size_t)a * D;
 #pragma unroll
-        for (int t = 0; t < DT; ++t)
+    for (int t = 0; t < QT; ++t) {
+        l[t] += __shfl_xor(l[t], 32, 64);
+        if (valid[t]) {
+            const float inv = 1.0f / l[t];
+            bf16_t* op = out + (size_t)(q_begin + q0 + t * 32 + lq) * ((size_t)n_q * D) + (size_t)a * D;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                vec8 w;
-                w.w[0] = pack_bf16x2(o[t][4 * j] * inv, o[t][4 * j + 1] * inv);
-                w.w[1] = pack_bf16x2(o[t][4 * j + 2] * inv, o[t][4 * j + 3] * inv);
-                *reinterpret_cast<vec8*>(op + t * 32 + 8 * j + 4 * g2) = w;
-            }
+            for (int u = 0; u < DT; ++u)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    vec8 w;
+                    w.w[0] = pack_bf16x2(o[t][u][4 * j] * inv, o[t][u][4 * j + 1] * inv);
+                    w.w[1] = pack_bf16x2(o[t][u][4 * j + 2] * inv, o[t][u][4 * j + 3] * inv);
+                    *reinterpret_cast<vec8*>(op + u * 32 + 8 * j + 4 * g2) = w;
+                }
+        }
     }
 }
 
@@ -160,7 +181,7 @@ hipError_t attn_prefill(int dt, const void* qkv, void* out, int n_q, int n_kv, c
     if (bm.n_seqs > 65535 || n_q > 65535) return hipErrorInvalidValue;
     dim3 grid((bm.max_q_len + 127) / 128, n_q, bm.n_seqs);
     const float sl2 = 1.4426950408889634f / sqrtf((float)kv.d);
-    attn_prefill_mfma_kernel<128><<<grid, 256, 0, s>>>((const bf16_t*)qkv, (bf16_t*)out, n_q, n_kv, bm,
+    attn_prefill_mfma_kernel<128, 1><<<grid, 256, 0, s>>>((const bf16_t*)qkv, (bf16_t*)out, n_q, n_kv, bm,
                                                        (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, sl2);
     return hipGetLastError();
 }
@@ -251,8 +272,10 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
         pf.w[1] = pack_bf16x2(sA[2], sA[3]);
         pf.w[2] = pack_bf16x2(sB[0], sB[1]);
         pf.w[3] = pack_bf16x2(sB[2], sB[3]);
-        const bf16_t* vA = v_pool + (size_t)pA * page_elems + head_off + (size_t)lq * 16 + 4 * g4;
-        const bf16_t* vB = v_pool + (size_t)pB * page_elems + head_off + (size_t)lq * 16 + 4 * g4;
+        // tokens 4*g4 .. 4*g4+3 sit at piece ((g4 & 1) << 1 | g4 >> 1) of the row (see vslot)
+        const int vpiece = ((g4 & 1) << 1) | (g4 >> 1);
+        const bf16_t* vA = v_pool + (size_t)pA * page_elems + head_off + (size_t)lq * 16 + 4 * vpiece;
+        const bf16_t* vB = v_pool + (size_t)pB * page_elems + head_off + (size_t)lq * 16 + 4 * vpiece;
 #pragma unroll
         for (int t = 0; t < DT; ++t) {
             Frag vf;

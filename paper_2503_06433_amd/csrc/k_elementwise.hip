@@ -108,7 +108,7 @@ hipError_t embed_rows(int dt, const void* table, const int32_t* ids, void* out, 
 // ---------------------------------------------------------------- RoPE + KV page write
 // One block per token.  Work items are 16-byte chunk pairs (element i.. and
 // i + d/2 ..) of the q and k heads, and 16-byte chunks of the v heads.
-// K lands in its page as [head][slot][d]; V lands transposed, [head][d][slot].
+// K lands in its page as [head][slot][d]; V lands transposed, [head][d][vslot(slot)].
 template <typename T>
 __global__ __launch_bounds__(256) void rope_kvwrite_kernel(T* __restrict__ qkv, int n_q, int n_kv, int d,
                                                            const float* __restrict__ rope, BatchMeta bm,
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(T* __restrict__ qkv, 
     }
     // V: element (g, e) -> v_pool[page][g][e][slot]
     const T* vrow = row + (size_t)(n_q + n_kv) * d;
-    T* vdst = v_pool + (size_t)page * page_elems + slot;
+    T* vdst = v_pool + (size_t)page * page_elems + vslot(slot);
     const int n_v = n_kv * d;
     for (int w = threadIdx.x; w < n_v; w += 256) vdst[(size_t)w * page_size] = vrow[w];
 }

@@ -55,6 +55,11 @@ template <> __device__ __forceinline__ vec16 pack16<bf16_t>(const float* f) {
     return v;
 }
 
+// Position of token slot s (0..15) inside a 16-token row of a V page.  Rows keep the order
+// [0-3, 8-11, 4-7, 12-15] (bits 2 and 3 of the slot swapped), so that the 8 tokens one MFMA lane
+// group contributes to the second attention product are one contiguous 16-byte piece.
+__device__ __forceinline__ int vslot(int s) { return (s & 3) | ((s & 4) << 1) | ((s & 8) >> 1); }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

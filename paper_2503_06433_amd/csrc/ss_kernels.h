@@ -42,7 +42,8 @@ hipError_t embed_rows(int dt, const void* table, const int32_t* ids, void* out, 
 
 // Paged cache geometry of one shard and one layer.
 //   K page: [n_heads][page_size][d]   (token-major, d contiguous)
-//   V page: [n_heads][d][page_size]   (transposed inside the page: token contiguous)
+//   V page: [n_heads][d][page_size]   (transposed inside the page: token contiguous, in the
+//           order 0-3, 8-11, 4-7, 12-15, see vslot() in ss_device.h)
 // page p of the pool starts at element p * n_heads * page_size * d.
 struct KvLayer {
     void* k_pool;
