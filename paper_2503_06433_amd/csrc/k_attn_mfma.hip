@@ -11,6 +11,8 @@
 // The contraction order inside one MFMA is free as long as both operands agree:
 // the token <-> k-slot assignment below is chosen to match what the S^T
 // accumulator holds, and the V^T operand is gathered with the same assignment.
+#include <cstdlib>
+
 #include "ss_device.h"
 #include "ss_kernels.h"
 
@@ -170,6 +172,168 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const bf16_t* __
     }
 }
 
+// ----------------------------------------------------------------------
+// Prefill, LDS-staged.  Block = 8 waves = 256 consecutive queries of one (sequence, q head).  The K
+// and V^T chunks of 64 tokens (4 pages, 32 KB) are brought into a two-stage LDS ring with direct
+// global->LDS loads and shared by all eight waves, which cuts the L2 traffic of the attention by 8
+// against every wave fetching its own operands.  K rows (256 bytes) are stored with the 16-byte
+// chunk index XOR-ed with the row number, so the 16 rows one pass of a fragment read touches fall
+// on different banks; V^T chunks are stored exactly as in the page (a fragment read is 1 KB
+// contiguous).  A wave skips the MFMAs of tiles none of its queries can see, but takes part in every
+// load and barrier.
+// ----------------------------------------------------------------------
+__device__ __forceinline__ void dma16a(const void* gptr, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
+}
+
+template <int D>
+__global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
+                                                               int n_q, int n_kv, BatchMeta bm,
+                                                               const bf16_t* __restrict__ k_pool,
+                                                               const bf16_t* __restrict__ v_pool, float scale_log2e) {
+    static_assert(D == 128, "layout below assumes 256-byte K rows");
+    constexpr int KS = D / 16, DT = D / 32, NS = 2;
+    constexpr int KBYTES = 64 * D * 2, STAGE = 2 * KBYTES;     // 16 KB of K + 16 KB of V^T
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const int sq = blockIdx.z, a = blockIdx.y;
+    const int q_begin = bm.cu_q[sq], q_len = bm.cu_q[sq + 1] - q_begin;
+    const int qb0 = blockIdx.x * 256;
+    if (qb0 >= q_len) return;                                  // whole block: before any barrier
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int before = bm.kv_before[sq];
+    const int g = a / (n_q / n_kv);
+    const int lq = lane & 31, g2 = lane >> 5;
+    const int q0 = qb0 + wave * 32;
+    const int qi = q0 + lq;
+    const bool valid = qi < q_len;
+    const int p = before + (valid ? qi : 0);
+    // last position any query of this wave / of the block can see
+    const int wave_last = before + ((q0 + 31 < q_len) ? q0 + 31 : q_len - 1);
+    const bool wave_active = q0 < q_len;
+    const int blk_last = before + ((qb0 + 255 < q_len) ? qb0 + 255 : q_len - 1);
+    const int n_pages = blk_last / 16 + 1;
+    const int n_tiles = (n_pages + 3) / 4;
+    const size_t row_stride = (size_t)(n_q + 2 * n_kv) * D;
+    const int32_t* pt = bm.page_tables + (size_t)sq * bm.pt_stride;
+    const size_t page_elems = (size_t)n_kv * 16 * D;
+    const size_t head_off = (size_t)g * 16 * D;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
+
+    Frag qf[KS];
+    {
+        const bf16_t* qp = qkv + (size_t)(q_begin + (valid ? qi : 0)) * row_stride + (size_t)a * D + g2 * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks].q = *reinterpret_cast<const vec16*>(qp + ks * 16);
+    }
+    f32x16_t o[DT];
+#pragma unroll
+    for (int u = 0; u < DT; ++u)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[u][v] = 0.f;
+    float m = -INFINITY, l = 0.f;
+
+    // DMA assignment per stage: wave w brings K rows [8w, 8w+8) (two loads of 4 rows) and V^T pieces 2w, 2w+1
+    // (piece i = page i/4 of the tile, d rows [32*(i%4), +32): 1 KB contiguous in the page).
+    auto issue = [&](int tile) {
+        const int tl = tile < n_tiles ? tile : n_tiles - 1;     // past the end: harmless repeat, keeps vmcnt uniform
+        const uint32_t st = lds_base + (uint32_t)(tile % NS) * STAGE;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int row = wave * 8 + i * 4 + (lane >> 4);     // token row of the tile
+            int pg = tl * 4 + (row >> 4);
+            pg = pg < n_pages ? pg : n_pages - 1;
+            const int chunk = (lane & 15) ^ (row & 15);
+            const bf16_t* src = k_pool + (size_t)pt[pg] * page_elems + head_off + (size_t)(row & 15) * D + chunk * 8;
+            dma16a(src, st + (wave * 8 + i * 4) * 256);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int piece = wave * 2 + i;
+            int pg = tl * 4 + (piece >> 2);
+            pg = pg < n_pages ? pg : n_pages - 1;
+            const bf16_t* src = v_pool + (size_t)pt[pg] * page_elems + head_off + (size_t)(piece & 3) * 512 + lane * 8;
+            dma16a(src, st + KBYTES + piece * 1024);
+        }
+    };
+
+    issue(0);
+    for (int it = 0; it < n_tiles; ++it) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt == 0: this wave's part of tile `it` has landed
+        __builtin_amdgcn_s_barrier();                  // everyone's part landed; stage (it-1)%NS is free
+        __builtin_amdgcn_sched_barrier(0);
+        issue(it + 1);
+        if (!wave_active || it * 64 > wave_last) continue;     // nothing visible to this wave in the tile
+        const uint8_t* st = smem + (it % NS) * STAGE;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int t0 = it * 64 + h * 32;
+            if (t0 > wave_last) break;
+            // ---- S^T = K Q^T for 32 tokens
+            const int row = h * 32 + lq;
+            f32x16_t s;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                Frag kf;
+                kf.v = *reinterpret_cast<const bf16x8_t*>(st + row * 256 + (((ks * 2 + g2) ^ (row & 15)) << 4));
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s, 0, 0, 0);
+            }
+            float mx = m;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int tpos = t0 + 8 * (v >> 2) + 4 * g2 + (v & 3);
+                s[v] = (tpos <= p) ? s[v] * scale_log2e : -INFINITY;
+                mx = fmaxf(mx, s[v]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float alpha = exp2f(m - mx);
+            m = mx;
+            float rs = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { s[v] = exp2f(s[v] - mx); rs += s[v]; }
+            l = l * alpha + rs;
+#pragma unroll
+            for (int u = 0; u < DT; ++u)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[u][v] *= alpha;
+            Frag pfA, pfB;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                pfA.w[i] = pack_bf16x2(s[2 * i], s[2 * i + 1]);
+                pfB.w[i] = pack_bf16x2(s[8 + 2 * i], s[8 + 2 * i + 1]);
+            }
+            // ---- O^T += V^T P^T : pages 2h and 2h+1 of the tile
+            const uint8_t* vA = st + KBYTES + (2 * h) * 4096 + lq * 32 + g2 * 16;
+            const uint8_t* vB = vA + 4096;
+#pragma unroll
+            for (int u = 0; u < DT; ++u) {
+                Frag va, vb;
+                va.v = *reinterpret_cast<const bf16x8_t*>(vA + u * 1024);
+                vb.v = *reinterpret_cast<const bf16x8_t*>(vB + u * 1024);
+                o[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pfA.v, o[u], 0, 0, 0);
+                o[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb.v, pfB.v, o[u], 0, 0, 0);
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                // drain the repeats issued past the end
+    l += __shfl_xor(l, 32, 64);
+    if (valid) {
+        const float inv = 1.0f / l;
+        bf16_t* op = out + (size_t)(q_begin + qi) * ((size_t)n_q * D) + (size_t)a * D;
+#pragma unroll
+        for (int u = 0; u < DT; ++u)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                vec8 w;
+                w.w[0] = pack_bf16x2(o[u][4 * j] * inv, o[u][4 * j + 1] * inv);
+                w.w[1] = pack_bf16x2(o[u][4 * j + 2] * inv, o[u][4 * j + 3] * inv);
+                *reinterpret_cast<vec8*>(op + u * 32 + 8 * j + 4 * g2) = w;
+            }
+    }
+}
+
 hipError_t attn_generic(int dt, const void* qkv, void* out, int n_q, int n_kv, const BatchMeta& bm,
                         const KvLayer& kv, hipStream_t s);
 
@@ -179,10 +343,25 @@ hipError_t attn_prefill(int dt, const void* qkv, void* out, int n_q, int n_kv, c
     if (dt != BF16 || force_generic || kv.d != 128) return attn_generic(dt, qkv, out, n_q, n_kv, bm, kv, s);
     if (kv.page_size != 16 || n_kv <= 0 || n_q % n_kv != 0 || kv.n_heads != n_kv) return hipErrorInvalidValue;
     if (bm.n_seqs > 65535 || n_q > 65535) return hipErrorInvalidValue;
-    dim3 grid((bm.max_q_len + 127) / 128, n_q, bm.n_seqs);
     const float sl2 = 1.4426950408889634f / sqrtf((float)kv.d);
-    attn_prefill_mfma_kernel<128, 1><<<grid, 256, 0, s>>>((const bf16_t*)qkv, (bf16_t*)out, n_q, n_kv, bm,
-                                                       (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, sl2);
+    static const bool direct = getenv("SS_ATTN_DIRECT") != nullptr;   // tuning switch: per-wave operand loads
+    if (direct || bm.max_q_len <= 64) {
+        dim3 grid((bm.max_q_len + 127) / 128, n_q, bm.n_seqs);
+        attn_prefill_mfma_kernel<128, 1><<<grid, 256, 0, s>>>((const bf16_t*)qkv, (bf16_t*)out, n_q, n_kv, bm,
+                                                               (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, sl2);
+        return hipGetLastError();
+    }
+    constexpr int LDS = 2 * 32768;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)attn_prefill_lds_kernel<128>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((bm.max_q_len + 255) / 256, n_q, bm.n_seqs);
+    attn_prefill_lds_kernel<128><<<grid, 512, LDS, s>>>((const bf16_t*)qkv, (bf16_t*)out, n_q, n_kv, bm,
+                                                        (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, sl2);
     return hipGetLastError();
 }
 
