@@ -28,6 +28,15 @@ PEAK_BF16_TFLOPS = 2500.0     # dense bf16 MFMA, MI355X
 PEAK_HBM_GBS = 8000.0
 
 
+def measured_traffic():
+    """HBM bytes per launch from the rocprofv3 --pmc runs recorded in profiles/ (None if not recorded)."""
+    path = os.path.join(ROOT, "bench_traffic.json")
+    if not os.path.exists(path):
+        return {}
+    with open(path) as f:
+        return json.load(f)
+
+
 def gemm_flops_per_token(cfg, k=1):
     return 2.0 * cfg.layer_params() / k
 
@@ -81,6 +90,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-reshard", action="store_true", help="leave the KV re-shard out of the step")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives); --gpus %d is not supported" % args.gpus,
@@ -95,6 +106,13 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+    if args.calibrate_copy:
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda")      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     work = wl.config2()
     cfg = work.cfg
     p_lens = [int(v) for v in work.prefill_lens]
@@ -212,6 +230,8 @@ def main():
     rp_ms, rp_n = rp[3]
     rp_bytes = 2.0 * Tp * kv_tok_bytes
 
+    traffic = measured_traffic()
+
     def hbm(bytes_per_launch, ms_total, n, traffic=None):
         a = bytes_per_launch * n / (ms_total * 1e-3) / 1e9 if ms_total > 0 else 0.0
         return {"bound": "hbm", "achieved": a, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": a / PEAK_HBM_GBS,
@@ -225,16 +245,16 @@ def main():
                    "decode_seqs": B, "decode_kv_tokens": decode_tokens, "k": 1, "layers": 1,
                    "reshard_in_step": do_reshard},
         "roofline": {"bound": "mfma", "achieved": gemm_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": gemm_tflops / PEAK_BF16_TFLOPS, "traffic": traffic.get("prefill_gemms"),
                      "kernel": "prefill GEMMs (QKV, O, gate/up, down)", "avg_ms_per_call": gemm_ms / reps},
         "rooflines": {
             "prefill_attention": {"bound": "mfma", "achieved": attn_flops * reps / (attn_ms * 1e-3) / 1e12,
                                   "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                                   "frac": attn_flops * reps / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                                   "avg_ms": attn_ms / reps},
-            "decode_attention": hbm(dattn_bytes, dattn_ms, dattn_n),
-            "decode_gemms": hbm(dgemm_bytes, dgemm_ms, reps),
-            "kv_repack": hbm(rp_bytes, rp_ms, rp_n),
+            "decode_attention": hbm(dattn_bytes, dattn_ms, dattn_n, traffic.get("decode_attention")),
+            "decode_gemms": hbm(dgemm_bytes, dgemm_ms, reps, traffic.get("decode_gemms")),
+            "kv_repack": hbm(rp_bytes, rp_ms, rp_n, traffic.get("kv_repack")),
         },
         "phase_ms": {"prefill_call": sum(v[0] for v in pf.values()) / reps,
                      "decode_call": sum(v[0] for v in dc.values()) / reps,

@@ -4,7 +4,7 @@
 // so that a tensor-parallel shard's heads are contiguous runs.
 //
 // Pure data movement, HBM-bound: every byte is read once and written once with
-// 16-byte accesses.  One block per (page, unit).  K page chunks ([16][d] per
+// 16-byte accesses.  One block per (page, unit, head).  K page chunks ([16][d] per
 // head) are already position-major and are copied straight through; V page
 // chunks are stored transposed in the page ([d][16], token order see vslot) and go through a small
 // LDS tile to be turned back into [position][d] (and the reverse on scatter).
@@ -33,9 +33,9 @@ __global__ __launch_bounds__(256) void kv_repack_kernel(void* const* __restrict_
     const int vec_per_row = d / EV;                  // 16-byte vectors per position row
     const int vec_per_chunk = PS * vec_per_row;
 
-    // ---- K: straight copy of the valid rows
-    for (int i = threadIdx.x; i < n_heads * vec_per_chunk; i += 256) {
-        const int g = i / vec_per_chunk, r = i % vec_per_chunk;
+    // ---- K: straight copy of the valid rows (one head per block: blockIdx.z)
+    const int g = blockIdx.z;
+    for (int r = threadIdx.x; r < vec_per_chunk; r += 256) {
         const int tok = r / vec_per_row;
         if (tok >= nvalid) continue;
         E* pgp = kpool + ((size_t)page * n_heads + g) * chunk + (size_t)r * EV;
@@ -44,11 +44,11 @@ __global__ __launch_bounds__(256) void kv_repack_kernel(void* const* __restrict_
         else *reinterpret_cast<vec16*>(pgp) = *reinterpret_cast<const vec16*>(stp);
     }
 
-    // ---- V: [d][16] in the page <-> [position][d] in staging, one head at a time
-    __shared__ E tile[128][PS + 2];
+    // ---- V: [d][16] in the page <-> [position][d] in staging
+    __shared__ E tile[128][PS + 1];   // odd row stride: the transposed element reads of 16 lanes fall on 16 banks
     E* stv = st + (size_t)n_heads * len * d;          // V half of the unit
     constexpr int VPR = PS / EV;                      // vectors per d-row of the page chunk
-    for (int g = 0; g < n_heads; ++g) {
+    {
         E* pgp = vpool + ((size_t)page * n_heads + g) * chunk;
         E* stp = stv + ((size_t)g * len + p0) * d;
         if (GATHER) {
@@ -93,8 +93,8 @@ template <bool GATHER>
 static hipError_t launch_repack(int dt, void* const* k_pools, void* const* v_pools, int n_heads, int d,
                                 int page_size, const RepackUnits& u, void* staging, hipStream_t s) {
     if (u.n_units <= 0 || u.max_pages <= 0) return hipSuccess;
-    if (page_size != 16 || d > 128 || d % 8 != 0 || n_heads <= 0 || u.n_units > 65535) return hipErrorInvalidValue;
-    dim3 grid(u.max_pages, u.n_units);
+    if (page_size != 16 || d > 128 || d % 8 != 0 || n_heads <= 0 || n_heads > 65535 || u.n_units > 65535) return hipErrorInvalidValue;
+    dim3 grid(u.max_pages, u.n_units, n_heads);
     if (dt == F32)
         kv_repack_kernel<uint32_t, GATHER><<<grid, 256, 0, s>>>(k_pools, v_pools, n_heads, d, u, (uint32_t*)staging);
     else
