@@ -31,8 +31,13 @@ union Frag {
     uint32_t w[4];
 };
 
+// two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-    return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16);
+    const f32x2_t v = {a, b};
+    const bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
+    return *reinterpret_cast<const uint32_t*>(&r);
 }
 
 // ======================================================================
@@ -280,24 +285,32 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
                 kf.v = *reinterpret_cast<const bf16x8_t*>(st + row * 256 + (((ks * 2 + g2) ^ (row & 15)) << 4));
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s, 0, 0, 0);
             }
-            float mx = m;
+            // causal mask only on steps that reach past the wave's first query (wave-uniform test)
+            if (t0 + 31 > before + q0) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int tpos = t0 + 8 * (v >> 2) + 4 * g2 + (v & 3);
-                s[v] = (tpos <= p) ? s[v] * scale_log2e : -INFINITY;
-                mx = fmaxf(mx, s[v]);
+                for (int v = 0; v < 16; ++v) {
+                    const int tpos = t0 + 8 * (v >> 2) + 4 * g2 + (v & 3);
+                    s[v] = (tpos <= p) ? s[v] : -INFINITY;
+                }
             }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            // streaming softmax in base 2 on the raw scores: exp2(s*c - max*c) with c = log2(e)/sqrt(d)
+            float mr = s[0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) mr = fmaxf(mr, s[v]);
+            mr = fmaxf(mr, __shfl_xor(mr, 32, 64));
+            const float mx = fmaxf(m, mr * scale_log2e);
             const float alpha = exp2f(m - mx);
             m = mx;
             float rs = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { s[v] = exp2f(s[v] - mx); rs += s[v]; }
+            for (int v = 0; v < 16; ++v) { s[v] = exp2f(fmaf(s[v], scale_log2e, -mx)); rs += s[v]; }
             l = l * alpha + rs;
+            if (__ballot(alpha != 1.0f) != 0ull) {       // the running maximum moved for some query of the wave
 #pragma unroll
-            for (int u = 0; u < DT; ++u)
+                for (int u = 0; u < DT; ++u)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o[u][v] *= alpha;
+                    for (int v = 0; v < 16; ++v) o[u][v] *= alpha;
+            }
             Frag pfA, pfB;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {

@@ -612,6 +612,194 @@ static hipError_t launch_dma4(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t
     return hipGetLastError();
 }
 
+
+// Variant with K slices of 64 (128-byte LDS rows, full cache lines per request) and two ring stages
+// of 64 KB: half as many barriers and DMA instructions per flop as the 32-wide ring.  Four MFMA groups
+// per slice; the barrier that publishes slice kt+1 and frees slice kt's stage sits before the last
+// group, whose MFMAs run while slice kt+2 is requested.
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm_mfma_dma64_kernel(const bf16_t* __restrict__ A, int lda,
+                                                              const bf16_t* __restrict__ Wt, bf16_t* __restrict__ C,
+                                                              int ldc, const bf16_t* __restrict__ R, int M, int N, int K,
+                                                              int tiles_m, int tiles_n, int per_xcd) {
+    constexpr int BM = 256, BN = 256, WN = 4, TM = 4, TN = 2;
+    constexpr int STAGE = (BM + BN) * 128;
+    constexpr int LPS = 8;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+    const int xcd = blockIdx.x & 7;
+    const int logical = xcd * per_xcd + (blockIdx.x >> 3);
+    if ((blockIdx.x >> 3) >= per_xcd || logical >= tiles_m * tiles_n) return;
+    constexpr int GM = 8;
+    const int group_size = GM * tiles_n;
+    const int group = logical / group_size;
+    const int first_m = group * GM;
+    const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+    const int in_group = logical - group * group_size;
+    const int m0 = (first_m + in_group % gm) * BM, n0 = (in_group / gm) * BN;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
+
+    // waves 0-3 bring A rows [64w, 64w+64), waves 4-7 bring Wt rows; a wave-level load covers 8 rows of 128 bytes
+    const bool isA = wave < 4;
+    const int row_base = (wave & 3) * 64;
+    const uint8_t* src[LPS];
+#pragma unroll
+    for (int i = 0; i < LPS; ++i) {
+        const int row = row_base + i * 8 + (lane >> 3);
+        const int kc = (lane & 7) ^ ((row & 7) ^ ((row >> 3) & 1));
+        if (isA) {
+            int gr = m0 + row;
+            gr = gr < M ? gr : M - 1;
+            src[i] = reinterpret_cast<const uint8_t*>(A + (size_t)gr * lda + kc * 8);
+        } else {
+            int gr = n0 + row;
+            gr = gr < N ? gr : N - 1;
+            src[i] = reinterpret_cast<const uint8_t*>(Wt + (size_t)gr * K + kc * 8);
+        }
+    }
+    const uint32_t dst0 = lds_base + (isA ? 0 : BM * 128) + row_base * 128;
+    const int nk = K / 64;
+    auto issue1 = [&](int slice, int i) {
+        const int sl = slice < nk ? slice : nk - 1;
+        const uint32_t d = dst0 + (uint32_t)(slice & 1) * STAGE;
+        dma16(src[i] + (size_t)sl * 128, d + i * 1024);
+    };
+
+    f32x16_t acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int lrow = lane & 31, lgrp = lane >> 5;
+    bf16x8_t af[2][TM], bfr[2][TN];
+    auto read_frags = [&](const uint8_t* st, int ks) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            af[ks & 1][i] = *reinterpret_cast<const bf16x8_t*>(st + lds_chunk_off(wm * 128 + i * 32 + lrow, ks * 2 + lgrp));
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            bfr[ks & 1][j] = *reinterpret_cast<const bf16x8_t*>(st + BM * 128 + lds_chunk_off(wn * 64 + j * 32 + lrow, ks * 2 + lgrp));
+    };
+    auto mfma_group = [&](int ks) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+    };
+
+#pragma unroll
+    for (int i = 0; i < LPS; ++i) issue1(0, i);
+#pragma unroll
+    for (int i = 0; i < LPS; ++i) issue1(1, i);
+    __builtin_amdgcn_s_waitcnt(VmcntImm<LPS>::value);      // slice 0 landed
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(smem, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+        const uint8_t* st = smem + (kt & 1) * STAGE;
+        const uint8_t* stn = smem + ((kt + 1) & 1) * STAGE;
+#pragma unroll
+        for (int ks = 0; ks < 3; ++ks) {
+            read_frags(st, ks + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_group(ks);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): slice kt+1 has landed
+        __builtin_amdgcn_s_waitcnt(0xC07F);                  // lgkmcnt(0): the last fragments of slice kt are in registers
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(stn, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        // last group of the slice, with the requests for slice kt+2 (into the stage just freed) between its MFMAs
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                issue1(kt + 2, i * TN + j);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][i], bfr[1][j], acc[i][j], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+
+    const int col_in = lane & 31;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int rbase = m0 + wm * 128 + i * 32 + 4 * lgrp;
+        if (EPI == EPI_SWIGLU) {
+#pragma unroll
+            for (int j = 0; j < TN; j += 2) {
+                const int nb = n0 + wn * 64 + j * 32;
+                const int oc = (nb >> 1) + col_in;
+                if (nb + col_in >= N) continue;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = rbase + 8 * (v >> 2) + (v & 3);
+                    if (r >= M) continue;
+                    const float g = acc[i][j][v], u = acc[i][j + 1][v];
+                    C[(size_t)r * ldc + oc] = f2bf(g / (1.0f + __expf(-g)) * u);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int c = n0 + wn * 64 + j * 32 + col_in;
+                if (c >= N) continue;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = rbase + 8 * (v >> 2) + (v & 3);
+                    if (r >= M) continue;
+                    float o = acc[i][j][v];
+                    if (EPI == EPI_RESIDUAL) o += bf2f(R[(size_t)r * ldc + c]);
+                    C[(size_t)r * ldc + c] = f2bf(o);
+                }
+            }
+        }
+    }
+}
+
+static hipError_t launch_dma64(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
+                               int N, int K, int epi, hipStream_t s) {
+    constexpr size_t LDS = (size_t)2 * 512 * 128;
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    const long long n_tiles = (long long)tiles_m * tiles_n;
+    if (n_tiles > (1ll << 30) || K % 64 != 0) return hipErrorInvalidValue;
+    const int per_xcd = (int)((n_tiles + 7) / 8);
+    const unsigned grid = (unsigned)per_xcd * 8;
+#define SS_LAUNCH(E)                                                                                            \
+    {                                                                                                           \
+        auto kfn = gemm_mfma_dma64_kernel<E>;                                                                   \
+        static bool attr_set = false;                                                                           \
+        if (!attr_set) {                                                                                        \
+            hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS); \
+            if (e != hipSuccess) return e;                                                                      \
+            attr_set = true;                                                                                    \
+        }                                                                                                       \
+        kfn<<<grid, 512, LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd);                  \
+    }
+    switch (epi) {
+        case EPI_STORE: SS_LAUNCH(EPI_STORE) break;
+        case EPI_RESIDUAL:
+            if (!R) return hipErrorInvalidValue;
+            SS_LAUNCH(EPI_RESIDUAL) break;
+        case EPI_SWIGLU: SS_LAUNCH(EPI_SWIGLU) break;
+        default: return hipErrorInvalidValue;
+    }
+#undef SS_LAUNCH
+    return hipGetLastError();
+}
+
 template <int NS, int PROBE = 0>
 static hipError_t launch_dma(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
                              int N, int K, int epi, hipStream_t s) {
@@ -765,6 +953,7 @@ hipError_t gemm_mfma_bf16_cfg(int cfg, const void* A, int lda, const void* Wt, v
         case 9: return launch_dma<4, 4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
         case 10: return launch_dma<4, 8>(a, lda, w, c, ldc, r, M, N, K, epi, s);
         case 11: return launch_dma4<4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+        case 13: return launch_dma64(a, lda, w, c, ldc, r, M, N, K, epi, s);
         case 12: return launch_dma4<3>(a, lda, w, c, ldc, r, M, N, K, epi, s);
         default: return hipErrorInvalidValue;
     }
