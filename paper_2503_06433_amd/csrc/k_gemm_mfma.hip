@@ -918,13 +918,15 @@ hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int l
     bf16_t* c = (bf16_t*)C;
     const bf16_t* r = (const bf16_t*)R;
     // Prefill-sized outputs: the 256 x 256 direct-to-LDS kernel.  Smaller outputs (decode batches)
-    // are bound by streaming the weights: 128 x 128 tiles, and K split until at least ~512 blocks
-    // keep all 256 CUs pulling from HBM (partials in fp32, summed by a small second kernel).
+    // are bound by streaming the weights: 128 x 128 tiles with split-K (partials in fp32, summed by a
+    // small second kernel).
     const long long big = (long long)((M + 255) / 256) * ((N + 255) / 256);
     if (big >= 512) return launch_dma<4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
     const long long mid = (long long)((M + 127) / 128) * ((N + 127) / 128);
+    // split K until every CU has a block, but only while the fp32 partials (8*S*M*N bytes written and
+    // read back) stay below the weight bytes (2*N*K) they help to stream: S <= K / (4 M)
     int split = 1;
-    while (split < 8 && mid * split < 512 && (K / 64) % (split * 2) == 0 &&
+    while (split < 8 && mid * split < 256 && (K / 64) % (split * 2) == 0 && (long long)(split * 2) * 4 * M <= K &&
            (size_t)(split * 2) * M * N * sizeof(float) <= ws_bytes && ws)
         split *= 2;
     return launch_cfg<128, 128, 2, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s, split, ws);

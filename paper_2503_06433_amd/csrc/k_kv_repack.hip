@@ -40,8 +40,8 @@ __global__ __launch_bounds__(256) void kv_repack_kernel(void* const* __restrict_
         if (tok >= nvalid) continue;
         E* pgp = kpool + ((size_t)page * n_heads + g) * chunk + (size_t)r * EV;
         E* stp = st + ((size_t)g * len + p0) * d + (size_t)r * EV;
-        if (GATHER) *reinterpret_cast<vec16*>(stp) = *reinterpret_cast<const vec16*>(pgp);
-        else *reinterpret_cast<vec16*>(pgp) = *reinterpret_cast<const vec16*>(stp);
+        if (GATHER) st16_stream(stp, ld16_stream(pgp));
+        else st16_stream(pgp, ld16_stream(stp));
     }
 
     // ---- V: [d][16] in the page <-> [position][d] in staging
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) void kv_repack_kernel(void* const* __restrict_
             for (int i = threadIdx.x; i < d * VPR; i += 256) {
                 const int e = i / VPR, t0 = (i % VPR) * EV;
                 union { vec16 v; E x[EV]; } w;
-                w.v = *reinterpret_cast<const vec16*>(pgp + (size_t)e * PS + t0);
+                w.v = ld16_stream(pgp + (size_t)e * PS + t0);
 #pragma unroll
                 for (int j = 0; j < EV; ++j) tile[e][t0 + j] = w.x[j];
             }
@@ -65,13 +65,13 @@ __global__ __launch_bounds__(256) void kv_repack_kernel(void* const* __restrict_
                 union { vec16 v; E x[EV]; } w;
 #pragma unroll
                 for (int j = 0; j < EV; ++j) w.x[j] = tile[e0 + j][vslot(tok)];
-                *reinterpret_cast<vec16*>(stp + (size_t)tok * d + e0) = w.v;
+                st16_stream(stp + (size_t)tok * d + e0, w.v);
             }
         } else {
             for (int o = threadIdx.x; o < PS * vec_per_row; o += 256) {
                 const int tok = o / vec_per_row, e0 = (o % vec_per_row) * EV;
                 union { vec16 v; E x[EV]; } w;
-                if (tok < nvalid) w.v = *reinterpret_cast<const vec16*>(stp + (size_t)tok * d + e0);
+                if (tok < nvalid) w.v = ld16_stream(stp + (size_t)tok * d + e0);
                 else w.v = vec16{{0u, 0u, 0u, 0u}};
 #pragma unroll
                 for (int j = 0; j < EV; ++j) tile[e0 + j][vslot(tok)] = w.x[j];
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void kv_repack_kernel(void* const* __restrict_
                 union { vec16 v; E x[EV]; } w;
 #pragma unroll
                 for (int j = 0; j < EV; ++j) w.x[j] = tile[e][t0 + j];
-                *reinterpret_cast<vec16*>(pgp + (size_t)e * PS + t0) = w.v;
+                st16_stream(pgp + (size_t)e * PS + t0, w.v);
             }
         }
         __syncthreads();

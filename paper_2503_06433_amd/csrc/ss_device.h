@@ -25,6 +25,19 @@ __device__ __forceinline__ void stf(bf16_t* p, float v) { *p = f2bf(v); }
 // 16-byte vector of raw storage
 struct __attribute__((aligned(16))) vec16 { uint32_t w[4]; };
 
+// streaming (touched once) 16-byte accesses: nontemporal hints keep them from displacing reusable lines
+typedef uint32_t u32x4_nt __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ vec16 ld16_stream(const void* p) {
+    const u32x4_nt v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(p));
+    vec16 r;
+    r.w[0] = v[0]; r.w[1] = v[1]; r.w[2] = v[2]; r.w[3] = v[3];
+    return r;
+}
+__device__ __forceinline__ void st16_stream(void* p, const vec16& r) {
+    const u32x4_nt v = {r.w[0], r.w[1], r.w[2], r.w[3]};
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4_nt*>(p));
+}
+
 template <typename T> struct VecOf;              // elements per 16 bytes
 template <> struct VecOf<float> { static constexpr int N = 4; };
 template <> struct VecOf<bf16_t> { static constexpr int N = 8; };

@@ -316,10 +316,11 @@ ssk::KvLayer kv_layer(ss_ctx* c, Shard* s, int ll) {
     return k;
 }
 
-// Pages per decode work item.  Longer items mean fewer partial results to write and merge (measured:
-// 5.2 TB/s at 8 pages, 5.6 TB/s at 64 on the 7B-shape decode batch), but the batch must still split
-// into enough waves to fill 256 CUs several times: aim at about 16 K waves (items x kv heads), within
-// [8, 64] pages.  SS_DECODE_ITEM_PAGES overrides the choice (tuning).
+// Pages per decode work item.  Longer items mean fewer partial results to write and merge and less
+// per-wave set-up (measured on the 7B-shape batch: 5.2 TB/s at 8 pages, 5.6 at 64; on the GQA shard
+// with one kv head: 3.9 TB/s at 8 pages, 4.6 at 64, 3.7 at 128), but the batch must still split into a
+// couple of thousand waves (items x kv heads): within [16, 64] pages.  SS_DECODE_ITEM_PAGES overrides
+// the choice (tuning).
 static int decode_item_pages(int64_t total_pages, int n_kv_local) {
     static const int forced = [] {
         const char* e = getenv("SS_DECODE_ITEM_PAGES");
@@ -327,8 +328,8 @@ static int decode_item_pages(int64_t total_pages, int n_kv_local) {
         return n >= 2 && n <= 4096 ? (n & ~1) : 0;
     }();
     if (forced) return forced;
-    int64_t n = total_pages * n_kv_local / 16384;
-    n = std::max<int64_t>(8, std::min<int64_t>(64, n));
+    int64_t n = total_pages * n_kv_local / 2048;
+    n = std::max<int64_t>(16, std::min<int64_t>(64, n));
     return (int)(n & ~1);
 }
 
