@@ -11,8 +11,6 @@
 // The contraction order inside one MFMA is free as long as both operands agree:
 // the token <-> k-slot assignment below is chosen to match what the S^T
 // accumulator holds, and the V^T operand is gathered with the same assignment.
-#include <cstdlib>
-
 #include "ss_device.h"
 #include "ss_kernels.h"
 
@@ -357,8 +355,7 @@ hipError_t attn_prefill(int dt, const void* qkv, void* out, int n_q, int n_kv, c
     if (kv.page_size != 16 || n_kv <= 0 || n_q % n_kv != 0 || kv.n_heads != n_kv) return hipErrorInvalidValue;
     if (bm.n_seqs > 65535 || n_q > 65535) return hipErrorInvalidValue;
     const float sl2 = 1.4426950408889634f / sqrtf((float)kv.d);
-    static const bool direct = getenv("SS_ATTN_DIRECT") != nullptr;   // tuning switch: per-wave operand loads
-    if (direct || bm.max_q_len <= 64) {
+    if (bm.max_q_len <= 64) {       // short prompts: per-wave operand loads, no ring to fill
         dim3 grid((bm.max_q_len + 127) / 128, n_q, bm.n_seqs);
         attn_prefill_mfma_kernel<128, 1><<<grid, 256, 0, s>>>((const bf16_t*)qkv, (bf16_t*)out, n_q, n_kv, bm,
                                                                (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, sl2);

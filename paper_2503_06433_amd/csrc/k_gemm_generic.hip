@@ -79,15 +79,15 @@ static hipError_t launch_generic(const void* A, int lda, const void* Wt, void* C
 }
 
 hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int ldc, const void* R, int M, int N,
-                          int K, int epi, hipStream_t s, float* ws, size_t ws_bytes);
+                          int K, int epi, hipStream_t s, float* ws, size_t ws_bytes, int max_rounds);
 bool gemm_mfma_supported(int M, int N, int K, int lda, int ldc, int epi);
 
 hipError_t gemm_nt(int dt, const void* A, int lda, const void* Wt, void* C, int ldc, const void* R, int M, int N,
-                   int K, int epi, bool force_generic, hipStream_t s, float* ws, size_t ws_bytes) {
+                   int K, int epi, bool force_generic, hipStream_t s, float* ws, size_t ws_bytes, int max_rounds) {
     if (M <= 0 || N <= 0) return hipSuccess;
     if (K <= 0 || lda < K || !A || !Wt || !C) return hipErrorInvalidValue;
     if (dt == BF16 && !force_generic && gemm_mfma_supported(M, N, K, lda, ldc, epi))
-        return gemm_mfma_bf16(A, lda, Wt, C, ldc, R, M, N, K, epi, s, ws, ws_bytes);
+        return gemm_mfma_bf16(A, lda, Wt, C, ldc, R, M, N, K, epi, s, ws, ws_bytes, max_rounds);
     if (epi == EPI_SWIGLU) return hipErrorInvalidValue;
     if (dt == F32) return launch_generic<float>(A, lda, Wt, C, ldc, R, M, N, K, epi, s);
     return launch_generic<bf16_t>(A, lda, Wt, C, ldc, R, M, N, K, epi, s);

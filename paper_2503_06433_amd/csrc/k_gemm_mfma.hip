@@ -211,239 +211,90 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
 
 
 // ----------------------------------------------------------------------------
-// Large-tile kernel with direct global->LDS loads and a multi-stage LDS ring.
+// Large-output kernel: persistent, direct global->LDS loads, two-stage ring.
 //
-// 256 x 256 tile, 8 waves (2 x 4, wave tile 128 x 64), K slices of 32, NS ring
-// stages of 32 KB.  `global_load_lds_dwordx4` moves 16 bytes per lane straight
-// into LDS (lane j of a wave lands at M0 + 16*j), so no registers are spent on
-// staging and slices can be requested NS-1 iterations ahead: an L2 miss (about
-// one in five requests here, served by the memory-side cache or HBM) has
-// several thousand cycles to arrive instead of one iteration.  Completion is
-// tracked with vmcnt by hand (the loads are issued from inline asm), and a
-// bare s_barrier publishes a stage; the fence form of the barrier would drain
-// every outstanding load.
+// One block (4 waves, 2 x 2, wave tile 128 x 128, 256 fp32 accumulators per lane)
+// per CU walks that CU's share of the 256 x 256 output tiles.  K is cut in slices
+// of 64: a row of a slice is one 128-byte line, so every request to L2 moves a
+// whole line (slices of 32 ask for every line twice, and the number of requests,
+// not their bytes, is what the L2 channels run out of).  `global_load_lds_dwordx4`
+// moves 16 bytes per lane straight into LDS (lane j of a wave lands at
+// M0 + 16*j): no registers are spent on staging.  The ring has two stages of
+// 64 KB and runs on across tile boundaries, so the first slices of the next tile
+// are already in flight while the current tile is finished and written out.
 //
-// LDS rows are 64 bytes (4 chunks of 16 bytes); chunk position = kc ^ sw(row)
-// with sw(row) = ((row>>1)&3) ^ ((row>>3)&1), which spreads the 16 rows that one
-// pass of a 16-byte fragment read touches over all banks.  A wave-level load
-// covers 16 consecutive rows: lane j supplies row j/4, position j%4, and
-// therefore fetches global chunk (j%4) ^ sw(row) of that row.
+// Per slice (4 k-steps of 16 MFMAs per wave):
+//   k-steps 0..2  multiply out of the current stage; the fragments of the next
+//                 k-step are read one at a time behind the first 8 MFMAs (a burst
+//                 of 8 reads fills the LDS command queue and holds up the MFMAs
+//                 issued behind it)
+//   k-step 3      wait until the own loads of the next slice have landed, barrier
+//                 (the next stage is complete, the current one is free), then
+//                 request the slice after the next into the freed stage: 8 loads
+//                 per wave here and 8 in k-step 0 of the next slice, one behind
+//                 every other MFMA (the L1 -> LDS path moves 64 bytes per clock, a
+//                 64 KB slice keeps it busy for half of the slice's MFMA time;
+//                 requests queued faster than that stall the issuing wave)
+// Completion is tracked with vmcnt by hand (the loads are issued from inline
+// asm), and a bare s_barrier publishes a stage; only loads of this one kind are
+// in flight, so they complete in issue order.
+//
+// LDS rows are 128 bytes (8 chunks of 16 bytes); chunk position = kc ^ ((row>>1)&7),
+// which spreads the 16 rows that one pass of a fragment read touches over all
+// banks.  A wave-level load covers 8 consecutive rows: lane j supplies row j/8,
+// position j%8, and therefore fetches global chunk (j%8) ^ ((row>>1)&7).
+//
+// The product is formed transposed (weight fragment as the row operand): a lane
+// ends up with 4 consecutive output columns of one token, which go through an
+// 8 KB per wave fp32 staging tile (outside the ring) to come out as 16-byte,
+// full-line stores.  Outputs are written with the nontemporal hint: they are
+// not read again by this kernel and would otherwise push the operand slices
+// out of L2.
 // ----------------------------------------------------------------------------
-__device__ __forceinline__ int lds64_off(int row, int kc) {
-    const int sw = ((row >> 1) & 3) ^ ((row >> 3) & 1);
-    return row * 64 + ((kc ^ sw) << 4);
-}
-
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_addr) : "memory");
-}
-
-template <int EPI, int NS, int PROBE = 0>
-__global__ __launch_bounds__(512) void gemm_mfma_dma_kernel(const bf16_t* __restrict__ A, int lda,
-                                                            const bf16_t* __restrict__ Wt, bf16_t* __restrict__ C,
-                                                            int ldc, const bf16_t* __restrict__ R, int M, int N, int K,
-                                                            int tiles_m, int tiles_n, int per_xcd) {
-    constexpr int BM = 256, BN = 256, WN = 4, TM = 4, TN = 2;
-    constexpr int STAGE = (BM + BN) * 64;        // bytes per ring stage
-    constexpr int LPS = 4;                       // DMA loads per wave per stage
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-
-    const int xcd = blockIdx.x & 7;
-    const int logical = xcd * per_xcd + (blockIdx.x >> 3);
-    if ((blockIdx.x >> 3) >= per_xcd || logical >= tiles_m * tiles_n) return;
-    constexpr int GM = 8;
-    const int group_size = GM * tiles_n;
-    const int group = logical / group_size;
-    const int first_m = group * GM;
-    const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
-    const int in_group = logical - group * group_size;
-    const int m0 = (first_m + in_group % gm) * BM, n0 = (in_group / gm) * BN;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
-    const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
-
-    // ---- DMA assignment: waves 0-3 bring A rows [64w, 64w+64), waves 4-7 bring Wt rows [64(w-4), ...)
-    const bool isA = wave < 4;
-    const int row_base = (wave & 3) * 64;
-    const uint8_t* src[LPS];
-#pragma unroll
-    for (int i = 0; i < LPS; ++i) {
-        const int row = (PROBE & 4) ? row_base + i * 8 + (lane >> 3) : row_base + i * 16 + (lane >> 2);
-        const int kc = (PROBE & 4) ? (lane & 7) : (lane & 3) ^ (((row >> 1) & 3) ^ ((row >> 3) & 1));
-        if (isA) {
-            int gr = ((PROBE & 8) ? 0 : m0) + row;
-            gr = gr < M ? gr : M - 1;
-            src[i] = reinterpret_cast<const uint8_t*>(A + (size_t)gr * lda + kc * 8);
-        } else {
-            int gr = ((PROBE & 8) ? 0 : n0) + row;
-            gr = gr < N ? gr : N - 1;
-            src[i] = reinterpret_cast<const uint8_t*>(Wt + (size_t)gr * K + kc * 8);
-        }
-    }
-    const uint32_t dst0 = lds_base + (isA ? 0 : BM * 64) + row_base * 64;
-    const int nk = K / 32;
-    // one DMA load (1 KB per wave) of a slice; slices past the end repeat the last one, which is
-    // harmless and keeps the vmcnt bookkeeping uniform
-    auto issue1 = [&](int slice, int i) {
-        const int sl = slice < nk ? slice : nk - 1;
-        const uint32_t d = dst0 + (uint32_t)(slice % NS) * STAGE;
-        dma16(src[i] + (size_t)sl * 64, d + i * 1024);
-    };
-    auto issue = [&](int slice) {
-#pragma unroll
-        for (int i = 0; i < LPS; ++i) issue1(slice, i);
-    };
-
-    f32x16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    const int lrow = lane & 31, lgrp = lane >> 5;
-    int a_off[TM][2], b_off[TN][2];
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) a_off[i][ks] = lds64_off(wm * 128 + i * 32 + lrow, ks * 2 + lgrp);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b_off[j][ks] = BM * 64 + lds64_off(wn * 64 + j * 32 + lrow, ks * 2 + lgrp);
-    }
-
-    // Pipeline (per K slice kt, two MFMA groups G0 = k-step 0, G1 = k-step 1):
-    //   [A] read fragments F1(kt) from LDS; issue G0 with F0(kt)
-    //   [B] wait until slice kt+1 has landed and F1(kt) has arrived; barrier
-    //       -> stage kt+1 is readable by everyone, stage kt is no longer read by anyone
-    //   [C] request slice kt+NS into stage kt; read F0(kt+1); issue G1 with F1(kt)
-    // so every MFMA group has its operands requested one group ahead, and the
-    // barrier falls between two groups whose MFMAs keep the pipe busy meanwhile.
-    auto wait_landed = [&](int younger) {     // vmcnt <= 4 * younger (immediates only)
-        if (younger >= 4) __builtin_amdgcn_s_waitcnt(0x4F70);       // 16
-        else if (younger == 3) __builtin_amdgcn_s_waitcnt(0x0F7C);  // 12
-        else if (younger == 2) __builtin_amdgcn_s_waitcnt(0x0F78);  // 8
-        else if (younger == 1) __builtin_amdgcn_s_waitcnt(0x0F74);  // 4
-        else __builtin_amdgcn_s_waitcnt(0x0F70);
-    };
-    bf16x8_t af[2][TM], bfr[2][TN];
-    auto read_frags = [&](const uint8_t* st, int ks) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) af[ks][i] = *reinterpret_cast<const bf16x8_t*>(st + a_off[i][ks]);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[ks][j] = *reinterpret_cast<const bf16x8_t*>(st + b_off[j][ks]);
-    };
-    // The L1 -> LDS path moves 64 bytes per clock at best, so a slice (32 KB per block) needs at least
-    // 512 of the ~1024 cycles its MFMAs take: the DMA loads are spread between the MFMAs instead of
-    // being queued in one burst that would hold up the fragment reads issued behind them.
-    auto mfma_half = [&](int ks, int h) {
-#pragma unroll
-        for (int i = 2 * h; i < 2 * h + 2; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
-    };
-
-#pragma unroll
-    for (int s = 0; s < NS - 1; ++s) issue(s);
-    wait_landed(NS - 2);           // slice 0 has landed (slices 1 .. NS-2 may still fly)
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    issue1(NS - 1, 0);
-    issue1(NS - 1, 1);
-    read_frags(smem, 0);
-    for (int kt = 0; kt < nk; ++kt) {
-        const uint8_t* st = smem + (kt % NS) * STAGE;
-        const uint8_t* stn = smem + ((kt + 1) % NS) * STAGE;
-        read_frags(st, 1);                                   // [A]
-        __builtin_amdgcn_sched_barrier(0);
-        mfma_half(0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (!(PROBE & 1)) issue1(kt + NS - 1, 2);            // second half of the slice whose stage was freed one barrier ago
-        mfma_half(0, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        if (!(PROBE & 1)) issue1(kt + NS - 1, 3);
-        wait_landed(NS - 2);                                 // [B] slice kt+1 complete (4 * (NS-2) younger loads may fly)
-        __builtin_amdgcn_s_waitcnt(0xC07F);                  // lgkmcnt(0): F1(kt) is in registers
-        if (!(PROBE & 2)) __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(stn, 0);                                  // [C]
-        __builtin_amdgcn_sched_barrier(0);
-        if (!(PROBE & 1)) issue1(kt + NS, 0);
-        mfma_half(1, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (!(PROBE & 1)) issue1(kt + NS, 1);
-        mfma_half(1, 1);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // drain the repeats issued past the end
-
-    const int col_in = lane & 31;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int rbase = m0 + wm * 128 + i * 32 + 4 * lgrp;
-        if (EPI == EPI_SWIGLU) {
-#pragma unroll
-            for (int j = 0; j < TN; j += 2) {
-                const int nb = n0 + wn * 64 + j * 32;
-                const int oc = (nb >> 1) + col_in;
-                if (nb + col_in >= N) continue;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int r = rbase + 8 * (v >> 2) + (v & 3);
-                    if (r >= M) continue;
-                    const float g = acc[i][j][v], u = acc[i][j + 1][v];
-                    C[(size_t)r * ldc + oc] = f2bf(g / (1.0f + __expf(-g)) * u);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int c = n0 + wn * 64 + j * 32 + col_in;
-                if (c >= N) continue;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int r = rbase + 8 * (v >> 2) + (v & 3);
-                    if (r >= M) continue;
-                    float o = acc[i][j][v];
-                    if (EPI == EPI_RESIDUAL) o += bf2f(R[(size_t)r * ldc + c]);
-                    C[(size_t)r * ldc + c] = f2bf(o);
-                }
-            }
-        }
-    }
-}
-
-
-// Same ring, four waves (2 x 2), wave tile 128 x 128: every fragment read from LDS feeds four MFMAs
-// instead of two or four (8 fragment reads per 16 MFMAs, against 6 per 8 above), which takes a third
-// off the LDS read traffic that competes with the incoming DMA writes.  One wave per SIMD, 256
-// accumulator registers per lane.
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 template <int V> struct VmcntImm { static constexpr int value = (V & 15) | ((V >> 4) << 14) | 0x0F70; };
 
-template <int EPI, int NS>
-__global__ __launch_bounds__(256) void gemm_mfma_dma4_kernel(const bf16_t* __restrict__ A, int lda,
-                                                             const bf16_t* __restrict__ Wt, bf16_t* __restrict__ C,
-                                                             int ldc, const bf16_t* __restrict__ R, int M, int N, int K,
-                                                             int tiles_m, int tiles_n, int per_xcd) {
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __restrict__ A, int lda,
+                                                               const bf16_t* __restrict__ Wt, bf16_t* __restrict__ C,
+                                                               int ldc, const bf16_t* __restrict__ R, int M, int N,
+                                                               int K, int tiles_m, int tiles_n, int per_xcd,
+                                                               int cus_per_xcd, int it0, int max_it) {
     constexpr int BM = 256, BN = 256, TM = 4, TN = 4;
-    constexpr int STAGE = (BM + BN) * 64;
-    constexpr int LPS = 8;                       // DMA loads per wave per stage
+    constexpr int STAGE = (BM + BN) * 128;       // bytes per ring stage
+    constexpr int LPS = 16;                      // loads per wave per slice
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
-    const int xcd = blockIdx.x & 7;
-    const int logical = xcd * per_xcd + (blockIdx.x >> 3);
-    if ((blockIdx.x >> 3) >= per_xcd || logical >= tiles_m * tiles_n) return;
+    // ---- this block's tiles: XCD x (blocks are dealt to the XCDs round-robin) owns the contiguous run
+    // [x * per_xcd, (x+1) * per_xcd) of tiles, ordered in groups of 8 tile rows, so that the slices an XCD
+    // touches at one time stay in its own L2; inside the run the XCD's blocks take tiles round-robin
+    const int xcd = blockIdx.x & 7, cu = blockIdx.x >> 3;
+    const int n_tiles = tiles_m * tiles_n;
+    int xcd_end = (xcd + 1) * per_xcd;
+    xcd_end = xcd_end < n_tiles ? xcd_end : n_tiles;
+    // (this launch covers rounds [it0, it0 + max_it) of that walk)
+    const int first = xcd * per_xcd + cu + it0 * cus_per_xcd;
+    if (first >= xcd_end) return;
+    int nt_local = (xcd_end - first + cus_per_xcd - 1) / cus_per_xcd;
+    nt_local = nt_local < max_it ? nt_local : max_it;
     constexpr int GM = 8;
-    const int group_size = GM * tiles_n;
-    const int group = logical / group_size;
-    const int first_m = group * GM;
-    const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
-    const int in_group = logical - group * group_size;
-    const int m0 = (first_m + in_group % gm) * BM, n0 = (in_group / gm) * BN;
+    auto tile_origin = [&](int it, int& m0, int& n0) {
+        const int logical = first + it * cus_per_xcd;
+        const int group_size = GM * tiles_n;
+        const int group = logical / group_size;
+        const int first_m = group * GM;
+        const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+        const int in_group = logical - group * group_size;
+        m0 = (first_m + in_group % gm) * BM;
+        n0 = (in_group / gm) * BN;
+    };
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -451,30 +302,35 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma4_kernel(const bf16_t* __res
     const int wm = wave >> 1, wn = wave & 1;
     const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
 
-    // waves 0-1 bring A rows [128w, 128w+128), waves 2-3 bring Wt rows [128(w-2), ...)
+    // ---- loads: waves 0-1 bring A rows [128w, 128w+128), waves 2-3 bring Wt rows [128(w-2), ...);
+    // one load = 8 rows.  roff[i] = byte offset of this lane's 16 bytes inside slice 0 of the tile whose
+    // slices are being requested (rows beyond the matrix are clamped: their products are never stored)
     const bool isA = wave < 2;
     const int row_base = (wave & 1) * 128;
-    const uint8_t* src[LPS];
+    const uint8_t* gbase = reinterpret_cast<const uint8_t*>(isA ? A : Wt);
+    const int ld = isA ? lda : K;
+    const int row_lim = isA ? M : N;
+    uint32_t roff[LPS];
+    auto set_roff = [&](int it) {
+        int m0, n0;
+        tile_origin(it < nt_local ? it : nt_local - 1, m0, n0);
+        const int row0 = isA ? m0 : n0;
 #pragma unroll
-    for (int i = 0; i < LPS; ++i) {
-        const int row = row_base + i * 16 + (lane >> 2);
-        const int kc = (lane & 3) ^ (((row >> 1) & 3) ^ ((row >> 3) & 1));
-        if (isA) {
-            int gr = m0 + row;
-            gr = gr < M ? gr : M - 1;
-            src[i] = reinterpret_cast<const uint8_t*>(A + (size_t)gr * lda + kc * 8);
-        } else {
-            int gr = n0 + row;
-            gr = gr < N ? gr : N - 1;
-            src[i] = reinterpret_cast<const uint8_t*>(Wt + (size_t)gr * K + kc * 8);
+        for (int i = 0; i < LPS; ++i) {
+            const int row = row_base + i * 8 + (lane >> 3);
+            const int kc = (lane & 7) ^ ((row >> 1) & 7);
+            int gr = row0 + row;
+            gr = gr < row_lim ? gr : row_lim - 1;
+            roff[i] = (uint32_t)gr * (uint32_t)ld * 2u + (uint32_t)kc * 16u;
         }
-    }
-    const uint32_t dst0 = lds_base + (isA ? 0 : BM * 64) + row_base * 64;
-    const int nk = K / 32;
-    auto issue1 = [&](int slice, int i) {
-        const int sl = slice < nk ? slice : nk - 1;
-        const uint32_t d = dst0 + (uint32_t)(slice % NS) * STAGE;
-        dma16(src[i] + (size_t)sl * 64, d + i * 1024);
+    };
+    const uint32_t dst0 = lds_base + (isA ? 0 : BM * 128) + row_base * 128;
+    const int nsl = K / 64;
+    const int g_last = nt_local * nsl - 1;       // last slice of this block's stream
+    auto issue1 = [&](int stage, int ksl, int i) {
+        const uint8_t* sb = gbase + (size_t)ksl * 128;
+        const uint32_t d = dst0 + (uint32_t)stage * STAGE + i * 1024;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(roff[i]), "s"(sb), "s"(d) : "memory");
     };
 
     f32x16_t acc[TM][TN];
@@ -486,339 +342,190 @@ __global__ __launch_bounds__(256) void gemm_mfma_dma4_kernel(const bf16_t* __res
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int lrow = lane & 31, lgrp = lane >> 5;
-    int a_off[TM][2], b_off[TN][2];
+    int koff[4];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) a_off[i][ks] = lds64_off(wm * 128 + i * 32 + lrow, ks * 2 + lgrp);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b_off[j][ks] = BM * 64 + lds64_off(wn * 128 + j * 32 + lrow, ks * 2 + lgrp);
-    }
+    for (int ks = 0; ks < 4; ++ks) koff[ks] = lrow * 128 + ((((ks * 2 + lgrp) ^ ((lrow >> 1) & 7))) << 4);
+    const int a_base = wm * 128 * 128, b_base = BM * 128 + wn * 128 * 128;
     bf16x8_t af[2][TM], bfr[2][TN];
-    auto read_frags = [&](const uint8_t* st, int ks) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) af[ks][i] = *reinterpret_cast<const bf16x8_t*>(st + a_off[i][ks]);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) bfr[ks][j] = *reinterpret_cast<const bf16x8_t*>(st + b_off[j][ks]);
+    // t-th of the 8 fragment reads of k-step ks (weight fragments first: the first MFMAs need them all)
+    auto read_one = [&](const uint8_t* st, int ks, int par, int t) {
+        if (t < 4) bfr[par][t] = *reinterpret_cast<const bf16x8_t*>(st + b_base + t * 4096 + koff[ks]);
+        else af[par][t - 4] = *reinterpret_cast<const bf16x8_t*>(st + a_base + (t - 4) * 4096 + koff[ks]);
     };
-    auto mfma_row = [&](int ks, int i) {
+    // 16 MFMAs on fragment set `par`; behind them the reads of k-step rks of stage rst into the other set
+    // and, when n_loads == 8, loads first_op .. first_op+7 of k-slice ksl into ring stage `stage`
+    auto mfma_step = [&](int par, const uint8_t* rst, int rks, int n_loads, bool enable, int stage, int ksl,
+                         int first_op) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks][i], bfr[ks][j], acc[i][j], 0, 0, 0);
+        for (int t = 0; t < 16; ++t) {
+            const int q = t >> 2, j = t & 3;
+            acc[q][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[par][j], af[par][q], acc[q][j], 0, 0, 0);
+            if (t < 8) {
+                __builtin_amdgcn_sched_barrier(0);
+                read_one(rst, rks, par ^ 1, t);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (n_loads == 8 && (t & 1)) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (enable) issue1(stage, ksl, first_op + (t >> 1));
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
     };
 
-    // same pipeline as the eight-wave kernel ([A] / [B] / [C] per slice), 8 loads per wave per slice
+    // ---- epilogue of one tile: per block of 32 tokens and 64 output columns, fp32 staging [32][64]
+    // (row stride 256 B, 16-byte chunk index XORed with the row), then 8 consecutive columns per lane
+    float* stg = reinterpret_cast<float*>(smem + 2 * STAGE + wave * 8192);
+    auto epilogue = [&](int it) {
+        int m0, n0;
+        tile_origin(it, m0, n0);
+        constexpr int NH = (EPI == EPI_SWIGLU) ? 1 : 2;        // passes per token block
+        const int n_out = (EPI == EPI_SWIGLU) ? (N >> 1) : N;
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
+        for (int q = 0; q < TM; ++q)
 #pragma unroll
-        for (int i = 0; i < LPS; ++i) issue1(s, i);
-    __builtin_amdgcn_s_waitcnt(VmcntImm<LPS * (NS - 2)>::value);
+            for (int h = 0; h < NH; ++h) {
+                // lane holds token lrow and columns 32 jj + 8 a + 4 lgrp + (0..3) of accumulator tile jj
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        f32x4_t o;
+                        if (EPI == EPI_SWIGLU) {       // tiles 0, 2 hold gate blocks, tiles 1, 3 the matching up blocks
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float g = acc[q][2 * jj][4 * a + e], u = acc[q][2 * jj + 1][4 * a + e];
+                                o[e] = g / (1.0f + __expf(-g)) * u;
+                            }
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = acc[q][2 * h + jj][4 * a + e];
+                        }
+                        const int c = jj * 8 + a * 2 + lgrp;
+                        *reinterpret_cast<f32x4_t*>(stg + lrow * 64 + ((c ^ (lrow & 15)) << 2)) = o;
+                    }
+                const int oc0 = (EPI == EPI_SWIGLU) ? ((n0 + wn * 128) >> 1) : (n0 + wn * 128 + 64 * h);
+#pragma unroll
+                for (int r8 = 0; r8 < 4; ++r8) {
+                    const int row = r8 * 8 + (lane >> 3);
+                    const int g8 = lane & 7;
+                    const f32x4_t lo = *reinterpret_cast<const f32x4_t*>(stg + row * 64 + (((2 * g8) ^ (row & 15)) << 2));
+                    const f32x4_t hi = *reinterpret_cast<const f32x4_t*>(stg + row * 64 + (((2 * g8 + 1) ^ (row & 15)) << 2));
+                    const int gr = m0 + wm * 128 + q * 32 + row;
+                    const int gc = oc0 + g8 * 8;
+                    if (gr < M && gc < n_out) {
+                        float o[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        if (EPI == EPI_RESIDUAL) {
+                            const u32x4_t rv = *reinterpret_cast<const u32x4_t*>(R + (size_t)gr * ldc + gc);
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                o[2 * e] += __uint_as_float(rv[e] << 16);
+                                o[2 * e + 1] += __uint_as_float(rv[e] & 0xffff0000u);
+                            }
+                        }
+                        u32x4_t pv;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) pv[e] = pack_bf16x2(o[2 * e], o[2 * e + 1]);
+                        __builtin_nontemporal_store(pv, reinterpret_cast<u32x4_t*>(C + (size_t)gr * ldc + gc));
+                    }
+                }
+            }
+    };
+
+    // ---- prologue: slices 0 and 1 of the first tile (K >= 128)
+    set_roff(0);
+#pragma unroll
+    for (int i = 0; i < LPS; ++i) issue1(0, 0, i);
+#pragma unroll
+    for (int i = 0; i < LPS; ++i) issue1(1, 1, i);
+    __builtin_amdgcn_s_waitcnt(VmcntImm<LPS>::value);        // slice 0 has landed
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) issue1(NS - 1, i);
-    read_frags(smem, 0);
-    for (int kt = 0; kt < nk; ++kt) {
-        const uint8_t* st = smem + (kt % NS) * STAGE;
-        const uint8_t* stn = smem + ((kt + 1) % NS) * STAGE;
-        read_frags(st, 1);                                   // [A]
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            mfma_row(0, q);
+    for (int t = 0; t < 8; ++t) read_one(smem, 0, 0, t);
+
+    int g = 0;                                   // slice counter of this block's stream
+    for (int it = 0; it < nt_local; ++it) {
+        for (int s = 0; s < nsl; ++s, ++g) {
+            const uint8_t* st = smem + (g & 1) * STAGE;
+            const uint8_t* stn = smem + ((g + 1) & 1) * STAGE;
+            // k-step 0 requests the second half of stream slice g+1, k-step 3 the first half of g+2;
+            // requests past the end of the stream repeat its last slice into the stage that is free then
+            int k1 = s + 1, k2 = s + 2;
+            if (k1 >= nsl) k1 -= nsl;
+            if (k2 >= nsl) k2 -= nsl;
+            if (g + 1 > g_last) k1 = nsl - 1;
+            if (g + 2 > g_last) k2 = nsl - 1;
+            mfma_step(0, st, 1, 8, g > 0, (g + 1) & 1, k1, 8);
             __builtin_amdgcn_sched_barrier(0);
-            issue1(kt + NS - 1, 4 + q);
-        }
-        __builtin_amdgcn_s_waitcnt(VmcntImm<LPS * (NS - 2)>::value);   // [B]
-        __builtin_amdgcn_s_waitcnt(0xC07F);
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(stn, 0);                                  // [C]
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            issue1(kt + NS, q);
-            mfma_row(1, q);
+            mfma_step(1, st, 2, 0, false, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(0, st, 3, 0, false, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (s == nsl - 2) set_roff(it + 1);              // from here on the requests belong to the next tile
+            __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): the fragments of k-step 3 are in registers
+            __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): own loads of slice g+1 have landed
+            __builtin_amdgcn_s_barrier();                    // ... everyone's; nobody reads stage g any more
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_step(1, stn, 0, 8, true, g & 1, k2, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-
-    const int col_in = lane & 31;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int rbase = m0 + wm * 128 + i * 32 + 4 * lgrp;
-        if (EPI == EPI_SWIGLU) {
-#pragma unroll
-            for (int j = 0; j < TN; j += 2) {
-                const int nb = n0 + wn * 128 + j * 32;
-                const int oc = (nb >> 1) + col_in;
-                if (nb + col_in >= N) continue;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int r = rbase + 8 * (v >> 2) + (v & 3);
-                    if (r >= M) continue;
-                    const float g = acc[i][j][v], u = acc[i][j + 1][v];
-                    C[(size_t)r * ldc + oc] = f2bf(g / (1.0f + __expf(-g)) * u);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int c = n0 + wn * 128 + j * 32 + col_in;
-                if (c >= N) continue;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int r = rbase + 8 * (v >> 2) + (v & 3);
-                    if (r >= M) continue;
-                    float o = acc[i][j][v];
-                    if (EPI == EPI_RESIDUAL) o += bf2f(R[(size_t)r * ldc + c]);
-                    C[(size_t)r * ldc + c] = f2bf(o);
-                }
-            }
-        }
-    }
-}
-
-template <int NS>
-static hipError_t launch_dma4(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
-                              int N, int K, int epi, hipStream_t s) {
-    constexpr size_t LDS = (size_t)NS * 512 * 64;
-    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
-    const long long n_tiles = (long long)tiles_m * tiles_n;
-    if (n_tiles > (1ll << 30) || K % 32 != 0) return hipErrorInvalidValue;
-    const int per_xcd = (int)((n_tiles + 7) / 8);
-    const unsigned grid = (unsigned)per_xcd * 8;
-#define SS_LAUNCH(E)                                                                                            \
-    {                                                                                                           \
-        auto kfn = gemm_mfma_dma4_kernel<E, NS>;                                                                \
-        static bool attr_set = false;                                                                           \
-        if (!attr_set) {                                                                                        \
-            hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS); \
-            if (e != hipSuccess) return e;                                                                      \
-            attr_set = true;                                                                                    \
-        }                                                                                                       \
-        kfn<<<grid, 256, LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd);                  \
-    }
-    switch (epi) {
-        case EPI_STORE: SS_LAUNCH(EPI_STORE) break;
-        case EPI_RESIDUAL:
-            if (!R) return hipErrorInvalidValue;
-            SS_LAUNCH(EPI_RESIDUAL) break;
-        case EPI_SWIGLU: SS_LAUNCH(EPI_SWIGLU) break;
-        default: return hipErrorInvalidValue;
-    }
-#undef SS_LAUNCH
-    return hipGetLastError();
-}
-
-
-// Variant with K slices of 64 (128-byte LDS rows, full cache lines per request) and two ring stages
-// of 64 KB: half as many barriers and DMA instructions per flop as the 32-wide ring.  Four MFMA groups
-// per slice; the barrier that publishes slice kt+1 and frees slice kt's stage sits before the last
-// group, whose MFMAs run while slice kt+2 is requested.
-template <int EPI>
-__global__ __launch_bounds__(512) void gemm_mfma_dma64_kernel(const bf16_t* __restrict__ A, int lda,
-                                                              const bf16_t* __restrict__ Wt, bf16_t* __restrict__ C,
-                                                              int ldc, const bf16_t* __restrict__ R, int M, int N, int K,
-                                                              int tiles_m, int tiles_n, int per_xcd) {
-    constexpr int BM = 256, BN = 256, WN = 4, TM = 4, TN = 2;
-    constexpr int STAGE = (BM + BN) * 128;
-    constexpr int LPS = 8;
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-
-    const int xcd = blockIdx.x & 7;
-    const int logical = xcd * per_xcd + (blockIdx.x >> 3);
-    if ((blockIdx.x >> 3) >= per_xcd || logical >= tiles_m * tiles_n) return;
-    constexpr int GM = 8;
-    const int group_size = GM * tiles_n;
-    const int group = logical / group_size;
-    const int first_m = group * GM;
-    const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
-    const int in_group = logical - group * group_size;
-    const int m0 = (first_m + in_group % gm) * BM, n0 = (in_group / gm) * BN;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
-    const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
-
-    // waves 0-3 bring A rows [64w, 64w+64), waves 4-7 bring Wt rows; a wave-level load covers 8 rows of 128 bytes
-    const bool isA = wave < 4;
-    const int row_base = (wave & 3) * 64;
-    const uint8_t* src[LPS];
-#pragma unroll
-    for (int i = 0; i < LPS; ++i) {
-        const int row = row_base + i * 8 + (lane >> 3);
-        const int kc = (lane & 7) ^ ((row & 7) ^ ((row >> 3) & 1));
-        if (isA) {
-            int gr = m0 + row;
-            gr = gr < M ? gr : M - 1;
-            src[i] = reinterpret_cast<const uint8_t*>(A + (size_t)gr * lda + kc * 8);
-        } else {
-            int gr = n0 + row;
-            gr = gr < N ? gr : N - 1;
-            src[i] = reinterpret_cast<const uint8_t*>(Wt + (size_t)gr * K + kc * 8);
-        }
-    }
-    const uint32_t dst0 = lds_base + (isA ? 0 : BM * 128) + row_base * 128;
-    const int nk = K / 64;
-    auto issue1 = [&](int slice, int i) {
-        const int sl = slice < nk ? slice : nk - 1;
-        const uint32_t d = dst0 + (uint32_t)(slice & 1) * STAGE;
-        dma16(src[i] + (size_t)sl * 128, d + i * 1024);
-    };
-
-    f32x16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    const int lrow = lane & 31, lgrp = lane >> 5;
-    bf16x8_t af[2][TM], bfr[2][TN];
-    auto read_frags = [&](const uint8_t* st, int ks) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-            af[ks & 1][i] = *reinterpret_cast<const bf16x8_t*>(st + lds_chunk_off(wm * 128 + i * 32 + lrow, ks * 2 + lgrp));
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-            bfr[ks & 1][j] = *reinterpret_cast<const bf16x8_t*>(st + BM * 128 + lds_chunk_off(wn * 64 + j * 32 + lrow, ks * 2 + lgrp));
-    };
-    auto mfma_group = [&](int ks) {
+        epilogue(it);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
-    };
-
 #pragma unroll
-    for (int i = 0; i < LPS; ++i) issue1(0, i);
-#pragma unroll
-    for (int i = 0; i < LPS; ++i) issue1(1, i);
-    __builtin_amdgcn_s_waitcnt(VmcntImm<LPS>::value);      // slice 0 landed
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(smem, 0);
-    for (int kt = 0; kt < nk; ++kt) {
-        const uint8_t* st = smem + (kt & 1) * STAGE;
-        const uint8_t* stn = smem + ((kt + 1) & 1) * STAGE;
-#pragma unroll
-        for (int ks = 0; ks < 3; ++ks) {
-            read_frags(st, ks + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_group(ks);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): slice kt+1 has landed
-        __builtin_amdgcn_s_waitcnt(0xC07F);                  // lgkmcnt(0): the last fragments of slice kt are in registers
-        __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(stn, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        // last group of the slice, with the requests for slice kt+2 (into the stage just freed) between its MFMAs
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                issue1(kt + 2, i * TN + j);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][i], bfr[1][j], acc[i][j], 0, 0, 0);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-
-    const int col_in = lane & 31;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int rbase = m0 + wm * 128 + i * 32 + 4 * lgrp;
-        if (EPI == EPI_SWIGLU) {
-#pragma unroll
-            for (int j = 0; j < TN; j += 2) {
-                const int nb = n0 + wn * 64 + j * 32;
-                const int oc = (nb >> 1) + col_in;
-                if (nb + col_in >= N) continue;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int r = rbase + 8 * (v >> 2) + (v & 3);
-                    if (r >= M) continue;
-                    const float g = acc[i][j][v], u = acc[i][j + 1][v];
-                    C[(size_t)r * ldc + oc] = f2bf(g / (1.0f + __expf(-g)) * u);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int c = n0 + wn * 64 + j * 32 + col_in;
-                if (c >= N) continue;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int r = rbase + 8 * (v >> 2) + (v & 3);
-                    if (r >= M) continue;
-                    float o = acc[i][j][v];
-                    if (EPI == EPI_RESIDUAL) o += bf2f(R[(size_t)r * ldc + c]);
-                    C[(size_t)r * ldc + c] = f2bf(o);
-                }
-            }
-        }
-    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // the repeats requested past the end
 }
 
-static hipError_t launch_dma64(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
-                               int N, int K, int epi, hipStream_t s) {
-    constexpr size_t LDS = (size_t)2 * 512 * 128;
+constexpr size_t STREAM_LDS = (size_t)2 * 512 * 128 + 4 * 8192;     // ring + staging = 160 KB
+
+bool gemm_mfma_stream_supported(const void* C, const void* R, int ldc, int M, int N, int K, int lda, int epi) {
+    if (K % 64 != 0 || K < 128 || N % 16 != 0 || ldc % 8 != 0) return false;
+    if (((uintptr_t)C & 15) != 0 || (epi == EPI_RESIDUAL && ((uintptr_t)R & 15) != 0)) return false;
+    // 32-bit byte offsets inside the operands
+    if ((long long)M * lda * 2 >= (1ll << 32) || (long long)N * K * 2 >= (1ll << 32)) return false;
+    return true;
+}
+
+// Blocks of the persistent kernel own their CU (all registers, all LDS) until they are done, so a kernel
+// of another stream can only start at a launch boundary.  `max_rounds` > 0 cuts the walk into launches
+// of at most that many tiles per block, for callers that have latency-bound work on other streams.
+static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
+                                int N, int K, int epi, hipStream_t s, int max_rounds) {
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     const long long n_tiles = (long long)tiles_m * tiles_n;
-    if (n_tiles > (1ll << 30) || K % 64 != 0) return hipErrorInvalidValue;
+    if (n_tiles > (1ll << 30)) return hipErrorInvalidValue;
+    static int n_cus = 0;
+    if (!n_cus) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        e = hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        if (n_cus < 8) n_cus = 8;
+    }
     const int per_xcd = (int)((n_tiles + 7) / 8);
-    const unsigned grid = (unsigned)per_xcd * 8;
+    const int cus_per_xcd = n_cus / 8;
+    const unsigned grid = 8 * (unsigned)(per_xcd < cus_per_xcd ? per_xcd : cus_per_xcd);
+    const int rounds_total = (per_xcd + cus_per_xcd - 1) / cus_per_xcd;
+    const int step = max_rounds > 0 ? max_rounds : rounds_total;
 #define SS_LAUNCH(E)                                                                                            \
     {                                                                                                           \
-        auto kfn = gemm_mfma_dma64_kernel<E>;                                                                   \
+        auto kfn = gemm_mfma_stream_kernel<E>;                                                                  \
         static bool attr_set = false;                                                                           \
         if (!attr_set) {                                                                                        \
-            hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS); \
+            hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize,   \
+                                               (int)STREAM_LDS);                                                \
             if (e != hipSuccess) return e;                                                                      \
             attr_set = true;                                                                                    \
         }                                                                                                       \
-        kfn<<<grid, 512, LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd);                  \
-    }
-    switch (epi) {
-        case EPI_STORE: SS_LAUNCH(EPI_STORE) break;
-        case EPI_RESIDUAL:
-            if (!R) return hipErrorInvalidValue;
-            SS_LAUNCH(EPI_RESIDUAL) break;
-        case EPI_SWIGLU: SS_LAUNCH(EPI_SWIGLU) break;
-        default: return hipErrorInvalidValue;
-    }
-#undef SS_LAUNCH
-    return hipGetLastError();
-}
-
-template <int NS, int PROBE = 0>
-static hipError_t launch_dma(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
-                             int N, int K, int epi, hipStream_t s) {
-    constexpr size_t LDS = (size_t)NS * 512 * 64;
-    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
-    const long long n_tiles = (long long)tiles_m * tiles_n;
-    if (n_tiles > (1ll << 30) || K % 32 != 0) return hipErrorInvalidValue;
-    const int per_xcd = (int)((n_tiles + 7) / 8);
-    const unsigned grid = (unsigned)per_xcd * 8;
-#define SS_LAUNCH(E)                                                                                            \
-    {                                                                                                           \
-        auto kfn = gemm_mfma_dma_kernel<E, NS, PROBE>;                                                                 \
-        static bool attr_set = false;                                                                           \
-        if (!attr_set) {                                                                                        \
-            hipError_t e = hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS); \
-            if (e != hipSuccess) return e;                                                                      \
-            attr_set = true;                                                                                    \
-        }                                                                                                       \
-        kfn<<<grid, 512, LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd);                  \
+        for (int it0 = 0; it0 < rounds_total; it0 += step)                                                      \
+            kfn<<<grid, 256, STREAM_LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd,        \
+                                              cus_per_xcd, it0, step);                                          \
     }
     switch (epi) {
         case EPI_STORE: SS_LAUNCH(EPI_STORE) break;
@@ -912,16 +619,17 @@ static hipError_t launch_cfg(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t*
 }
 
 hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int ldc, const void* R, int M, int N,
-                          int K, int epi, hipStream_t s, float* ws, size_t ws_bytes) {
+                          int K, int epi, hipStream_t s, float* ws, size_t ws_bytes, int max_rounds) {
     const bf16_t* a = (const bf16_t*)A;
     const bf16_t* w = (const bf16_t*)Wt;
     bf16_t* c = (bf16_t*)C;
     const bf16_t* r = (const bf16_t*)R;
-    // Prefill-sized outputs: the 256 x 256 direct-to-LDS kernel.  Smaller outputs (decode batches)
-    // are bound by streaming the weights: 128 x 128 tiles with split-K (partials in fp32, summed by a
-    // small second kernel).
+    // Prefill-sized outputs (at least one 256 x 256 tile per CU): the persistent direct-to-LDS kernel.
+    // Smaller outputs (decode batches) are bound by streaming the weights: 128 x 128 tiles with split-K
+    // (partials in fp32, summed by a small second kernel).
     const long long big = (long long)((M + 255) / 256) * ((N + 255) / 256);
-    if (big >= 512) return launch_dma<4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
+    if (big >= 256 && gemm_mfma_stream_supported(C, R, ldc, M, N, K, lda, epi))
+        return launch_stream(a, lda, w, c, ldc, r, M, N, K, epi, s, max_rounds);
     const long long mid = (long long)((M + 127) / 128) * ((N + 127) / 128);
     // split K until every CU has a block, but only while the fp32 partials (8*S*M*N bytes written and
     // read back) stay below the weight bytes (2*N*K) they help to stream: S <= K / (4 M)
@@ -932,32 +640,4 @@ hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int l
     return launch_cfg<128, 128, 2, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s, split, ws);
 }
 
-}  // namespace ssk
-
-// Tuning hook (not part of the C ABI): run one named tile configuration.
-namespace ssk {
-hipError_t gemm_mfma_bf16_cfg(int cfg, const void* A, int lda, const void* Wt, void* C, int ldc, const void* R,
-                              int M, int N, int K, int epi, hipStream_t s, int ksplit, float* ws) {
-    const bf16_t* a = (const bf16_t*)A;
-    const bf16_t* w = (const bf16_t*)Wt;
-    bf16_t* c = (bf16_t*)C;
-    const bf16_t* r = (const bf16_t*)R;
-    switch (cfg) {
-        case 0: return launch_cfg<256, 256, 2, 4>(a, lda, w, c, ldc, r, M, N, K, epi, s, ksplit, ws);
-        case 1: return launch_cfg<128, 128, 2, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s, ksplit, ws);
-        case 2: return launch_cfg<64, 64, 2, 1>(a, lda, w, c, ldc, r, M, N, K, epi, s, ksplit, ws);
-        case 3: return launch_dma<4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-        case 4: return launch_dma<5>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-        case 5: return launch_dma<3>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-        case 6: return launch_dma<4, 1>(a, lda, w, c, ldc, r, M, N, K, epi, s);   // timing probes: wrong results
-        case 7: return launch_dma<4, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-        case 8: return launch_dma<4, 3>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-        case 9: return launch_dma<4, 4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-        case 10: return launch_dma<4, 8>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-        case 11: return launch_dma4<4>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-        case 13: return launch_dma64(a, lda, w, c, ldc, r, M, N, K, epi, s);
-        case 12: return launch_dma4<3>(a, lda, w, c, ldc, r, M, N, K, epi, s);
-        default: return hipErrorInvalidValue;
-    }
-}
 }  // namespace ssk

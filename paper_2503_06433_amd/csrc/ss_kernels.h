@@ -25,9 +25,12 @@ enum Epilogue {
 // otherwise bf16 with K % 64 == 0 runs on the MFMA kernel.
 // `ws` is an optional float workspace of ws_bytes for split-K partial sums (used
 // when the output has too few tiles to occupy the chip, as at decode batch sizes).
+// The large-output bf16 kernel runs as persistent blocks that own their CUs until the launch is done;
+// max_rounds > 0 cuts it into launches of at most that many output tiles per block, so that kernels of
+// other streams (the KV movers' repack kernels) get the chip at the boundaries; 0 = one launch.
 hipError_t gemm_nt(int dt, const void* A, int lda, const void* Wt, void* C, int ldc,
                    const void* R, int M, int N, int K, int epi, bool force_generic,
-                   hipStream_t s, float* ws = nullptr, size_t ws_bytes = 0);
+                   hipStream_t s, float* ws = nullptr, size_t ws_bytes = 0, int max_rounds = 0);
 
 // out[t,:] = x[t,:] * rsqrt(mean(x[t,:]^2) + eps) * g
 hipError_t rmsnorm(int dt, const void* x, const void* g, void* out, int T, int H, float eps,

@@ -128,6 +128,8 @@ struct ss_ctx {
     int dt = 0;
     size_t es = 2;
     bool force_generic = false;
+    int gemm_rounds_busy = 4;                    // GEMM launch granularity while mover jobs are pending
+    int gemm_rounds = 0;                         // ... of the layer call in progress (0 = one launch)
     int copy_threads = 4;
     bool trace_mover = false;
     std::string err;
@@ -513,7 +515,7 @@ int run_attn_phase(ss_ctx* c, Shard* s, int ll, const ss_batch* b, bool decode, 
     {
         ProfScope ps(c, 0, st);
         K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, H, w.wqkv_t, c->ws_qkv.p, nqkv, nullptr, T, nqkv, H, ssk::EPI_STORE,
-                              c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
+                              c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
     }
     {
         ProfScope ps(c, 4, st);
@@ -531,7 +533,7 @@ int run_attn_phase(ss_ctx* c, Shard* s, int ll, const ss_batch* b, bool decode, 
     {
         ProfScope ps(c, 0, st);
         K_TRY(c, ssk::gemm_nt(c->dt, c->ws_attn.p, s->nq_l * d, w.wo_t, out, H, residual ? x_in : nullptr, T, H,
-                              s->nq_l * d, residual ? ssk::EPI_RESIDUAL : ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
+                              s->nq_l * d, residual ? ssk::EPI_RESIDUAL : ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
     }
     return mark_meta_used(c, ms, st);
 }
@@ -551,13 +553,13 @@ int run_mlp_phase(ss_ctx* c, Shard* s, int ll, int T, const void* x1, void* out,
     if (w.gu_interleaved) {
         ProfScope ps(c, 0, st);
         K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, H, w.wgu_t, c->ws_act.p, F, nullptr, T, 2 * F, H, ssk::EPI_SWIGLU,
-                              false, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
+                              false, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
     } else {
         if ((rc = ensure_buf(c, c->ws_gu, (size_t)T * 2 * F * c->es))) return rc;
         {
             ProfScope ps(c, 0, st);
             K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, H, w.wgu_t, c->ws_gu.p, 2 * F, nullptr, T, 2 * F, H,
-                                  ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
+                                  ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
         }
         ProfScope ps(c, 4, st);
         K_TRY(c, ssk::swiglu(c->dt, c->ws_gu.p, c->ws_act.p, T, F, st));
@@ -565,7 +567,7 @@ int run_mlp_phase(ss_ctx* c, Shard* s, int ll, int T, const void* x1, void* out,
     {
         ProfScope ps(c, 0, st);
         K_TRY(c, ssk::gemm_nt(c->dt, c->ws_act.p, F, w.wd_t, out, H, residual ? x1 : nullptr, T, H, F,
-                              residual ? ssk::EPI_RESIDUAL : ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
+                              residual ? ssk::EPI_RESIDUAL : ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
     }
     return SS_OK;
 }
@@ -593,6 +595,10 @@ int layer_call(ss_ctx* c, const ss_shard_desc* d, int layer, int phase, const ss
     hipStream_t st = (hipStream_t)stream;
     int64_t T = 0;
     for (int i = 0; i < b->n_seqs; ++i) T += b->q_lens[i];
+    {   // the movers' repack kernels need launch boundaries to get onto the chip between persistent GEMM blocks
+        std::lock_guard<std::mutex> lk(c->mu);
+        c->gemm_rounds = c->jobs_done < c->jobs_issued ? c->gemm_rounds_busy : 0;
+    }
     if (ph == SS_ATTN) return run_attn_phase(c, s, ll, b, decode, x_in, out, residual, st);
     if (ph == SS_MLP) {
         if (T <= 0 || T > (1 << 30)) return fail(c, SS_EINVAL, "bad token count");
@@ -985,6 +991,7 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
     const char* fg = getenv("SS_FORCE_GENERIC");
     c->force_generic = fg && fg[0] == '1';
     c->trace_mover = getenv("SS_TRACE_MOVER") != nullptr;
+    if (const char* gr = getenv("SS_GEMM_ROUNDS")) c->gemm_rounds_busy = std::max(0, atoi(gr));
     if (const char* ct = getenv("SS_COPY_THREADS")) c->copy_threads = std::max(1, std::min(16, atoi(ct)));
     int rc = SS_OK;
     auto boot = [&]() -> int {
