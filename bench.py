@@ -90,6 +90,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-reshard", action="store_true", help="leave the KV re-shard out of the step")
+    ap.add_argument("--pinned-mb", type=int, default=256, help="pinned staging ring of the KV movers (two lanes x two slots)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -123,7 +124,7 @@ def main():
     N_SETS = 3
     pages = sum(-(-(n + 1) // 16) for n in d_lens) + N_SETS * sum(-(-n // 16) for n in p_lens) + 64
     tier_bytes = N_SETS * Tp * kv_tok_bytes * cfg.n_layers + (1 << 20)
-    ctx = hz.make_context(cfg, pages=pages, tier_bytes=tier_bytes, pinned_bytes=256 << 20, max_seq_len=4096)
+    ctx = hz.make_context(cfg, pages=pages, tier_bytes=tier_bytes, pinned_bytes=args.pinned_mb << 20, max_seq_len=4096)
     vals, raws = wl.make_layer_weights(cfg, 2001)
     pp = hz.pp_desc(cfg)
     tp = hz.tp_desc(cfg, 1, 0)

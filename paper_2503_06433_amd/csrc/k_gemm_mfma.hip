@@ -213,43 +213,49 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
 // ----------------------------------------------------------------------------
 // Large-output kernel: persistent, direct global->LDS loads, two-stage ring.
 //
-// One block (4 waves, 2 x 2, wave tile 128 x 128, 256 fp32 accumulators per lane)
-// per CU walks that CU's share of the 256 x 256 output tiles.  K is cut in slices
-// of 64: a row of a slice is one 128-byte line, so every request to L2 moves a
-// whole line (slices of 32 ask for every line twice, and the number of requests,
-// not their bytes, is what the L2 channels run out of).  `global_load_lds_dwordx4`
-// moves 16 bytes per lane straight into LDS (lane j of a wave lands at
-// M0 + 16*j): no registers are spent on staging.  The ring has two stages of
-// 64 KB and runs on across tile boundaries, so the first slices of the next tile
-// are already in flight while the current tile is finished and written out.
+// One block (4 waves, 2 x 2, wave tile 128 x 128 = 8 x 8 tiles of v_mfma_f32_16x16x32_bf16,
+// 256 fp32 accumulators per lane) per CU walks that CU's share of the 256 x 256 output
+// tiles.  Under the chip's power limit the 16x16x32 shape sustains 10-20 % more than
+// 32x32x16 on random data (half the accumulator traffic per flop).  Its operand layout:
+// lane l supplies row (l % 16) of the row operand / column (l % 16) of the column operand
+// with the 8 k-values of group (l / 16); accumulator register v of lane l is
+// D[4*(l/16) + v][l % 16].
 //
-// Per slice (4 k-steps of 16 MFMAs per wave):
-//   k-steps 0..2  multiply out of the current stage; the fragments of the next
-//                 k-step are read one at a time behind the first 8 MFMAs (a burst
-//                 of 8 reads fills the LDS command queue and holds up the MFMAs
-//                 issued behind it)
-//   k-step 3      wait until the own loads of the next slice have landed, barrier
-//                 (the next stage is complete, the current one is free), then
-//                 request the slice after the next into the freed stage: 8 loads
-//                 per wave here and 8 in k-step 0 of the next slice, one behind
-//                 every other MFMA (the L1 -> LDS path moves 64 bytes per clock, a
-//                 64 KB slice keeps it busy for half of the slice's MFMA time;
-//                 requests queued faster than that stall the issuing wave)
-// Completion is tracked with vmcnt by hand (the loads are issued from inline
-// asm), and a bare s_barrier publishes a stage; only loads of this one kind are
-// in flight, so they complete in issue order.
+// K is cut in slices of 64: a row of a slice is one 128-byte line, so every request to L2
+// moves a whole line (slices of 32 ask for every line twice, and the number of requests,
+// not their bytes, is what the L2 channels run out of).  `global_load_lds_dwordx4` moves
+// 16 bytes per lane straight into LDS (lane j of a wave lands at M0 + 16*j): no registers
+// are spent on staging.  The ring has two stages of 64 KB and runs on across tile
+// boundaries, so the first slices of the next tile are already in flight while the current
+// tile is finished and written out.
 //
-// LDS rows are 128 bytes (8 chunks of 16 bytes); chunk position = kc ^ ((row>>1)&7),
-// which spreads the 16 rows that one pass of a fragment read touches over all
-// banks.  A wave-level load covers 8 consecutive rows: lane j supplies row j/8,
-// position j%8, and therefore fetches global chunk (j%8) ^ ((row>>1)&7).
+// Per slice (2 k-steps of 32, 64 MFMAs per wave each):
+//   k-step 0  multiply out of the current stage; the 16 fragments of k-step 1 are read one
+//             at a time behind every other one of the first 32 MFMAs (a burst of reads
+//             fills the LDS command queue and holds up the MFMAs issued behind it)
+//   k-step 1  wait until the own loads of the next slice have landed, barrier (the next
+//             stage is complete, the current one is free), then request the slice after
+//             the next into the freed stage: 16 loads per wave, one behind every 4th MFMA
+//             (the L1 -> LDS path moves 64 bytes per clock, a 64 KB slice keeps it busy for
+//             half of the slice's MFMA time; requests queued faster than that stall the
+//             issuing wave), and read the fragments of the next slice's k-step 0
+// Completion is tracked with vmcnt by hand (the loads are issued from inline asm), and a
+// bare s_barrier publishes a stage; only loads of this one kind are in flight in the main
+// loop, so they complete in issue order.  The MFMAs are inline asm too, with the
+// accumulators constrained to the accumulation registers: left to itself the register
+// allocator moves accumulators between the two register files inside the loop in some
+// instantiations.
 //
-// The product is formed transposed (weight fragment as the row operand): a lane
-// ends up with 4 consecutive output columns of one token, which go through an
-// 8 KB per wave fp32 staging tile (outside the ring) to come out as 16-byte,
-// full-line stores.  Outputs are written with the nontemporal hint: they are
-// not read again by this kernel and would otherwise push the operand slices
-// out of L2.
+// LDS rows are 128 bytes (8 chunks of 16 bytes); chunk position = kc ^ ((row>>1)&7), which
+// spreads the 16 rows that one pass of a fragment read touches over all banks.  A
+// wave-level load covers 8 consecutive rows: lane j supplies row j/8, position j%8, and
+// therefore fetches global chunk (j%8) ^ ((row>>1)&7).
+//
+// The product is formed transposed (weight fragment as the row operand): a lane ends up
+// with 4 consecutive output columns of one token, which go through an 8 KB per wave fp32
+// staging tile (outside the ring) to come out as 16-byte, full-line stores.  Outputs are
+// written with the nontemporal hint: they are not read again by this kernel and would
+// otherwise push the operand slices out of L2.
 // ----------------------------------------------------------------------------
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 template <int V> struct VmcntImm { static constexpr int value = (V & 15) | ((V >> 4) << 14) | 0x0F70; };
@@ -267,7 +273,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
                                                                int ldc, const bf16_t* __restrict__ R, int M, int N,
                                                                int K, int tiles_m, int tiles_n, int per_xcd,
                                                                int cus_per_xcd, int it0, int max_it) {
-    constexpr int BM = 256, BN = 256, TM = 4, TN = 4;
+    constexpr int BM = 256, BN = 256;
     constexpr int STAGE = (BM + BN) * 128;       // bytes per ring stage
     constexpr int LPS = 16;                      // loads per wave per slice
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -333,153 +339,189 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(roff[i]), "s"(sb), "s"(d) : "memory");
     };
 
-    f32x16_t acc[TM][TN];
+    f32x4_t acc[8][8];       // [n tile][m tile] of 16 x 16
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < 8; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
 
-    const int lrow = lane & 31, lgrp = lane >> 5;
-    int koff[4];
+    // fragment of a 16-row tile: lane supplies row l % 16, 16-byte chunk 4 ks + l / 16 of the 128-byte row
+    const int l16 = lane & 15, lk = lane >> 4;
+    int koff[2];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) koff[ks] = lrow * 128 + ((((ks * 2 + lgrp) ^ ((lrow >> 1) & 7))) << 4);
+    for (int ks = 0; ks < 2; ++ks) koff[ks] = l16 * 128 + ((((ks * 4 + lk) ^ ((l16 >> 1) & 7))) << 4);
     const int a_base = wm * 128 * 128, b_base = BM * 128 + wn * 128 * 128;
-    bf16x8_t af[2][TM], bfr[2][TN];
-    // t-th of the 8 fragment reads of k-step ks (weight fragments first: the first MFMAs need them all)
+    bf16x8_t af[2][8], bfr[2][8];
+    // t-th of the 16 fragment reads of a k-step: token fragments first (the first MFMAs need them all)
     auto read_one = [&](const uint8_t* st, int ks, int par, int t) {
-        if (t < 4) bfr[par][t] = *reinterpret_cast<const bf16x8_t*>(st + b_base + t * 4096 + koff[ks]);
-        else af[par][t - 4] = *reinterpret_cast<const bf16x8_t*>(st + a_base + (t - 4) * 4096 + koff[ks]);
+        if (t < 8) af[par][t] = *reinterpret_cast<const bf16x8_t*>(st + a_base + t * 2048 + koff[ks]);
+        else bfr[par][t - 8] = *reinterpret_cast<const bf16x8_t*>(st + b_base + (t - 8) * 2048 + koff[ks]);
     };
-    // 16 MFMAs on fragment set `par`; behind them the reads of k-step rks of stage rst into the other set
-    // and, when n_loads == 8, loads first_op .. first_op+7 of k-slice ksl into ring stage `stage`
-    auto mfma_step = [&](int par, const uint8_t* rst, int rks, int n_loads, bool enable, int stage, int ksl,
-                         int first_op) {
+    // 64 MFMAs on set `par`; behind every other one of the first 32 a fragment read of (rst, rks) into the other
+    // set; when `loads`, one load behind every 4th MFMA
+    auto mfma_step = [&](int par, const uint8_t* rst, int rks, bool loads, int stage, int ksl) {
 #pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            const int q = t >> 2, j = t & 3;
-            acc[q][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[par][j], af[par][q], acc[q][j], 0, 0, 0);
-            if (t < 8) {
+        for (int t = 0; t < 64; ++t) {
+            const int nt = t >> 3, mt = t & 7;
+            // accumulators pinned to the accumulation registers, fragments to the ordinary ones
+            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[nt][mt]) : "v"(bfr[par][nt]), "v"(af[par][mt]));
+            if (t < 32 && (t & 1)) {
                 __builtin_amdgcn_sched_barrier(0);
-                read_one(rst, rks, par ^ 1, t);
+                read_one(rst, rks, par ^ 1, t >> 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (n_loads == 8 && (t & 1)) {
+            if (loads && (t & 3) == 2) {
                 __builtin_amdgcn_sched_barrier(0);
-                if (enable) issue1(stage, ksl, first_op + (t >> 1));
+                issue1(stage, ksl, t >> 2);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
 
-    // ---- epilogue of one tile: per block of 32 tokens and 64 output columns, fp32 staging [32][64]
-    // (row stride 256 B, 16-byte chunk index XORed with the row), then 8 consecutive columns per lane
     float* stg = reinterpret_cast<float*>(smem + 2 * STAGE + wave * 8192);
+    // Epilogue of one tile.  A pass covers 32 tokens x 64 output columns: the lanes' 4-column pieces go
+    // into the fp32 staging tile [32][64] (row stride 256 B, 16-byte chunk index XORed with the row) and
+    // come back as 8 consecutive columns per lane.  Passes are software-pipelined: the staging writes of
+    // pass p+1 (and its residual loads) are issued behind the read-back of pass p -- LDS executes a wave's
+    // operations in order, so the read-back still sees pass p -- and run while pass p is packed and stored.
     auto epilogue = [&](int it) {
         int m0, n0;
         tile_origin(it, m0, n0);
-        constexpr int NH = (EPI == EPI_SWIGLU) ? 1 : 2;        // passes per token block
+        constexpr int NH = (EPI == EPI_SWIGLU) ? 1 : 2;
+        constexpr int NP = 4 * NH;
         const int n_out = (EPI == EPI_SWIGLU) ? (N >> 1) : N;
+        const int row_l = lane >> 3, g8 = lane & 7;
+        auto write_pass = [&](int p) {
+            const int q = p / NH, h = p % NH;
 #pragma unroll
-        for (int q = 0; q < TM; ++q)
+            for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int h = 0; h < NH; ++h) {
-                // lane holds token lrow and columns 32 jj + 8 a + 4 lgrp + (0..3) of accumulator tile jj
+                for (int c4 = 0; c4 < 4; ++c4) {
+                    f32x4_t o;
+                    if (EPI == EPI_SWIGLU) {             // n tiles (0,1) gate, (2,3) up, (4,5) gate, (6,7) up
+                        const int gt = (c4 >> 1) * 4 + (c4 & 1);
 #pragma unroll
-                for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-                    for (int a = 0; a < 4; ++a) {
-                        f32x4_t o;
-                        if (EPI == EPI_SWIGLU) {       // tiles 0, 2 hold gate blocks, tiles 1, 3 the matching up blocks
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const float g = acc[q][2 * jj][4 * a + e], u = acc[q][2 * jj + 1][4 * a + e];
-                                o[e] = g / (1.0f + __expf(-g)) * u;
-                            }
-                        } else {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = acc[q][2 * h + jj][4 * a + e];
+                        for (int e = 0; e < 4; ++e) {
+                            const float g = acc[gt][2 * q + mt][e], u = acc[gt + 2][2 * q + mt][e];
+                            o[e] = g / (1.0f + __expf(-g)) * u;
                         }
-                        const int c = jj * 8 + a * 2 + lgrp;
-                        *reinterpret_cast<f32x4_t*>(stg + lrow * 64 + ((c ^ (lrow & 15)) << 2)) = o;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = acc[4 * h + c4][2 * q + mt][e];
                     }
-                const int oc0 = (EPI == EPI_SWIGLU) ? ((n0 + wn * 128) >> 1) : (n0 + wn * 128 + 64 * h);
+                    const int row = mt * 16 + l16;
+                    const int c = c4 * 4 + lk;
+                    *reinterpret_cast<f32x4_t*>(stg + row * 64 + ((c ^ (row & 15)) << 2)) = o;
+                }
+        };
+        auto out_ptr = [&](int p, int r8, bool& ok) -> size_t {
+            const int q = p / NH, h = p % NH;
+            const int oc0 = (EPI == EPI_SWIGLU) ? ((n0 + wn * 128) >> 1) : (n0 + wn * 128 + 64 * h);
+            const int gr = m0 + wm * 128 + q * 32 + r8 * 8 + row_l;
+            const int gc = oc0 + g8 * 8;
+            ok = gr < M && gc < n_out;
+            return (size_t)gr * ldc + gc;
+        };
+        constexpr int RD = 4;                    // residual loads run RD-1 passes ahead
+        u32x4_t rres[RD][4];
+        auto load_res = [&](int p) {
+            if (EPI != EPI_RESIDUAL) return;
 #pragma unroll
-                for (int r8 = 0; r8 < 4; ++r8) {
-                    const int row = r8 * 8 + (lane >> 3);
-                    const int g8 = lane & 7;
-                    const f32x4_t lo = *reinterpret_cast<const f32x4_t*>(stg + row * 64 + (((2 * g8) ^ (row & 15)) << 2));
-                    const f32x4_t hi = *reinterpret_cast<const f32x4_t*>(stg + row * 64 + (((2 * g8 + 1) ^ (row & 15)) << 2));
-                    const int gr = m0 + wm * 128 + q * 32 + row;
-                    const int gc = oc0 + g8 * 8;
-                    if (gr < M && gc < n_out) {
-                        float o[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                        if (EPI == EPI_RESIDUAL) {
-                            const u32x4_t rv = *reinterpret_cast<const u32x4_t*>(R + (size_t)gr * ldc + gc);
+            for (int r8 = 0; r8 < 4; ++r8) {
+                bool ok;
+                const size_t off = out_ptr(p, r8, ok);
+                rres[p % RD][r8] = *reinterpret_cast<const u32x4_t*>(R + (ok ? off : 0));    // no branch: out-of-range lanes read element 0
+            }
+        };
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                o[2 * e] += __uint_as_float(rv[e] << 16);
-                                o[2 * e + 1] += __uint_as_float(rv[e] & 0xffff0000u);
-                            }
+        for (int p = 0; p < RD - 1 && p < NP; ++p) load_res(p);
+        write_pass(0);
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            f32x4_t lo[4], hi[4];
+#pragma unroll
+            for (int r8 = 0; r8 < 4; ++r8) {
+                const int row = r8 * 8 + row_l;
+                lo[r8] = *reinterpret_cast<const f32x4_t*>(stg + row * 64 + (((2 * g8) ^ (row & 15)) << 2));
+                hi[r8] = *reinterpret_cast<const f32x4_t*>(stg + row * 64 + (((2 * g8 + 1) ^ (row & 15)) << 2));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (p + RD - 1 < NP) load_res(p + RD - 1);
+            if (p + 1 < NP) write_pass(p + 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int r8 = 0; r8 < 4; ++r8) {
+                bool ok;
+                const size_t off = out_ptr(p, r8, ok);
+                if (ok) {
+                    float o[8] = {lo[r8][0], lo[r8][1], lo[r8][2], lo[r8][3], hi[r8][0], hi[r8][1], hi[r8][2], hi[r8][3]};
+                    if (EPI == EPI_RESIDUAL) {
+                        const u32x4_t rv = rres[p % RD][r8];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            o[2 * e] += __uint_as_float(rv[e] << 16);
+                            o[2 * e + 1] += __uint_as_float(rv[e] & 0xffff0000u);
                         }
-                        u32x4_t pv;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) pv[e] = pack_bf16x2(o[2 * e], o[2 * e + 1]);
-                        __builtin_nontemporal_store(pv, reinterpret_cast<u32x4_t*>(C + (size_t)gr * ldc + gc));
                     }
+                    u32x4_t pv;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) pv[e] = pack_bf16x2(o[2 * e], o[2 * e + 1]);
+                    // streaming stores are acknowledged late, and the residual loads behind them in the
+                    // memory counter would wait for that: plain stores when there is a residual to read
+                    if (EPI == EPI_RESIDUAL) *reinterpret_cast<u32x4_t*>(C + off) = pv;
+                    else __builtin_nontemporal_store(pv, reinterpret_cast<u32x4_t*>(C + off));
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
 
-    // ---- prologue: slices 0 and 1 of the first tile (K >= 128)
     set_roff(0);
 #pragma unroll
     for (int i = 0; i < LPS; ++i) issue1(0, 0, i);
 #pragma unroll
     for (int i = 0; i < LPS; ++i) issue1(1, 1, i);
-    __builtin_amdgcn_s_waitcnt(VmcntImm<LPS>::value);        // slice 0 has landed
+    __builtin_amdgcn_s_waitcnt(VmcntImm<LPS>::value);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int t = 0; t < 8; ++t) read_one(smem, 0, 0, t);
+    for (int t = 0; t < 16; ++t) read_one(smem, 0, 0, t);
 
-    int g = 0;                                   // slice counter of this block's stream
+    int g = 0;
     for (int it = 0; it < nt_local; ++it) {
         for (int s = 0; s < nsl; ++s, ++g) {
             const uint8_t* st = smem + (g & 1) * STAGE;
             const uint8_t* stn = smem + ((g + 1) & 1) * STAGE;
-            // k-step 0 requests the second half of stream slice g+1, k-step 3 the first half of g+2;
-            // requests past the end of the stream repeat its last slice into the stage that is free then
-            int k1 = s + 1, k2 = s + 2;
-            if (k1 >= nsl) k1 -= nsl;
+            int k2 = s + 2;
             if (k2 >= nsl) k2 -= nsl;
-            if (g + 1 > g_last) k1 = nsl - 1;
             if (g + 2 > g_last) k2 = nsl - 1;
-            mfma_step(0, st, 1, 8, g > 0, (g + 1) & 1, k1, 8);
+            mfma_step(0, st, 1, false, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            mfma_step(1, st, 2, 0, false, 0, 0, 0);
+            if (s == nsl - 2) set_roff(it + 1);
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            mfma_step(0, st, 3, 0, false, 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            if (s == nsl - 2) set_roff(it + 1);              // from here on the requests belong to the next tile
-            __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0): the fragments of k-step 3 are in registers
-            __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): own loads of slice g+1 have landed
-            __builtin_amdgcn_s_barrier();                    // ... everyone's; nobody reads stage g any more
-            __builtin_amdgcn_sched_barrier(0);
-            mfma_step(1, stn, 0, 8, true, g & 1, k2, 0);
+            mfma_step(1, stn, 0, true, g & 1, k2);
             __builtin_amdgcn_sched_barrier(0);
         }
+        // the MFMAs are issued from inline asm, so the compiler does not place the wait states an
+        // accumulator read behind a matrix instruction needs: the last products are written before they are read
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
         epilogue(it);
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < 8; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+                for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
+        asm volatile("s_nop 7" ::: "memory");        // ... and the zeros are in place before the next product reads them
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);          // the repeats requested past the end
+    __builtin_amdgcn_s_waitcnt(0x0F70);
 }
+
 
 constexpr size_t STREAM_LDS = (size_t)2 * 512 * 128 + 4 * 8192;     // ring + staging = 160 KB
 
