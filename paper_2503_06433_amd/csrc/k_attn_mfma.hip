@@ -394,7 +394,7 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
                                                               float* __restrict__ scratch, float scale_log2e) {
     constexpr int KS = D / 32;
     constexpr int DT = D / 16;
-    const int item = blockIdx.x, g = blockIdx.y;
+    const int item = wk.item_order[blockIdx.x], g = blockIdx.y;
     const int G = n_q / n_kv;
     const int sq = wk.item_seq[item];
     const int page0 = wk.item_page0[item], npg = wk.item_npages[item];
@@ -486,12 +486,13 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
     }
 }
 
-// Merge of the per-item partials: one block of D threads per (q head, sequence).
-template <int D>
-__global__ __launch_bounds__(D) void attn_decode_merge_kernel(const float* __restrict__ scratch,
-                                                              bf16_t* __restrict__ out, int n_q, BatchMeta bm,
-                                                              DecodeWork wk) {
-    const int a = blockIdx.x, sq = blockIdx.y, e = threadIdx.x;
+// Merge of the per-item partials: D threads per (q head, sequence), HB heads per block.
+template <int D, int HB>
+__global__ __launch_bounds__(D * HB) void attn_decode_merge_kernel(const float* __restrict__ scratch,
+                                                                   bf16_t* __restrict__ out, int n_q, BatchMeta bm,
+                                                                   DecodeWork wk) {
+    const int a = blockIdx.x * HB + threadIdx.x / D, sq = blockIdx.y, e = threadIdx.x % D;
+    if (a >= n_q) return;
     const int i0 = wk.seq_item0[sq], i1 = wk.seq_item0[sq + 1];
     float M = -INFINITY;
     for (int i = i0; i < i1; ++i) M = fmaxf(M, scratch[((size_t)i * n_q + a) * (D + 4) + D]);
@@ -520,8 +521,8 @@ hipError_t attn_decode(int dt, const void* qkv, void* out, int n_q, int n_kv, co
     dim3 grid(wk.n_items, n_kv);
     attn_decode_mfma_kernel<128><<<grid, 64, 0, s>>>((const bf16_t*)qkv, n_q, n_kv, bm, wk,
                                                      (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, scratch, sl2);
-    dim3 mgrid(n_q, bm.n_seqs);
-    attn_decode_merge_kernel<128><<<mgrid, 128, 0, s>>>(scratch, (bf16_t*)out, n_q, bm, wk);
+    dim3 mgrid((n_q + 7) / 8, bm.n_seqs);
+    attn_decode_merge_kernel<128, 8><<<mgrid, 1024, 0, s>>>(scratch, (bf16_t*)out, n_q, bm, wk);
     return hipGetLastError();
 }
 

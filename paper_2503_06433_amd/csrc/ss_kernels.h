@@ -90,6 +90,7 @@ struct DecodeWork {
     const int32_t* item_page0;  // [n_items] first page index within the sequence
     const int32_t* item_npages; // [n_items]
     const int32_t* seq_item0;   // [n_seqs+1] first item of each sequence
+    const int32_t* item_order;  // [n_items] launch order (block x works on item item_order[x])
     int n_items;
     int max_items_per_seq;
 };

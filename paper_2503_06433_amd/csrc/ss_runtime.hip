@@ -396,17 +396,24 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
         for (int i = 0; i < n; ++i) {
             seq_item0[i] = (int32_t)item_seq.size();
             const int used = (b->kv_lens_before[i] + 1 + c->m.page_size - 1) / c->m.page_size;
-            int cnt = 0;
-            for (int p0 = 0; p0 < used; p0 += ipp, ++cnt) {
+            // near-equal items (even page counts: the kernel walks pages in pairs) instead of full items
+            // and a short remainder
+            const int cnt = (used + ipp - 1) / ipp;
+            const int per = (((used + cnt - 1) / cnt) + 1) & ~1;
+            for (int p0 = 0; p0 < used; p0 += per) {
                 item_seq.push_back(i);
                 item_page0.push_back(p0);
-                item_np.push_back(std::min(ipp, used - p0));
+                item_np.push_back(std::min(per, used - p0));
             }
             max_items = std::max(max_items, cnt);
         }
         seq_item0[n] = (int32_t)item_seq.size();
     }
     const size_t n_items = item_seq.size();
+    // launch order: longest items first, so that the last waves of the grid are the short ones
+    std::vector<int32_t> item_order(n_items);
+    for (size_t i = 0; i < n_items; ++i) item_order[i] = (int32_t)i;
+    std::stable_sort(item_order.begin(), item_order.end(), [&](int32_t a, int32_t b2) { return item_np[a] > item_np[b2]; });
     auto al = [](size_t x) { return (x + 63) & ~(size_t)63; };
     size_t off_tok_seq = 0;
     size_t off_tok_pos = off_tok_seq + al(4 * (size_t)T);
@@ -417,7 +424,8 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
     size_t off_ip0 = off_iseq + al(4 * n_items);
     size_t off_inp = off_ip0 + al(4 * n_items);
     size_t off_si0 = off_inp + al(4 * n_items);
-    size_t total = off_si0 + al(4 * (size_t)(n + 1));
+    size_t off_iord = off_si0 + al(4 * (size_t)(n + 1));
+    size_t total = off_iord + al(4 * n_items);
     if (total > ms.cap) {
         if (ms.host) { HIP_TRY(c, hipHostFree(ms.host)); ms.host = nullptr; }
         if (ms.dev) { HIP_TRY(c, hipFree(ms.dev)); ms.dev = nullptr; }
@@ -449,6 +457,7 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
         memcpy(ms.host + off_ip0, item_page0.data(), 4 * n_items);
         memcpy(ms.host + off_inp, item_np.data(), 4 * n_items);
         memcpy(ms.host + off_si0, seq_item0.data(), 4 * (size_t)(n + 1));
+        memcpy(ms.host + off_iord, item_order.data(), 4 * n_items);
     }
     HIP_TRY(c, hipMemcpyAsync(ms.dev, ms.host, total, hipMemcpyHostToDevice, stream));
     ms.bm.tok_seq = (const int32_t*)(ms.dev + off_tok_seq);
@@ -464,6 +473,7 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
     ms.wk.item_page0 = (const int32_t*)(ms.dev + off_ip0);
     ms.wk.item_npages = (const int32_t*)(ms.dev + off_inp);
     ms.wk.seq_item0 = (const int32_t*)(ms.dev + off_si0);
+    ms.wk.item_order = (const int32_t*)(ms.dev + off_iord);
     ms.wk.n_items = (int)n_items;
     ms.wk.max_items_per_seq = max_items;
     ms.shard = s;
