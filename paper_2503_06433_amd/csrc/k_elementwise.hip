@@ -106,33 +106,38 @@ hipError_t embed_rows(int dt, const void* table, const int32_t* ids, void* out, 
 }
 
 // ---------------------------------------------------------------- RoPE + KV page write
-// One block per token.  Work items are 16-byte chunk pairs (element i.. and
-// i + d/2 ..) of the q and k heads, and 16-byte chunks of the v heads.
-// K lands in its page as [head][slot][d]; V lands transposed, [head][d][vslot(slot)].
+// One block per (page unit, kv head): the new tokens of one sequence that fall into one page (up to 16),
+// with the q heads of that kv head's group, the k head and the v head.  q is rotated in place; the rotated
+// k rows land in the page as [slot][d] (one contiguous run); v lands transposed, [d][vslot(slot)].  A full
+// page of v goes through an LDS tile and is written as one contiguous 16-byte-per-lane run; partial pages
+// (the first and last page of a prompt, every decode step) write element by element.
 template <typename T>
 __global__ __launch_bounds__(256) void rope_kvwrite_kernel(T* __restrict__ qkv, int n_q, int n_kv, int d,
                                                            const float* __restrict__ rope, BatchMeta bm,
-                                                           T* __restrict__ k_pool, T* __restrict__ v_pool,
-                                                           int page_size) {
+                                                           T* __restrict__ k_pool, T* __restrict__ v_pool) {
     constexpr int V = VecOf<T>::N;
-    const int t = blockIdx.x;
-    const int pos = bm.tok_pos[t];
-    const int sq = bm.tok_seq[t];
-    const int page = bm.page_tables[(size_t)sq * bm.pt_stride + pos / page_size];
-    const int slot = pos % page_size;
+    constexpr int PS = 16;
+    const int u = blockIdx.x, g = blockIdx.y;
+    const int sq = bm.unit_seq[u], tok0 = bm.unit_tok0[u], pos0 = bm.unit_pos0[u], cnt = bm.unit_cnt[u];
+    const int page = bm.page_tables[(size_t)sq * bm.pt_stride + pos0 / PS];
+    const int slot0 = pos0 % PS;
+    const int G = n_q / n_kv;
     const int half = d / 2;
-    const int cph = half / V;                     // chunk pairs per head
+    const int cph = half / V;                     // 16-byte chunk pairs per head row
     const size_t row_stride = (size_t)(n_q + 2 * n_kv) * d;
-    T* row = qkv + (size_t)t * row_stride;
-    const float* cs = rope + (size_t)pos * d;     // [half][2] = cos, sin interleaved
-    const size_t page_elems = (size_t)n_kv * page_size * d;
+    const size_t page_elems = (size_t)n_kv * PS * d;
+    T* kpage = k_pool + (size_t)page * page_elems + (size_t)g * PS * d;
+    T* vpage = v_pool + (size_t)page * page_elems + (size_t)g * PS * d;
 
-    const int n_rot = (n_q + n_kv) * cph;
-    for (int w = threadIdx.x; w < n_rot; w += 256) {
-        const int head = w / cph;
-        const int i0 = (w % cph) * V;
-        T* lo_p = row + (size_t)head * d + i0;
+    // ---- rotation: (G q heads + the k head) x tokens x chunk pairs
+    const int per_head = cnt * cph;
+    for (int w = threadIdx.x; w < (G + 1) * per_head; w += 256) {
+        const int hh = w / per_head, r = w % per_head;
+        const int tl = r / cph, i0 = (r % cph) * V;
+        const int head = hh < G ? g * G + hh : n_q + g;          // column block of the qkv row
+        T* lo_p = qkv + (size_t)(tok0 + tl) * row_stride + (size_t)head * d + i0;
         T* hi_p = lo_p + half;
+        const float* cs = rope + (size_t)(pos0 + tl) * d;        // [half][2] = cos, sin interleaved
         float lo[V], hi[V], olo[V], ohi[V];
         unpack16<T>(*reinterpret_cast<const vec16*>(lo_p), lo);
         unpack16<T>(*reinterpret_cast<const vec16*>(hi_p), hi);
@@ -143,34 +148,54 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(T* __restrict__ qkv, 
             ohi[j] = hi[j] * c + lo[j] * sn;
         }
         const vec16 plo = pack16<T>(olo), phi = pack16<T>(ohi);
-        if (head < n_q) {
+        if (hh < G) {
             *reinterpret_cast<vec16*>(lo_p) = plo;
             *reinterpret_cast<vec16*>(hi_p) = phi;
         } else {
-            const int g = head - n_q;
-            T* dst = k_pool + (size_t)page * page_elems + ((size_t)g * page_size + slot) * d + i0;
+            T* dst = kpage + (size_t)(slot0 + tl) * d + i0;
             *reinterpret_cast<vec16*>(dst) = plo;
             *reinterpret_cast<vec16*>(dst + half) = phi;
         }
     }
-    // V: element (g, e) -> v_pool[page][g][e][slot]
-    const T* vrow = row + (size_t)(n_q + n_kv) * d;
-    T* vdst = v_pool + (size_t)page * page_elems + vslot(slot);
-    const int n_v = n_kv * d;
-    for (int w = threadIdx.x; w < n_v; w += 256) vdst[(size_t)w * page_size] = vrow[w];
+
+    // ---- v: element (token tl, e) -> vpage[e][vslot(slot0 + tl)]
+    const T* vcol = qkv + (size_t)tok0 * row_stride + (size_t)(n_q + n_kv + g) * d;
+    __shared__ T tile[PS][128 + V];
+    if (cnt == PS && d == 128) {                   // block-uniform
+        for (int w = threadIdx.x; w < PS * (128 / V); w += 256) {
+            const int tl = w / (128 / V), c = w % (128 / V);
+            *reinterpret_cast<vec16*>(&tile[tl][c * V]) = *reinterpret_cast<const vec16*>(vcol + (size_t)tl * row_stride + c * V);
+        }
+        __syncthreads();
+        // 16-byte piece `pc` of row e holds positions [V*pc, V*pc + V); position p is token vslot(p) (an involution)
+        for (int w = threadIdx.x; w < 128 * (PS / V); w += 256) {
+            const int e = w / (PS / V), pc = w % (PS / V);
+            union { vec16 v; T x[V]; } o;
+#pragma unroll
+            for (int j = 0; j < V; ++j) o.x[j] = tile[vslot(pc * V + j)][e];
+            *reinterpret_cast<vec16*>(vpage + (size_t)e * PS + pc * V) = o.v;
+        }
+    } else {
+        for (int w = threadIdx.x; w < cnt * d; w += 256) {
+            const int tl = w / d, e = w % d;
+            vpage[(size_t)e * PS + vslot(slot0 + tl)] = vcol[(size_t)tl * row_stride + e];
+        }
+    }
 }
 
 hipError_t rope_kvwrite(int dt, void* qkv, int n_q, int n_kv, const float* rope_table, const BatchMeta& bm,
                         const KvLayer& kv, hipStream_t s) {
-    if (bm.T <= 0) return hipSuccess;
+    if (bm.T <= 0 || bm.n_units <= 0) return hipSuccess;
     const int V = dt == F32 ? 4 : 8;
-    if (kv.d % (2 * V) != 0 || kv.n_heads != n_kv || kv.page_size <= 0) return hipErrorInvalidValue;
+    if (kv.d % (2 * V) != 0 || kv.n_heads != n_kv || kv.page_size != 16 || n_kv <= 0 || n_q % n_kv != 0 || n_kv > 65535)
+        return hipErrorInvalidValue;
+    dim3 grid(bm.n_units, n_kv);
     if (dt == F32)
-        rope_kvwrite_kernel<float><<<bm.T, 256, 0, s>>>((float*)qkv, n_q, n_kv, kv.d, rope_table, bm,
-                                                        (float*)kv.k_pool, (float*)kv.v_pool, kv.page_size);
+        rope_kvwrite_kernel<float><<<grid, 256, 0, s>>>((float*)qkv, n_q, n_kv, kv.d, rope_table, bm,
+                                                        (float*)kv.k_pool, (float*)kv.v_pool);
     else
-        rope_kvwrite_kernel<bf16_t><<<bm.T, 256, 0, s>>>((bf16_t*)qkv, n_q, n_kv, kv.d, rope_table, bm,
-                                                         (bf16_t*)kv.k_pool, (bf16_t*)kv.v_pool, kv.page_size);
+        rope_kvwrite_kernel<bf16_t><<<grid, 256, 0, s>>>((bf16_t*)qkv, n_q, n_kv, kv.d, rope_table, bm,
+                                                         (bf16_t*)kv.k_pool, (bf16_t*)kv.v_pool);
     return hipGetLastError();
 }
 

@@ -69,6 +69,13 @@ struct BatchMeta {
     int n_seqs;
     int T;
     int max_q_len;
+    // page units of the new tokens: unit u = the tokens of sequence unit_seq[u] that fall into one of its
+    // pages: batch tokens [unit_tok0[u], +unit_cnt[u]), absolute positions from unit_pos0[u]
+    const int32_t* unit_seq;
+    const int32_t* unit_tok0;
+    const int32_t* unit_pos0;
+    const int32_t* unit_cnt;
+    int n_units;
 };
 
 // Rotates q and k in place inside qkv [T, (n_q + 2 n_kv) d] by the token's

@@ -101,6 +101,7 @@ struct Lane {
     hipStream_t side = nullptr;
     uint8_t* pinned = nullptr;
     uint8_t* dev_staging = nullptr;
+    size_t dev_cap = 0;                          // bytes of dev_staging
     uint8_t* mv_meta_host = nullptr;
     uint8_t* mv_meta_dev = nullptr;
     hipEvent_t mv_ev[2] = {nullptr, nullptr};
@@ -409,6 +410,24 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
         }
         seq_item0[n] = (int32_t)item_seq.size();
     }
+    // page units of the new tokens (for the RoPE + cache-write kernel)
+    std::vector<int32_t> unit_seq, unit_tok0, unit_pos0, unit_cnt;
+    {
+        int t0 = 0;
+        const int ps = c->m.page_size;
+        for (int i = 0; i < n; ++i) {
+            const int b0 = b->kv_lens_before[i], e0 = b0 + b->q_lens[i];
+            for (int pg = b0 / ps; pg * ps < e0; ++pg) {
+                const int p0 = std::max(b0, pg * ps), p1 = std::min(e0, pg * ps + ps);
+                unit_seq.push_back(i);
+                unit_tok0.push_back(t0 + (p0 - b0));
+                unit_pos0.push_back(p0);
+                unit_cnt.push_back(p1 - p0);
+            }
+            t0 += b->q_lens[i];
+        }
+    }
+    const size_t n_units = unit_seq.size();
     const size_t n_items = item_seq.size();
     // launch order: longest items first, so that the last waves of the grid are the short ones
     std::vector<int32_t> item_order(n_items);
@@ -425,7 +444,11 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
     size_t off_inp = off_ip0 + al(4 * n_items);
     size_t off_si0 = off_inp + al(4 * n_items);
     size_t off_iord = off_si0 + al(4 * (size_t)(n + 1));
-    size_t total = off_iord + al(4 * n_items);
+    size_t off_useq = off_iord + al(4 * n_items);
+    size_t off_utok = off_useq + al(4 * n_units);
+    size_t off_upos = off_utok + al(4 * n_units);
+    size_t off_ucnt = off_upos + al(4 * n_units);
+    size_t total = off_ucnt + al(4 * n_units);
     if (total > ms.cap) {
         if (ms.host) { HIP_TRY(c, hipHostFree(ms.host)); ms.host = nullptr; }
         if (ms.dev) { HIP_TRY(c, hipFree(ms.dev)); ms.dev = nullptr; }
@@ -459,6 +482,10 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
         memcpy(ms.host + off_si0, seq_item0.data(), 4 * (size_t)(n + 1));
         memcpy(ms.host + off_iord, item_order.data(), 4 * n_items);
     }
+    memcpy(ms.host + off_useq, unit_seq.data(), 4 * n_units);
+    memcpy(ms.host + off_utok, unit_tok0.data(), 4 * n_units);
+    memcpy(ms.host + off_upos, unit_pos0.data(), 4 * n_units);
+    memcpy(ms.host + off_ucnt, unit_cnt.data(), 4 * n_units);
     HIP_TRY(c, hipMemcpyAsync(ms.dev, ms.host, total, hipMemcpyHostToDevice, stream));
     ms.bm.tok_seq = (const int32_t*)(ms.dev + off_tok_seq);
     ms.bm.tok_pos = (const int32_t*)(ms.dev + off_tok_pos);
@@ -469,6 +496,11 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
     ms.bm.n_seqs = n;
     ms.bm.T = (int)T;
     ms.bm.max_q_len = max_q;
+    ms.bm.unit_seq = (const int32_t*)(ms.dev + off_useq);
+    ms.bm.unit_tok0 = (const int32_t*)(ms.dev + off_utok);
+    ms.bm.unit_pos0 = (const int32_t*)(ms.dev + off_upos);
+    ms.bm.unit_cnt = (const int32_t*)(ms.dev + off_ucnt);
+    ms.bm.n_units = (int)n_units;
     ms.wk.item_seq = (const int32_t*)(ms.dev + off_iseq);
     ms.wk.item_page0 = (const int32_t*)(ms.dev + off_ip0);
     ms.wk.item_npages = (const int32_t*)(ms.dev + off_inp);
@@ -713,8 +745,7 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
     }
     // Stage two (pinned <-> tier) is plain host memcpy; large chunks are split over a few helper
     // threads so that one core's copy rate does not become the ceiling of the whole movement.
-    auto host_copy = [&](size_t ci, bool to_tier) {
-        const int slot = (int)(ci & 1);
+    auto host_copy = [&](size_t ci, bool to_tier, int slot) {
         struct Piece { uint8_t* tier; uint8_t* pin; size_t bytes; };
         std::vector<Piece> pieces;
         uint8_t* p = L.pinned + (size_t)slot * c->slot_bytes;
@@ -756,47 +787,73 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
         for (size_t u = chunks[ci].first; u < chunks[ci].second; ++u) b += units[u].bytes;
         return b;
     };
-    const size_t meta_half = c->mv_meta_cap / 2;
-    for (size_t ci = 0; ci < chunks.size(); ++ci) {
-        const int slot = (int)(ci & 1);
-        uint8_t* mh = L.mv_meta_host + slot * meta_half;
-        uint8_t* md = L.mv_meta_dev + slot * meta_half;
-        uint8_t* dst = L.dev_staging + (size_t)slot * c->slot_bytes;
-        uint8_t* pin = L.pinned + (size_t)slot * c->slot_bytes;
-        ssk::RepackUnits ru{};
-        if (ci >= 2) HIP_TRY(c, hipEventSynchronize(L.mv_ev[slot]));   // slot's previous DMA and metadata are done
-        const size_t mbytes = build_units(c, s, job.seqs, units, chunks[ci].first, chunks[ci].second, mh, md, meta_half, &ru);
-        if (!mbytes) return fail(c, SS_ENOMEM, "KV mover metadata region too small");
-        const size_t bytes = chunk_bytes(ci);
-        if (job.dir == SS_OUT) {
-            HIP_TRY(c, hipMemcpyAsync(md, mh, mbytes, hipMemcpyHostToDevice, L.side));
-            {
-                ProfScope ps(c, 3, L.side);
-                K_TRY(c, ssk::kv_gather(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru,
-                                        dst, L.side));
-            }
-            HIP_TRY(c, hipMemcpyAsync(pin, dst, bytes, hipMemcpyDeviceToHost, L.side));
-            HIP_TRY(c, hipEventRecord(L.mv_ev[slot], L.side));
-            if (ci >= 1) {   // stage two of the previous chunk overlaps this chunk's gather + DMA
-                HIP_TRY(c, hipEventSynchronize(L.mv_ev[slot ^ 1]));
-                host_copy(ci - 1, true);
-            }
-        } else {
-            host_copy(ci, false);   // overlaps the previous chunk's DMA + scatter
-            HIP_TRY(c, hipMemcpyAsync(md, mh, mbytes, hipMemcpyHostToDevice, L.side));
-            HIP_TRY(c, hipMemcpyAsync(dst, pin, bytes, hipMemcpyHostToDevice, L.side));
-            {
-                ProfScope ps(c, 3, L.side);
-                K_TRY(c, ssk::kv_scatter(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size,
-                                         ru, dst, L.side));
-            }
-            HIP_TRY(c, hipEventRecord(L.mv_ev[slot], L.side));
+    // Device staging holds a group of consecutive chunks (a whole job when it fits): one repack kernel per
+    // group instead of one per chunk, so that the copies of a group run back to back on the lane's stream
+    // without a kernel (that has to find room on a chip busy with the caller's kernels) between them.
+    // out: gather(group) -> for each chunk: DMA staging -> pinned slot | stage two of the previous chunk
+    // in:  for each chunk: stage two into the pinned slot | DMA pinned slot -> staging; then scatter(group)
+    constexpr size_t DEV_CAP_MAX = (size_t)2 << 30;
+    size_t job_bytes = 0;
+    for (const Unit& u : units) job_bytes += u.bytes;
+    {
+        const size_t want = std::min(std::max(job_bytes, 2 * c->slot_bytes), DEV_CAP_MAX);
+        if (want > L.dev_cap) {              // the lane's stream is idle between jobs
+            if (L.dev_staging) HIP_TRY(c, hipFree(L.dev_staging));
+            L.dev_staging = nullptr;
+            L.dev_cap = 0;
+            HIP_TRY(c, hipMalloc((void**)&L.dev_staging, want));
+            L.dev_cap = want;
         }
     }
-    if (job.dir == SS_OUT && !chunks.empty()) {
-        const size_t last = chunks.size() - 1;
-        HIP_TRY(c, hipEventSynchronize(L.mv_ev[last & 1]));
-        host_copy(last, true);
+    size_t n_dma = 0;                        // chunks whose DMA has been issued (pinned slot = n_dma & 1)
+    for (size_t g0 = 0; g0 < chunks.size();) {
+        size_t g1 = g0, gbytes = 0;
+        while (g1 < chunks.size() && gbytes + chunk_bytes(g1) <= L.dev_cap &&
+               chunks[g1].second - chunks[g0].first <= 65535) gbytes += chunk_bytes(g1++);
+        if (g1 == g0) return fail(c, SS_ENOMEM, "device staging smaller than one chunk");
+        if (g0 > 0) HIP_TRY(c, hipStreamSynchronize(L.side));    // the previous group is through: metadata is free
+        ssk::RepackUnits ru{};
+        const size_t mbytes = build_units(c, s, job.seqs, units, chunks[g0].first, chunks[g1 - 1].second, L.mv_meta_host,
+                                          L.mv_meta_dev, c->mv_meta_cap, &ru);
+        if (!mbytes) return fail(c, SS_ENOMEM, "KV mover metadata region too small");
+        HIP_TRY(c, hipMemcpyAsync(L.mv_meta_dev, L.mv_meta_host, mbytes, hipMemcpyHostToDevice, L.side));
+        if (job.dir == SS_OUT) {
+            ProfScope ps(c, 3, L.side);
+            K_TRY(c, ssk::kv_gather(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru,
+                                    L.dev_staging, L.side));
+        }
+        size_t off = 0;
+        for (size_t ci = g0; ci < g1; ++ci, ++n_dma) {
+            const int slot = (int)(n_dma & 1);
+            uint8_t* pin = L.pinned + (size_t)slot * c->slot_bytes;
+            const size_t bytes = chunk_bytes(ci);
+            if (job.dir == SS_OUT) {
+                // the pinned slot is free: stage two of chunk ci-2 ran in the previous iteration
+                HIP_TRY(c, hipMemcpyAsync(pin, L.dev_staging + off, bytes, hipMemcpyDeviceToHost, L.side));
+                HIP_TRY(c, hipEventRecord(L.mv_ev[slot], L.side));
+                if (n_dma >= 1) {   // stage two of the previous chunk overlaps this chunk's DMA
+                    HIP_TRY(c, hipEventSynchronize(L.mv_ev[slot ^ 1]));
+                    host_copy(ci - 1, true, slot ^ 1);
+                }
+            } else {
+                if (n_dma >= 2) HIP_TRY(c, hipEventSynchronize(L.mv_ev[slot]));   // the DMA of chunk ci-2 has read the slot
+                host_copy(ci, false, slot);   // overlaps the previous chunk's DMA
+                HIP_TRY(c, hipMemcpyAsync(L.dev_staging + off, pin, bytes, hipMemcpyHostToDevice, L.side));
+                HIP_TRY(c, hipEventRecord(L.mv_ev[slot], L.side));
+            }
+            off += bytes;
+        }
+        if (job.dir == SS_IN) {
+            ProfScope ps(c, 3, L.side);
+            K_TRY(c, ssk::kv_scatter(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru,
+                                     L.dev_staging, L.side));
+        }
+        g0 = g1;
+    }
+    if (job.dir == SS_OUT && n_dma > 0) {
+        const int slot = (int)((n_dma - 1) & 1);
+        HIP_TRY(c, hipEventSynchronize(L.mv_ev[slot]));
+        host_copy(chunks.size() - 1, true, slot);
     } else {
         HIP_TRY(c, hipStreamSynchronize(L.side));
     }
@@ -1028,6 +1085,7 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
             if (c->slot_bytes) {
                 HIP_TRY(c, hipHostMalloc((void**)&L.pinned, 2 * c->slot_bytes, hipHostMallocDefault));
                 HIP_TRY(c, hipMalloc((void**)&L.dev_staging, 2 * c->slot_bytes));
+                L.dev_cap = 2 * c->slot_bytes;
             }
             HIP_TRY(c, hipHostMalloc((void**)&L.mv_meta_host, c->mv_meta_cap, hipHostMallocDefault));
             HIP_TRY(c, hipMalloc((void**)&L.mv_meta_dev, c->mv_meta_cap));
