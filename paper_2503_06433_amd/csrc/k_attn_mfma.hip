@@ -16,6 +16,11 @@
 
 namespace ssk {
 
+// 2^x on the hardware's exponential unit (v_exp_f32, about 1 ulp for normal results; results below the
+// normal range flush to zero, which a softmax weight may).  The library exp2f wraps the same instruction
+// in range scaling for denormal results: four more VALU operations per element in the innermost loop.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
@@ -123,11 +128,11 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const bf16_t* __
                 mx = fmaxf(mx, s[t][v]);
             }
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float alpha = exp2f(m[t] - mx);
+            const float alpha = fast_exp2(m[t] - mx);
             m[t] = mx;
             float rs = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { s[t][v] = exp2f(s[t][v] - mx); rs += s[t][v]; }
+            for (int v = 0; v < 16; ++v) { s[t][v] = fast_exp2(s[t][v] - mx); rs += s[t][v]; }
             l[t] = l[t] * alpha + rs;
 #pragma unroll
             for (int u = 0; u < DT; ++u)
@@ -297,11 +302,11 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
             for (int v = 1; v < 16; ++v) mr = fmaxf(mr, s[v]);
             mr = fmaxf(mr, __shfl_xor(mr, 32, 64));
             const float mx = fmaxf(m, mr * scale_log2e);
-            const float alpha = exp2f(m - mx);
+            const float alpha = fast_exp2(m - mx);
             m = mx;
             float rs = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { s[v] = exp2f(fmaf(s[v], scale_log2e, -mx)); rs += s[v]; }
+            for (int v = 0; v < 16; ++v) { s[v] = fast_exp2(fmaf(s[v], scale_log2e, -mx)); rs += s[v]; }
             l = l * alpha + rs;
             if (__ballot(alpha != 1.0f) != 0ull) {       // the running maximum moved for some query of the wave
 #pragma unroll
@@ -446,13 +451,13 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         // the first page of an item always holds a visible token: mx is finite
-        const float alpha = exp2f(m - mx);
+        const float alpha = fast_exp2(m - mx);
         m = mx;
         float rs = 0.f;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-            sA[v] = exp2f(sA[v] - mx);
-            sB[v] = exp2f(sB[v] - mx);
+            sA[v] = fast_exp2(sA[v] - mx);
+            sB[v] = fast_exp2(sB[v] - mx);
             rs += sA[v] + sB[v];
         }
         l = l * alpha + rs;
@@ -499,7 +504,7 @@ __global__ __launch_bounds__(D * HB) void attn_decode_merge_kernel(const float* 
     float num = 0.f, den = 0.f;
     for (int i = i0; i < i1; ++i) {
         const float* sp = scratch + ((size_t)i * n_q + a) * (D + 4);
-        const float w = exp2f(sp[D] - M);
+        const float w = fast_exp2(sp[D] - M);
         num += w * sp[e];
         den += w * sp[D + 1];
     }
