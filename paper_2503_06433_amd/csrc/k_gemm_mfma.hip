@@ -26,6 +26,14 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int EPI_PARTIAL = 100;   // internal: fp32 split-K partials
 
+// silu(g) * u with the exponential and the reciprocal on the hardware units (about 1 ulp each; the
+// result is rounded to bf16).  A plain `/` expands to the IEEE division sequence, a dozen VALU
+// operations per element in the epilogue.
+__device__ __forceinline__ float swiglu_act(float g, float u) {
+    const float e = __builtin_amdgcn_exp2f(g * -1.4426950408889634f);
+    return g * __builtin_amdgcn_rcpf(1.0f + e) * u;
+}
+
 __device__ __forceinline__ int lds_chunk_off(int row, int kc) {
     // byte offset of 16-byte chunk kc (0..7) of a 128-byte row
     const int sw = (row & 7) ^ ((row >> 3) & 1);
@@ -188,7 +196,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
                     const int r = rbase + 8 * (v >> 2) + (v & 3);
                     if (r >= M) continue;
                     const float g = acc[i][j][v], u = acc[i][j + 1][v];
-                    C[(size_t)r * ldc + oc] = f2bf(g / (1.0f + __expf(-g)) * u);
+                    C[(size_t)r * ldc + oc] = f2bf(swiglu_act(g, u));
                 }
             }
         } else {
@@ -405,7 +413,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const float g = acc[gt][2 * q + mt][e], u = acc[gt + 2][2 * q + mt][e];
-                            o[e] = g / (1.0f + __expf(-g)) * u;
+                            o[e] = swiglu_act(g, u);
                         }
                     } else {
 #pragma unroll
@@ -602,7 +610,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
         const int ng = (j >> 5) * 64 + (j & 31);
         float g = 0.f, u = 0.f;
         for (int s = 0; s < S; ++s) { g += P[s * plane + (size_t)m * N + ng]; u += P[s * plane + (size_t)m * N + ng + 32]; }
-        C[(size_t)m * ldc + j] = f2bf(g / (1.0f + __expf(-g)) * u);
+        C[(size_t)m * ldc + j] = f2bf(swiglu_act(g, u));
     } else {
         float o = 0.f;
         for (int s = 0; s < S; ++s) o += P[s * plane + (size_t)m * N + j];
