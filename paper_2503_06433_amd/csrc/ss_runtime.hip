@@ -132,6 +132,7 @@ struct ss_ctx {
     int gemm_rounds_busy = 4;                    // GEMM launch granularity while mover jobs are pending
     int gemm_rounds = 0;                         // ... of the layer call in progress (0 = one launch)
     int copy_threads = 4;
+    size_t copy_max_bytes = (size_t)8 << 20;      // adjacent runs of the direct tier path are merged up to this size
     bool trace_mover = false;
     std::string err;
     std::map<DescKey, Shard*> shards;
@@ -144,6 +145,7 @@ struct ss_ctx {
     size_t d_ids_cap = 0;
     // host tier
     uint8_t* tier = nullptr;
+    bool tier_pinned = false;                    // page-locked: the DMA engines address it directly
     size_t tier_cap = 0, tier_used = 0;
     std::map<size_t, size_t> tier_free;          // offset -> length of every free block (coalesced)
     std::unordered_map<int64_t, TierSlot> tier_slots;
@@ -806,6 +808,10 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
         }
     }
     size_t n_dma = 0;                        // chunks whose DMA has been issued (pinned slot = n_dma & 1)
+    const bool fine = c->trace_mover && getenv("SS_TRACE_MOVER")[0] == '2';
+    auto now_ms = [] { return std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now().time_since_epoch()).count(); };
+    const double tj0 = now_ms();
+    auto mark = [&](const char* what, size_t ci) { if (fine) fprintf(stderr, "[mover-fine] %s dir %d chunk %zu at %.3f ms\n", what, job.dir, ci, now_ms() - tj0); };
     for (size_t g0 = 0; g0 < chunks.size();) {
         size_t g1 = g0, gbytes = 0;
         while (g1 < chunks.size() && gbytes + chunk_bytes(g1) <= L.dev_cap &&
@@ -822,26 +828,76 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
             K_TRY(c, ssk::kv_gather(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru,
                                     L.dev_staging, L.side));
         }
+        // runs of this group: (unit, K|V) -> contiguous in staging and in the tier
+        size_t min_run = SIZE_MAX;
+        for (size_t u = chunks[g0].first; u < chunks[g1 - 1].second; ++u) min_run = std::min(min_run, units[u].bytes / 2);
+        const bool direct = c->tier_pinned && min_run >= ((size_t)256 << 10);
+        if (direct) {
+            // runs that follow each other both in staging and in the tier (K and V of a shard that owns all
+            // kv heads, consecutive layers, sequences whose tier slots are adjacent) go as one copy
+            size_t uoff = 0, cur_bytes = 0;
+            uint8_t *cur_t = nullptr, *cur_d = nullptr;
+            auto flush = [&]() -> int {
+                if (!cur_bytes) return SS_OK;
+                if (job.dir == SS_OUT) HIP_TRY(c, hipMemcpyAsync(cur_t, cur_d, cur_bytes, hipMemcpyDeviceToHost, L.side));
+                else HIP_TRY(c, hipMemcpyAsync(cur_d, cur_t, cur_bytes, hipMemcpyHostToDevice, L.side));
+                cur_bytes = 0;
+                return SS_OK;
+            };
+            for (size_t u = chunks[g0].first; u < chunks[g1 - 1].second; ++u) {
+                const SeqJob& sj = job.seqs[units[u].seq_idx];
+                const size_t run = units[u].bytes / 2;
+                for (int kv = 0; kv < 2; ++kv) {
+                    uint8_t* t = tier_run(c, s, sj, units[u].ll, kv);
+                    uint8_t* d = L.dev_staging + uoff + (size_t)kv * run;
+                    if (cur_bytes && cur_bytes + run <= c->copy_max_bytes && t == cur_t + cur_bytes && d == cur_d + cur_bytes) {
+                        cur_bytes += run;
+                    } else {
+                        int rc = flush();
+                        if (rc) return rc;
+                        cur_t = t; cur_d = d; cur_bytes = run;
+                    }
+                }
+                uoff += units[u].bytes;
+            }
+            int rc = flush();
+            if (rc) return rc;
+        }
         size_t off = 0;
-        for (size_t ci = g0; ci < g1; ++ci, ++n_dma) {
+        size_t pending = SIZE_MAX;               // out: chunk whose stage two has not run yet
+        for (size_t ci = g0; !direct && ci < g1; ++ci, ++n_dma) {
             const int slot = (int)(n_dma & 1);
             uint8_t* pin = L.pinned + (size_t)slot * c->slot_bytes;
             const size_t bytes = chunk_bytes(ci);
             if (job.dir == SS_OUT) {
-                // the pinned slot is free: stage two of chunk ci-2 ran in the previous iteration
+                // the pinned slot is free: stage two of the chunk before the previous one has run
                 HIP_TRY(c, hipMemcpyAsync(pin, L.dev_staging + off, bytes, hipMemcpyDeviceToHost, L.side));
                 HIP_TRY(c, hipEventRecord(L.mv_ev[slot], L.side));
-                if (n_dma >= 1) {   // stage two of the previous chunk overlaps this chunk's DMA
+                if (pending != SIZE_MAX) {   // stage two of the previous chunk overlaps this chunk's DMA
+                    mark("wait-dma", pending);
                     HIP_TRY(c, hipEventSynchronize(L.mv_ev[slot ^ 1]));
-                    host_copy(ci - 1, true, slot ^ 1);
+                    mark("dma-done", pending);
+                    host_copy(pending, true, slot ^ 1);
+                    mark("host-copied", pending);
                 }
+                pending = ci;
             } else {
+                mark("wait-slot", ci);
                 if (n_dma >= 2) HIP_TRY(c, hipEventSynchronize(L.mv_ev[slot]));   // the DMA of chunk ci-2 has read the slot
+                mark("slot-free", ci);
                 host_copy(ci, false, slot);   // overlaps the previous chunk's DMA
+                mark("host-copied", ci);
                 HIP_TRY(c, hipMemcpyAsync(L.dev_staging + off, pin, bytes, hipMemcpyHostToDevice, L.side));
                 HIP_TRY(c, hipEventRecord(L.mv_ev[slot], L.side));
             }
             off += bytes;
+        }
+        if (pending != SIZE_MAX) {
+            const int slot = (int)((n_dma - 1) & 1);
+            HIP_TRY(c, hipEventSynchronize(L.mv_ev[slot]));
+            mark("dma-done", pending);
+            host_copy(pending, true, slot);
+            mark("host-copied", pending);
         }
         if (job.dir == SS_IN) {
             ProfScope ps(c, 3, L.side);
@@ -850,13 +906,9 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
         }
         g0 = g1;
     }
-    if (job.dir == SS_OUT && n_dma > 0) {
-        const int slot = (int)((n_dma - 1) & 1);
-        HIP_TRY(c, hipEventSynchronize(L.mv_ev[slot]));
-        host_copy(chunks.size() - 1, true, slot);
-    } else {
-        HIP_TRY(c, hipStreamSynchronize(L.side));
-    }
+    mark("wait-stream", chunks.size());
+    HIP_TRY(c, hipStreamSynchronize(L.side));
+    mark("stream-done", chunks.size());
     return SS_OK;
 }
 
@@ -1059,6 +1111,7 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
     c->force_generic = fg && fg[0] == '1';
     c->trace_mover = getenv("SS_TRACE_MOVER") != nullptr;
     if (const char* gr = getenv("SS_GEMM_ROUNDS")) c->gemm_rounds_busy = std::max(0, atoi(gr));
+    if (const char* cm = getenv("SS_COPY_MAX_MB")) c->copy_max_bytes = (size_t)std::max(1, atoi(cm)) << 20;
     if (const char* ct = getenv("SS_COPY_THREADS")) c->copy_threads = std::max(1, std::min(16, atoi(ct)));
     int rc = SS_OK;
     auto boot = [&]() -> int {
@@ -1074,7 +1127,22 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
         HIP_TRY(c, hipMalloc((void**)&c->d_rope, tab.size() * sizeof(float)));
         HIP_TRY(c, hipMemcpy(c->d_rope, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice));
         if (rt->host_tier_bytes > 0) {
-            c->tier = (uint8_t*)malloc((size_t)rt->host_tier_bytes);
+            // Page-locked when it is of moderate size (SS_TIER_PIN_MAX_GB, default 64): the movers then copy
+            // between device staging and the tier directly, one DMA per (sequence, layer, K|V) run, and
+            // stage two through the pinned ring (a host memcpy per chunk, which doubles the host-memory
+            // traffic of a movement) is only taken for short runs.  Larger tiers are pageable.
+            double pin_max_gb = 64.0;
+            if (const char* e = getenv("SS_TIER_PIN_MAX_GB")) pin_max_gb = atof(e);
+            if ((double)rt->host_tier_bytes <= pin_max_gb * (double)(1ull << 30)) {
+                void* pt = nullptr;
+                if (hipHostMalloc(&pt, (size_t)rt->host_tier_bytes, hipHostMallocDefault) == hipSuccess) {
+                    c->tier = (uint8_t*)pt;
+                    c->tier_pinned = true;
+                } else {
+                    (void)hipGetLastError();
+                }
+            }
+            if (!c->tier) c->tier = (uint8_t*)malloc((size_t)rt->host_tier_bytes);
             if (!c->tier) return fail(c, SS_ENOMEM, "host tier allocation failed");
             c->tier_cap = (size_t)rt->host_tier_bytes;
             c->tier_free[0] = c->tier_cap;
@@ -1142,7 +1210,8 @@ int ss_destroy(ss_ctx* c) {
     for (void* p : {(void*)c->d_rope, c->d_embed, c->d_gf, c->d_wlm_t, (void*)c->d_ids})
         if (p) (void)hipFree(p);
     for (auto& r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
-    free(c->tier);
+    if (c->tier_pinned) (void)hipHostFree(c->tier);
+    else free(c->tier);
     delete c;
     return SS_OK;
 }
