@@ -48,8 +48,10 @@ typedef struct {
 
 typedef struct {
     int64_t gpu_kv_pages;    /* pages in the pool of EACH shard descriptor used */
-    int64_t host_tier_bytes; /* capacity of the host tier (complete caches) */
-    int64_t pinned_bytes;    /* pinned staging: two lanes (out, in) of two slots each */
+    int64_t host_tier_bytes; /* capacity of the host tier (complete caches); allocated page-locked up to 64 GiB
+                                (environment SS_TIER_PIN_MAX_GB), pageable above */
+    int64_t pinned_bytes;    /* pinned staging: two lanes (out, in) of two slots each; used for every movement
+                                into a pageable tier and for runs shorter than 256 KiB into a page-locked one */
     int32_t device;          /* HIP device ordinal */
     int32_t max_seq_len;     /* longest sequence (rotary table size) */
 } ss_runtime_cfg;
