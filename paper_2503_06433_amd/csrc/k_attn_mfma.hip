@@ -242,25 +242,31 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
     float m = -INFINITY, l = 0.f;
 
     // DMA assignment per stage: wave w brings K rows [8w, 8w+8) (two loads of 4 rows) and V^T pieces 2w, 2w+1
-    // (piece i = page i/4 of the tile, d rows [32*(i%4), +32): 1 KB contiguous in the page).
-    auto issue = [&](int tile) {
+    // (piece i = page i/4 of the tile, d rows [32*(i%4), +32): 1 KB contiguous in the page).  All of a wave's
+    // rows and pieces lie in page w/2 of the tile, so one page-table entry per wave and tile is needed; it
+    // is fetched one tile ahead (page_next), off the path between the barrier and the requests.
+    auto tile_page = [&](int tile) {
         const int tl = tile < n_tiles ? tile : n_tiles - 1;     // past the end: harmless repeat, keeps vmcnt uniform
+        int pg = tl * 4 + (wave >> 1);
+        pg = pg < n_pages ? pg : n_pages - 1;
+        return pt[pg];
+    };
+    int page_next = tile_page(0);
+    auto issue = [&](int tile) {
         const uint32_t st = lds_base + (uint32_t)(tile % NS) * STAGE;
+        const size_t page_off = (size_t)page_next * page_elems + head_off;
+        page_next = tile_page(tile + 1);
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int row = wave * 8 + i * 4 + (lane >> 4);     // token row of the tile
-            int pg = tl * 4 + (row >> 4);
-            pg = pg < n_pages ? pg : n_pages - 1;
             const int chunk = (lane & 15) ^ (row & 15);
-            const bf16_t* src = k_pool + (size_t)pt[pg] * page_elems + head_off + (size_t)(row & 15) * D + chunk * 8;
+            const bf16_t* src = k_pool + page_off + (size_t)(row & 15) * D + chunk * 8;
             dma16a(src, st + (wave * 8 + i * 4) * 256);
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int piece = wave * 2 + i;
-            int pg = tl * 4 + (piece >> 2);
-            pg = pg < n_pages ? pg : n_pages - 1;
-            const bf16_t* src = v_pool + (size_t)pt[pg] * page_elems + head_off + (size_t)(piece & 3) * 512 + lane * 8;
+            const bf16_t* src = v_pool + page_off + (size_t)(piece & 3) * 512 + lane * 8;
             dma16a(src, st + KBYTES + piece * 1024);
         }
     };
