@@ -95,6 +95,44 @@ const char* ss_last_error(ss_ctx* ctx);   /* valid until the next failing call *
  * (the pointers may be released on return). */
 int ss_load_layer(ss_ctx*, const ss_shard_desc*, int layer, const ss_layer_weights* full);
 
+/* ---- weight re-sharding (paper section 4.1 "Dynamic Model Re-sharding",
+ * Figure 5: at a switch between the prefill strategy and the decode strategy
+ * the weights are re-partitioned by reloading the shards the new strategy needs
+ * from a copy of the model in CPU memory; section 4.2: that cost does not
+ * depend on the batch size; Appendix A.3 for what a shard holds: 1/k of every
+ * matrix under tensor parallelism, whole layers under pipeline parallelism) ---
+ *
+ * ss_host_weights_put: copies the nine full tensors of `layer` (host or device
+ *   pointers, released on return) into the library's page-locked CPU copy of
+ *   the model, replacing an earlier copy of that layer.
+ * ss_reshard_weights(from, to, stream): every layer of `to`'s range receives
+ *   the shard's slices of the CPU copy.  Asynchronous: the copies run on the
+ *   library's weight stream after everything enqueued on `stream` (device
+ *   stream handle or NULL) before the call, and move exactly the shard's bytes
+ *   over PCIe (a row range of a matrix is one contiguous copy, a column range
+ *   one strided copy; a device kernel then lays the slice out for the GEMMs).
+ *   Layer calls on `to` issued later wait for the load on the GPU, the host
+ *   does not block.  `from` (may be NULL; ignored when it names the same shard
+ *   as `to`, which is then simply reloaded) loses its device weights once the
+ *   work enqueued on `stream` before the call has finished: its layer calls
+ *   fail with SS_EINVAL until it is loaded again; its KV pages are untouched.
+ *   The memory itself returns to the device at the next ss_reshard_weights,
+ *   ss_sync or ss_destroy after that point.  SS_ENOENT if a layer of `to` has
+ *   no CPU copy.
+ * ss_weights_wait: blocks the host until the descriptor's pending load is done.
+ * ss_weights_shard_bytes: bytes one (re)load of the descriptor moves (all its
+ *   layers: matrices / k plus the two gain vectors), or a negative code.
+ * ss_weights_read: inspection (slow): slice `which` (SS_W_*) that the shard
+ *   holds for `layer`, in [in_features, out_features] orientation as in
+ *   ss_layer_weights but with the shard's columns / rows only, into host_out.
+ */
+enum { SS_W_G1 = 0, SS_W_Q = 1, SS_W_K = 2, SS_W_V = 3, SS_W_O = 4, SS_W_G2 = 5, SS_W_G = 6, SS_W_U = 7, SS_W_D = 8 };
+int ss_host_weights_put(ss_ctx*, int layer, const ss_layer_weights* full);
+int ss_reshard_weights(ss_ctx*, const ss_shard_desc* from, const ss_shard_desc* to, void* stream);
+int ss_weights_wait(ss_ctx*, const ss_shard_desc*);
+int64_t ss_weights_shard_bytes(ss_ctx*, const ss_shard_desc*);
+int ss_weights_read(ss_ctx*, const ss_shard_desc*, int layer, int which, void* host_out);
+
 /* ---- the layer (paper section 2.1: "several linear layers and an attention
  * layer"; prefill handles all prompt tokens at once, decode one token per
  * sequence against its KV cache) --------------------------------------------

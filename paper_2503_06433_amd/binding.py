@@ -75,6 +75,11 @@ def load_library():
         "ss_destroy": (I, [V]),
         "ss_last_error": (C.c_char_p, [V]),
         "ss_load_layer": (I, [V, D, I, P(_LayerWeights)]),
+        "ss_host_weights_put": (I, [V, I, P(_LayerWeights)]),
+        "ss_reshard_weights": (I, [V, D, D, V]),
+        "ss_weights_wait": (I, [V, D]),
+        "ss_weights_shard_bytes": (L, [V, D]),
+        "ss_weights_read": (I, [V, D, I, I, V]),
         "ss_layer_prefill": (I, [V, D, I, I, P(_Batch), V, V, V]),
         "ss_layer_decode": (I, [V, D, I, I, P(_Batch), V, V, V]),
         "ss_kv_swap": (I, [V, D, I, P(L), I, V]),
@@ -107,10 +112,14 @@ def load_library():
     return lib
 
 
-EXPORTED = ("ss_create ss_destroy ss_last_error ss_load_layer ss_layer_prefill ss_layer_decode ss_kv_swap "
+EXPORTED = ("ss_create ss_destroy ss_last_error ss_load_layer ss_host_weights_put ss_reshard_weights ss_weights_wait "
+            "ss_weights_shard_bytes ss_weights_read ss_layer_prefill ss_layer_decode ss_kv_swap "
             "ss_kv_reshard ss_sync ss_kv_jobs_issued ss_kv_wait ss_kv_free ss_host_tier_release ss_kv_export_dev ss_kv_import_dev "
             "ss_kv_page_table ss_kv_seq_len ss_kv_read ss_host_tier_read ss_host_tier_used_bytes "
             "ss_kv_free_pages ss_load_head ss_embed ss_lm_head ss_prof_enable ss_prof_read ss_prof_reset").split()
+
+
+W_NAMES = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")     # index = SS_W_* of the header
 
 
 def _ptr(x):
@@ -164,6 +173,31 @@ class Context:
         keep = {k: (np.ascontiguousarray(v) if isinstance(v, np.ndarray) else v.contiguous()) for k, v in weights.items()}
         lw = _LayerWeights(*[_ptr(keep[n]) for n in ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")], location)
         self._ck(self.lib.ss_load_layer(self.h, C.byref(desc), layer, C.byref(lw)))
+
+    def host_weights_put(self, layer, weights, location=SS_HOST):
+        """Copies a layer's full weights (dict as for load_layer) into the library's CPU copy of the model."""
+        keep = {k: (np.ascontiguousarray(v) if isinstance(v, np.ndarray) else v.contiguous()) for k, v in weights.items()}
+        lw = _LayerWeights(*[_ptr(keep[n]) for n in W_NAMES], location)
+        self._ck(self.lib.ss_host_weights_put(self.h, layer, C.byref(lw)))
+
+    def reshard_weights(self, src, dst, stream=0):
+        """src may be None (nothing is released)."""
+        self._ck(self.lib.ss_reshard_weights(self.h, C.byref(src) if src is not None else None, C.byref(dst), stream))
+
+    def weights_wait(self, desc):
+        self._ck(self.lib.ss_weights_wait(self.h, C.byref(desc)))
+
+    def weights_shard_bytes(self, desc):
+        n = self.lib.ss_weights_shard_bytes(self.h, C.byref(desc))
+        if n < 0:
+            self._ck(int(n))
+        return int(n)
+
+    def weights_read(self, desc, layer, which, n_elems):
+        """Raw storage bits (uint16 for bf16, float32 for fp32) of the slice `which` the shard holds."""
+        out = np.empty(n_elems, dtype=np.float32 if self.model.dtype == SS_F32 else np.uint16)
+        self._ck(self.lib.ss_weights_read(self.h, C.byref(desc), layer, which, out.ctypes.data))
+        return out
 
     def load_head(self, embed, gf, wlm):
         e, g, w = (np.ascontiguousarray(a) for a in (embed, gf, wlm))

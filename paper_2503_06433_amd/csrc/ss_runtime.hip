@@ -38,6 +38,19 @@ struct LayerW {
     bool gu_interleaved = false;
 };
 
+// CPU copy of one layer's full weights (page-locked): the nine tensors in the order of
+// ss_layer_weights, [in_features, out_features] orientation, at byte offsets off[i] from base.
+struct HostLayer {
+    uint8_t* base = nullptr;
+    size_t off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+};
+
+// Device buffers whose release waits for the work that may still read them.
+struct DeferredFree {
+    hipEvent_t ev = nullptr;
+    std::vector<void*> ptrs;
+};
+
 struct SeqState {
     std::vector<int32_t> pages;
     int32_t len = 0;
@@ -54,6 +67,8 @@ struct Shard {
     std::priority_queue<int32_t, std::vector<int32_t>, std::greater<int32_t>> free_pages;
     std::unordered_map<int64_t, SeqState> seqs;
     uint64_t version = 0;     // bumped on every page-table change
+    hipEvent_t w_ready = nullptr;   // recorded on the weight stream behind the shard's last (re)load
+    bool w_pending = false;         // ... which layer calls still have to wait for
 };
 
 struct DescKey {
@@ -161,6 +176,11 @@ struct ss_ctx {
     int64_t out_issued = 0, out_done = 0;
     std::string worker_err;
     int worker_rc = 0;
+    // weight re-sharding: CPU copy of the model, the stream its reloads run on, their staging
+    std::vector<HostLayer> hw;
+    hipStream_t wstream = nullptr;
+    DevBuf w_staging;
+    std::vector<DeferredFree> deferred;
     // profiling
     bool prof_on = false;
     std::vector<ProfRec> prof;
@@ -629,6 +649,11 @@ int layer_call(ss_ctx* c, const ss_shard_desc* d, int layer, int phase, const ss
         return fail(c, SS_EINVAL, "layer %d outside the shard's range [%d,%d)", layer, d->layer_begin, d->layer_end);
     const int ll = layer - d->layer_begin;
     if (!s->w[ll].loaded) return fail(c, SS_EINVAL, "layer %d not loaded for this shard", layer);
+    if (s->w_pending) {      // a reload on the weight stream: the caller's stream waits for it, the host does not
+        HIP_TRY(c, hipStreamWaitEvent((hipStream_t)stream, s->w_ready, 0));
+        if (hipEventQuery(s->w_ready) == hipSuccess) s->w_pending = false;
+        else (void)hipGetLastError();
+    }
     const bool nores = (phase & SS_NO_RESIDUAL) != 0;
     const int ph = phase & 3;
     if (ph == 0) return fail(c, SS_EINVAL, "bad phase %d", phase);
@@ -1086,6 +1111,105 @@ void tier_release(ss_ctx* c, size_t off, size_t bytes) {
     c->tier_used -= bytes;
 }
 
+// ------------------------------------------------------------------ weights
+size_t tensor_elems(const ss_model_cfg& m, int which) {
+    const size_t H = m.hidden, qd = (size_t)m.n_q_heads * m.head_dim, kd = (size_t)m.n_kv_heads * m.head_dim, F = m.ffn;
+    switch (which) {
+        case SS_W_G1: case SS_W_G2: return H;
+        case SS_W_Q: return H * qd;
+        case SS_W_K: case SS_W_V: return H * kd;
+        case SS_W_O: return qd * H;
+        case SS_W_G: case SS_W_U: return H * F;
+        case SS_W_D: return F * H;
+    }
+    return 0;
+}
+
+int alloc_layer_buffers(ss_ctx* c, Shard* s, LayerW& L) {
+    const size_t H = c->m.hidden, nq = (size_t)s->nq_l * c->m.head_dim, nkv = (size_t)s->nkv_l * c->m.head_dim, F = s->f_l;
+    const size_t es = c->es;
+    auto alloc = [&](void** p, size_t bytes) -> int {
+        if (!*p) HIP_TRY(c, hipMalloc(p, bytes));
+        return SS_OK;
+    };
+    int rc;
+    if ((rc = alloc(&L.g1, H * es))) return rc;
+    if ((rc = alloc(&L.g2, H * es))) return rc;
+    if ((rc = alloc(&L.wqkv_t, (nq + 2 * nkv) * H * es))) return rc;
+    if ((rc = alloc(&L.wo_t, H * nq * es))) return rc;
+    if ((rc = alloc(&L.wgu_t, 2 * F * H * es))) return rc;
+    if ((rc = alloc(&L.wd_t, H * F * es))) return rc;
+    return SS_OK;
+}
+
+// Frees the buffers whose guarding event has completed (all of them, waiting, when `wait`).
+int release_deferred(ss_ctx* c, bool wait) {
+    for (size_t i = 0; i < c->deferred.size();) {
+        DeferredFree& df = c->deferred[i];
+        if (wait) HIP_TRY(c, hipEventSynchronize(df.ev));
+        const hipError_t q = hipEventQuery(df.ev);
+        if (q == hipSuccess) {
+            for (void* p : df.ptrs) HIP_TRY(c, hipFree(p));
+            (void)hipEventDestroy(df.ev);
+            c->deferred.erase(c->deferred.begin() + i);
+        } else {
+            (void)hipGetLastError();
+            ++i;
+        }
+    }
+    return SS_OK;
+}
+
+// One layer of shard s from the CPU copy, on the weight stream.  PCIe carries exactly the slice: a row
+// range is one contiguous copy, a column range one strided (2D) copy; a device kernel then lays the
+// staged slice out the way the GEMMs read it (transposed, gate/up interleaved).
+int reload_layer(ss_ctx* c, Shard* s, int ll) {
+    const ss_model_cfg& m = c->m;
+    const HostLayer& hl = c->hw[s->desc.layer_begin + ll];
+    LayerW& L = s->w[ll];
+    int rc = alloc_layer_buffers(c, s, L);
+    if (rc) return rc;
+    const size_t es = c->es;
+    const int H = m.hidden, dh = m.head_dim;
+    const int nq = s->nq_l * dh, nkv = s->nkv_l * dh, F = s->f_l;
+    const size_t qd = (size_t)m.n_q_heads * dh, kd = (size_t)m.n_kv_heads * dh;
+    hipStream_t ws = c->wstream;
+    HIP_TRY(c, hipMemcpyAsync(L.g1, hl.base + hl.off[SS_W_G1], (size_t)H * es, hipMemcpyHostToDevice, ws));
+    HIP_TRY(c, hipMemcpyAsync(L.g2, hl.base + hl.off[SS_W_G2], (size_t)H * es, hipMemcpyHostToDevice, ws));
+    // columns [c0, c0+n) of the host matrix [K, ld] -> dense staging [K, n] -> dst rows
+    auto cols = [&](int which, int K, size_t ld, size_t c0, int n, void* dst, int blk, int blk_stride, int row_off) -> int {
+        const uint8_t* src = hl.base + hl.off[which] + c0 * es;
+        if ((size_t)n == ld) HIP_TRY(c, hipMemcpyAsync(c->w_staging.p, src, (size_t)K * n * es, hipMemcpyHostToDevice, ws));
+        else HIP_TRY(c, hipMemcpy2DAsync(c->w_staging.p, (size_t)n * es, src, ld * es, (size_t)n * es, (size_t)K,
+                                         hipMemcpyHostToDevice, ws));
+        K_TRY(c, ssk::slice_transpose(c->dt, c->w_staging.p, (int64_t)n, K, 0, n, dst, blk, blk_stride, row_off, ws));
+        return SS_OK;
+    };
+    // rows [r0, r0+K) of the host matrix [*, n] (contiguous) -> staging [K, n] -> dst = its transpose
+    auto rows = [&](int which, size_t r0, int K, int n, void* dst) -> int {
+        const uint8_t* src = hl.base + hl.off[which] + r0 * (size_t)n * es;
+        HIP_TRY(c, hipMemcpyAsync(c->w_staging.p, src, (size_t)K * n * es, hipMemcpyHostToDevice, ws));
+        K_TRY(c, ssk::slice_transpose(c->dt, c->w_staging.p, (int64_t)n, K, 0, n, dst, n, n, 0, ws));
+        return SS_OK;
+    };
+    uint8_t* qkv = (uint8_t*)L.wqkv_t;
+    if ((rc = cols(SS_W_Q, H, qd, (size_t)s->q0 * dh, nq, qkv, nq, nq, 0))) return rc;
+    if ((rc = cols(SS_W_K, H, kd, (size_t)s->g0 * dh, nkv, qkv + (size_t)nq * H * es, nkv, nkv, 0))) return rc;
+    if ((rc = cols(SS_W_V, H, kd, (size_t)s->g0 * dh, nkv, qkv + (size_t)(nq + nkv) * H * es, nkv, nkv, 0))) return rc;
+    if ((rc = rows(SS_W_O, (size_t)s->q0 * dh, nq, H, L.wo_t))) return rc;
+    L.gu_interleaved = (c->dt == SS_BF16) && !c->force_generic && (F % 32 == 0) && (H % 64 == 0);
+    if (L.gu_interleaved) {
+        if ((rc = cols(SS_W_G, H, m.ffn, s->f0, F, L.wgu_t, 32, 64, 0))) return rc;
+        if ((rc = cols(SS_W_U, H, m.ffn, s->f0, F, L.wgu_t, 32, 64, 32))) return rc;
+    } else {
+        if ((rc = cols(SS_W_G, H, m.ffn, s->f0, F, L.wgu_t, F, F, 0))) return rc;
+        if ((rc = cols(SS_W_U, H, m.ffn, s->f0, F, L.wgu_t, F, F, F))) return rc;
+    }
+    if ((rc = rows(SS_W_D, (size_t)s->f0, F, H, L.wd_t))) return rc;
+    L.loaded = true;
+    return SS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1190,6 +1314,7 @@ int ss_destroy(ss_ctx* c) {
         for (void* p : s->v_pool) if (p) (void)hipFree(p);
         if (s->d_k_pools) (void)hipFree(s->d_k_pools);
         if (s->d_v_pools) (void)hipFree(s->d_v_pools);
+        if (s->w_ready) (void)hipEventDestroy(s->w_ready);
         delete s;
     }
     for (DevBuf* b : {&c->ws_h, &c->ws_qkv, &c->ws_attn, &c->ws_gu, &c->ws_act, &c->ws_x1, &c->ws_scratch, &c->ws_splitk})
@@ -1209,6 +1334,13 @@ int ss_destroy(ss_ctx* c) {
     }
     for (void* p : {(void*)c->d_rope, c->d_embed, c->d_gf, c->d_wlm_t, (void*)c->d_ids})
         if (p) (void)hipFree(p);
+    for (DeferredFree& df : c->deferred) {
+        for (void* p : df.ptrs) (void)hipFree(p);
+        if (df.ev) (void)hipEventDestroy(df.ev);
+    }
+    for (HostLayer& hl : c->hw) if (hl.base) (void)hipHostFree(hl.base);
+    if (c->w_staging.p) (void)hipFree(c->w_staging.p);
+    if (c->wstream) (void)hipStreamDestroy(c->wstream);
     for (auto& r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     if (c->tier_pinned) (void)hipHostFree(c->tier);
     else free(c->tier);
@@ -1260,6 +1392,167 @@ int ss_load_layer(ss_ctx* c, const ss_shard_desc* d, int layer, const ss_layer_w
     }
     if ((rc = slice_into(c, w->wd, w->location, m.ffn, H, (size_t)s->f0, F, 0, H, L.wd_t, H, H, 0))) return rc;
     L.loaded = true;
+    return SS_OK;
+}
+
+int ss_host_weights_put(ss_ctx* c, int layer, const ss_layer_weights* w) {
+    if (!c) return SS_EINVAL;
+    if (!w || !w->g1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->g2 || !w->wg || !w->wu || !w->wd)
+        return fail(c, SS_EINVAL, "null weight pointer");
+    if (w->location != SS_HOST && w->location != SS_DEVICE) return fail(c, SS_EINVAL, "bad weight location");
+    if (layer < 0 || layer >= c->m.n_layers) return fail(c, SS_EINVAL, "bad layer %d", layer);
+    if (c->hw.empty()) c->hw.resize(c->m.n_layers);
+    HostLayer& hl = c->hw[layer];
+    if (!hl.base) {
+        size_t total = 0;
+        for (int i = 0; i < 9; ++i) {
+            hl.off[i] = total;
+            total += (tensor_elems(c->m, i) * c->es + 255) & ~(size_t)255;
+        }
+        HIP_TRY(c, hipHostMalloc((void**)&hl.base, total, hipHostMallocDefault));
+    } else if (c->wstream) {
+        HIP_TRY(c, hipStreamSynchronize(c->wstream));       // no reload is reading the copy that is replaced
+    }
+    const void* src[9] = {w->g1, w->wq, w->wk, w->wv, w->wo, w->g2, w->wg, w->wu, w->wd};
+    for (int i = 0; i < 9; ++i) {
+        const size_t bytes = tensor_elems(c->m, i) * c->es;
+        if (w->location == SS_HOST) memcpy(hl.base + hl.off[i], src[i], bytes);
+        else HIP_TRY(c, hipMemcpy(hl.base + hl.off[i], src[i], bytes, hipMemcpyDeviceToHost));
+    }
+    return SS_OK;
+}
+
+int ss_reshard_weights(ss_ctx* c, const ss_shard_desc* from, const ss_shard_desc* to, void* stream) {
+    if (!c) return SS_EINVAL;
+    if (!to) return fail(c, SS_EINVAL, "null target descriptor");
+    Shard *sf = nullptr, *st = nullptr;
+    int rc = get_shard(c, to, &st);
+    if (rc) return rc;
+    if (from && (rc = get_shard(c, from, &sf))) return rc;
+    for (int l = to->layer_begin; l < to->layer_end; ++l)
+        if ((size_t)l >= c->hw.size() || !c->hw[l].base)
+            return fail(c, SS_ENOENT, "layer %d has no CPU copy (ss_host_weights_put)", l);
+    if (!c->wstream) HIP_TRY(c, hipStreamCreateWithFlags(&c->wstream, hipStreamNonBlocking));
+    if ((rc = release_deferred(c, false))) return rc;
+    hipStream_t cs = (hipStream_t)stream;
+    if (sf && sf != st) {
+        // the old shard's buffers go once everything enqueued on the caller's stream so far has run
+        if (sf->w_pending) {
+            HIP_TRY(c, hipEventSynchronize(sf->w_ready));
+            sf->w_pending = false;
+        }
+        DeferredFree df;
+        for (LayerW& L : sf->w) {
+            for (void** p : {&L.g1, &L.g2, &L.wqkv_t, &L.wo_t, &L.wgu_t, &L.wd_t})
+                if (*p) { df.ptrs.push_back(*p); *p = nullptr; }
+            L.loaded = false;
+        }
+        if (!df.ptrs.empty()) {
+            HIP_TRY(c, hipEventCreateWithFlags(&df.ev, hipEventDisableTiming));
+            HIP_TRY(c, hipEventRecord(df.ev, cs));
+            c->deferred.push_back(std::move(df));
+        }
+    }
+    // staging for the largest slice of the target
+    {
+        const size_t H = c->m.hidden;
+        const size_t widest = std::max<size_t>((size_t)st->nq_l * c->m.head_dim, (size_t)st->f_l);
+        const size_t need = H * widest * c->es;
+        if (need > c->w_staging.cap) {
+            HIP_TRY(c, hipStreamSynchronize(c->wstream));
+            if (c->w_staging.p) HIP_TRY(c, hipFree(c->w_staging.p));
+            c->w_staging.p = nullptr;
+            c->w_staging.cap = 0;
+            HIP_TRY(c, hipMalloc(&c->w_staging.p, need));
+            c->w_staging.cap = need;
+        }
+    }
+    // a reload into buffers that layer calls already enqueued on the caller's stream still read comes after them
+    {
+        hipEvent_t e = nullptr;
+        HIP_TRY(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        hipError_t er = hipEventRecord(e, cs);
+        if (er == hipSuccess) er = hipStreamWaitEvent(c->wstream, e, 0);
+        (void)hipEventDestroy(e);
+        if (er != hipSuccess) return fail(c, SS_EHIP, "weight re-shard ordering: %s", hipGetErrorString(er));
+    }
+    for (int ll = 0; ll < st->n_layers_l; ++ll)
+        if ((rc = reload_layer(c, st, ll))) return rc;
+    if (!st->w_ready) HIP_TRY(c, hipEventCreateWithFlags(&st->w_ready, hipEventDisableTiming));
+    HIP_TRY(c, hipEventRecord(st->w_ready, c->wstream));
+    st->w_pending = true;
+    return SS_OK;
+}
+
+int ss_weights_wait(ss_ctx* c, const ss_shard_desc* d) {
+    if (!c) return SS_EINVAL;
+    Shard* s = nullptr;
+    int rc = get_shard(c, d, &s);
+    if (rc) return rc;
+    if (s->w_pending) {
+        HIP_TRY(c, hipEventSynchronize(s->w_ready));
+        s->w_pending = false;
+    }
+    return SS_OK;
+}
+
+int64_t ss_weights_shard_bytes(ss_ctx* c, const ss_shard_desc* d) {
+    if (!c) return SS_EINVAL;
+    Shard* s = nullptr;
+    if (get_shard(c, d, &s)) return SS_EINVAL;
+    const int64_t H = c->m.hidden, dh = c->m.head_dim;
+    const int64_t per_layer = H * (s->nq_l + 2 * s->nkv_l) * dh + s->nq_l * dh * H + 3 * H * s->f_l + 2 * H;
+    return per_layer * s->n_layers_l * (int64_t)c->es;
+}
+
+int ss_weights_read(ss_ctx* c, const ss_shard_desc* d, int layer, int which, void* host_out) {
+    if (!c || !host_out) return SS_EINVAL;
+    Shard* s = nullptr;
+    int rc = get_shard(c, d, &s);
+    if (rc) return rc;
+    if (layer < d->layer_begin || layer >= d->layer_end) return fail(c, SS_EINVAL, "layer %d outside the shard", layer);
+    if (which < 0 || which > SS_W_D) return fail(c, SS_EINVAL, "bad tensor index %d", which);
+    const LayerW& L = s->w[layer - d->layer_begin];
+    if (!L.loaded) return fail(c, SS_ENOENT, "layer %d not loaded for this shard", layer);
+    if ((rc = ss_weights_wait(c, d))) return rc;
+    HIP_TRY(c, hipDeviceSynchronize());
+    const size_t es = c->es, H = c->m.hidden, dh = c->m.head_dim;
+    const size_t nq = (size_t)s->nq_l * dh, nkv = (size_t)s->nkv_l * dh, F = s->f_l;
+    uint8_t* out = (uint8_t*)host_out;
+    if (which == SS_W_G1 || which == SS_W_G2) {
+        HIP_TRY(c, hipMemcpy(out, which == SS_W_G1 ? L.g1 : L.g2, H * es, hipMemcpyDeviceToHost));
+        return SS_OK;
+    }
+    // device image -> host, then back to [in, out] orientation element by element
+    const void* dev = nullptr;
+    size_t rows_t = 0, cols_t = 0;        // device image [rows_t][cols_t]
+    switch (which) {
+        case SS_W_Q: case SS_W_K: case SS_W_V: dev = L.wqkv_t; rows_t = nq + 2 * nkv; cols_t = H; break;
+        case SS_W_O: dev = L.wo_t; rows_t = H; cols_t = nq; break;
+        case SS_W_G: case SS_W_U: dev = L.wgu_t; rows_t = 2 * F; cols_t = H; break;
+        default: dev = L.wd_t; rows_t = H; cols_t = F; break;
+    }
+    std::vector<uint8_t> img(rows_t * cols_t * es);
+    HIP_TRY(c, hipMemcpy(img.data(), dev, img.size(), hipMemcpyDeviceToHost));
+    auto put = [&](size_t o, size_t r, size_t cc) { memcpy(out + o * es, img.data() + (r * cols_t + cc) * es, es); };
+    if (which == SS_W_Q || which == SS_W_K || which == SS_W_V) {
+        const size_t n = which == SS_W_Q ? nq : nkv, r0 = which == SS_W_Q ? 0 : (which == SS_W_K ? nq : nq + nkv);
+        for (size_t h = 0; h < H; ++h)
+            for (size_t j = 0; j < n; ++j) put(h * n + j, r0 + j, h);
+    } else if (which == SS_W_O) {
+        for (size_t j = 0; j < nq; ++j)
+            for (size_t h = 0; h < H; ++h) put(j * H + h, h, j);
+    } else if (which == SS_W_G || which == SS_W_U) {
+        const bool up = which == SS_W_U;
+        for (size_t h = 0; h < H; ++h)
+            for (size_t j = 0; j < F; ++j) {
+                const size_t r = L.gu_interleaved ? (j / 32) * 64 + (j % 32) + (up ? 32 : 0) : j + (up ? F : 0);
+                put(h * F + j, r, h);
+            }
+    } else {
+        for (size_t f = 0; f < F; ++f)
+            for (size_t h = 0; h < H; ++h) put(f * H + h, h, f);
+    }
     return SS_OK;
 }
 
@@ -1345,6 +1638,11 @@ int ss_sync(ss_ctx* c) {
     if (!c) return SS_EINVAL;
     wait_idle(c);
     for (Lane& L : c->lane) HIP_TRY(c, hipStreamSynchronize(L.side));
+    if (c->wstream) HIP_TRY(c, hipStreamSynchronize(c->wstream));
+    {
+        int rc = release_deferred(c, false);
+        if (rc) return rc;
+    }
     std::lock_guard<std::mutex> lk(c->mu);
     if (c->worker_rc) {
         const int rc = c->worker_rc;
