@@ -262,6 +262,22 @@ def main():
                      "prefill_tokens_per_s": Tp * reps / (sum(v[0] for v in pf.values()) * 1e-3),
                      "decode_tokens_per_s": B * reps / (sum(v[0] for v in dc.values()) * 1e-3)},
     }
+    # ---- weight re-shard (outside the timed steps): reload of the decode strategy's slices of this layer
+    # from the page-locked CPU copy; k = 1 moves whole matrices, k = 4 the strided column / row slices
+    ctx.host_weights_put(0, raws)
+    wr = {}
+    for label, desc in (("k1", tp), ("k4_shard0", hz.tp_desc(cfg, 4, 0))):
+        ctx.reshard_weights(None, desc, stream)                  # first call allocates
+        ctx.weights_wait(desc)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(3):
+            ctx.reshard_weights(None, desc, stream)
+        ctx.weights_wait(desc)
+        dt_w = (time.perf_counter() - t1) / 3
+        nbytes = ctx.weights_shard_bytes(desc)
+        wr[label] = {"bytes": nbytes, "ms": dt_w * 1e3, "GB/s": nbytes / dt_w / 1e9}
+    out["weight_reshard"] = wr
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(work, vals)
     print(json.dumps(out))

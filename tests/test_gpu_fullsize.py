@@ -279,3 +279,24 @@ def test_config5_reshard_all_bytes_synthetic_cache():
         for l in range(L):
             assert np.array_equal(ctx.kv_read(tp, i, l, 1), want[l]), "sequence %d layer %d" % (i, l)
     ctx.destroy()
+
+
+def test_config3_weight_reshard_pp_layer_to_tp4_shard_bit_exact():
+    """The weight half of the configuration-3 switch at full layer size (13B shape: 317 M parameters per
+    layer): one layer of the pipeline stage is replaced by shard 2 of 4 of the same layer, reloaded from
+    the CPU copy; every tensor the shard then holds is compared bit for bit with the oracle's slice."""
+    from oracle import weight_shard as ows
+    from paper_2503_06433_amd.binding import W_NAMES
+    cfg = wl.config3().cfg
+    _, raws = wl.make_layer_weights(cfg, 3301)
+    ctx = make_context(cfg, pages=8)
+    ctx.host_weights_put(0, raws)
+    stage, shard = pp_desc(cfg, 0, 1), tp_desc(cfg, 4, 2, 0, 1)
+    ctx.reshard_weights(None, stage)
+    ctx.reshard_weights(stage, shard)
+    assert ctx.weights_shard_bytes(shard) == ows.reload_elems(cfg, 4, 0, 1) * 2
+    ref = ows.shard_weights(cfg, raws, 4, 2)
+    for which, name in enumerate(W_NAMES):
+        got = ctx.weights_read(shard, 0, which, ref[name].size)
+        assert np.array_equal(got, ref[name].reshape(-1)), name
+    ctx.destroy()
