@@ -219,6 +219,60 @@ int ss_embed(ss_ctx*, const int32_t* token_ids_host, int n, void* x_out, void* s
 /* logits [n, vocab] float32 device = RMSNorm(x; gf) * wlm */
 int ss_lm_head(ss_ctx*, const void* x, int n, float* logits, void* stream);
 
+/* The shapes the context was created with. */
+int ss_get_config(ss_ctx*, ss_model_cfg* model_out, ss_runtime_cfg* rt_out);
+
+/* ---- offline engine loop (paper section 4.2 "Tiered KV Cache Buffering and
+ * Transition-minimizing Scheduling", Figure 6; section 5.2 "Asynchronous
+ * swap-in") -------------------------------------------------------------------
+ *
+ * Runs a list of requests to completion on one GPU with greedy decoding,
+ * switching between a prefill strategy and a decode strategy only when the
+ * CPU store (the host tier) is full, respectively has been emptied onto the
+ * GPU.  Host control only: all work is issued through the entry points above.
+ * The rules (the paper fixes the triggers; the rest is stated so that the order
+ * of actions is unique):
+ *   prefill stage: requests in arrival order; a batch takes requests while
+ *     the prompt tokens stay within max_prefill_tokens (a longer prompt alone)
+ *     and the prompts' pages fit gpu_kv_pages;
+ *     every batch's cache is swapped out behind it; the stage ends when the
+ *     next prompt does not fit in the store (host_tier_bytes / bytes per token
+ *     over all layers) or nothing is left to prefill.  A request that wants one
+ *     token is finished by its prefill and never enters the store.
+ *   decode stage, per iteration: caches requested in the previous iteration
+ *     come on board; while the head of the store fits (pages of its final
+ *     length, prompt + outputs - 1 tokens, next to those promised to admitted
+ *     sequences within gpu_kv_pages; at most max_decode_seqs admitted) its
+ *     swap-in is requested; every sequence on board gets one token; finished
+ *     ones free their pages.  When the store is empty and nothing is arriving:
+ *     back to prefilling if requests wait (sequences still decoding keep their
+ *     pages and continue in the next decode stage), else on until all are done.
+ * Both descriptors must cover all layers with k == 1 (one GPU runs whole
+ * layers) and be distinct (one SS_PP, one SS_TP).  With reshard_weights != 0
+ * the stage's weights are reloaded from the CPU copy at every switch
+ * (ss_reshard_weights; needs ss_host_weights_put for every layer); with 0 both
+ * descriptors must already be loaded and stay resident.  Needs ss_load_head.
+ *
+ * prompt_tokens: the prompts back to back; tokens_out: out_lens[i] tokens per
+ * request back to back (token 1 comes from the prefill).  trace (may be NULL):
+ * int32 records  code, n, id_0 .. id_{n-1}  with code 1 prefill batch,
+ * 2 switch to decode, 3 swap-in requested, 4 decode step, 5 switch to prefill,
+ * 6 finished; *trace_len receives the length needed (SS_ENOMEM if above
+ * trace_cap).  All pointers are host memory.  SS_ENOMEM if a request can never
+ * fit the CPU store or the GPU store. */
+typedef struct {
+    ss_shard_desc prefill, decode;
+    int32_t max_prefill_tokens, max_decode_seqs;
+    int32_t reshard_weights;
+} ss_offline_cfg;
+typedef struct {
+    int64_t prefill_batches, decode_steps, to_decode, to_prefill, tokens;
+    double prefill_seconds, decode_seconds, switch_seconds, total_seconds;
+} ss_offline_stats;
+int ss_offline_run(ss_ctx*, const ss_offline_cfg*, int32_t n_requests, const int32_t* prompt_lens,
+                   const int32_t* prompt_tokens, const int32_t* out_lens, int32_t* tokens_out, int32_t* trace,
+                   int64_t trace_cap, int64_t* trace_len, ss_offline_stats* stats, void* stream);
+
 /* ---- timing hooks (bench) ------------------------------------------------ */
 /* Average duration in ms of the kernels of one class since the last reset,
  * measured with HIP events on the stream they were launched on; enabled with

@@ -23,7 +23,8 @@ so that two implementations can be compared action by action):
 
   * batch formation: requests are served in arrival order; a prefill batch takes
     requests while the sum of prompt lengths stays within `max_prefill_tokens`
-    (a longer single prompt forms a batch of its own);
+    (a longer single prompt forms a batch of its own) and the pages of its prompts fit the
+    GPU store;
   * "full": the next request's prompt does not fit in what is left of the CPU
     store (capacity counted in tokens; the store is empty whenever a prefill
     phase starts, so there is no fragmentation);
@@ -61,6 +62,8 @@ def simulate(prompt_lens, out_lens, tier_tokens, gpu_pages, max_prefill_tokens, 
             raise ValueError("request %d does not fit the CPU store" % i)
         if out_lens[i] > 1 and pages_of(prompt_lens[i] + out_lens[i] - 1, page_size) > gpu_pages:
             raise ValueError("request %d does not fit the GPU store" % i)
+        if pages_of(prompt_lens[i], page_size) > gpu_pages:
+            raise ValueError("prompt %d does not fit the GPU store" % i)
     trace = []
     waiting = list(range(n))            # arrival order
     store = []                          # CPU store, first in first out
@@ -79,7 +82,7 @@ def simulate(prompt_lens, out_lens, tier_tokens, gpu_pages, max_prefill_tokens, 
         # ---------------- prefill phase: until the store is full or nothing is left to prefill
         full = False
         while waiting and not full:
-            batch, tokens = [], 0
+            batch, tokens, pages = [], 0, 0
             while waiting:
                 r = waiting[0]
                 need = prompt_lens[r] if out_lens[r] > 1 else 0
@@ -88,9 +91,12 @@ def simulate(prompt_lens, out_lens, tier_tokens, gpu_pages, max_prefill_tokens, 
                     break
                 if batch and tokens + prompt_lens[r] > max_prefill_tokens:
                     break
+                if batch and pages + pages_of(prompt_lens[r], page_size) > gpu_pages:
+                    break
                 waiting.pop(0)
                 batch.append(r)
                 tokens += prompt_lens[r]
+                pages += pages_of(prompt_lens[r], page_size)
                 store_used += need
             if not batch:
                 break

@@ -59,6 +59,17 @@ class _LayerWeights(C.Structure):
 _lib = None
 
 
+class OfflineCfg(C.Structure):
+    _fields_ = [("prefill", ShardDesc), ("decode", ShardDesc), ("max_prefill_tokens", C.c_int32),
+                ("max_decode_seqs", C.c_int32), ("reshard_weights", C.c_int32)]
+
+
+class OfflineStats(C.Structure):
+    _fields_ = [("prefill_batches", C.c_int64), ("decode_steps", C.c_int64), ("to_decode", C.c_int64),
+                ("to_prefill", C.c_int64), ("tokens", C.c_int64), ("prefill_seconds", C.c_double),
+                ("decode_seconds", C.c_double), ("switch_seconds", C.c_double), ("total_seconds", C.c_double)]
+
+
 def load_library():
     """Loads libseesaw_rt.so and declares every entry point of seesaw_rt.h."""
     global _lib
@@ -100,6 +111,9 @@ def load_library():
         "ss_load_head": (I, [V, V, V, V]),
         "ss_embed": (I, [V, P(C.c_int32), I, V, V]),
         "ss_lm_head": (I, [V, V, I, V, V]),
+        "ss_get_config": (I, [V, P(ModelCfg), P(RuntimeCfg)]),
+        "ss_offline_run": (I, [V, P(OfflineCfg), C.c_int32, P(C.c_int32), P(C.c_int32), P(C.c_int32), P(C.c_int32),
+                               P(C.c_int32), L, P(L), P(OfflineStats), V]),
         "ss_prof_enable": (I, [V, I]),
         "ss_prof_read": (I, [V, I, P(C.c_double), P(L)]),
         "ss_prof_reset": (I, [V]),
@@ -116,7 +130,7 @@ EXPORTED = ("ss_create ss_destroy ss_last_error ss_load_layer ss_host_weights_pu
             "ss_weights_shard_bytes ss_weights_read ss_layer_prefill ss_layer_decode ss_kv_swap "
             "ss_kv_reshard ss_sync ss_kv_jobs_issued ss_kv_wait ss_kv_free ss_host_tier_release ss_kv_export_dev ss_kv_import_dev "
             "ss_kv_page_table ss_kv_seq_len ss_kv_read ss_host_tier_read ss_host_tier_used_bytes "
-            "ss_kv_free_pages ss_load_head ss_embed ss_lm_head ss_prof_enable ss_prof_read ss_prof_reset").split()
+            "ss_kv_free_pages ss_load_head ss_embed ss_lm_head ss_get_config ss_offline_run ss_prof_enable ss_prof_read ss_prof_reset").split()
 
 
 W_NAMES = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")     # index = SS_W_* of the header
@@ -198,6 +212,32 @@ class Context:
         out = np.empty(n_elems, dtype=np.float32 if self.model.dtype == SS_F32 else np.uint16)
         self._ck(self.lib.ss_weights_read(self.h, C.byref(desc), layer, which, out.ctypes.data))
         return out
+
+    def offline_run(self, prefill, decode, prompts, out_lens, max_prefill_tokens, max_decode_seqs, reshard_weights=True,
+                    stream=0, trace_cap=1 << 20):
+        """prompts: list of int arrays.  Returns (tokens per request, trace as [(code, [ids])], stats dict)."""
+        cfg = OfflineCfg(prefill, decode, max_prefill_tokens, max_decode_seqs, 1 if reshard_weights else 0)
+        n = len(prompts)
+        p_lens = _i32([len(p) for p in prompts])
+        p_toks = _i32(np.concatenate([np.asarray(p) for p in prompts]) if n else [])
+        o_lens = _i32(out_lens)
+        toks = np.zeros(max(int(o_lens.sum()), 1), dtype=np.int32)
+        trace = np.zeros(trace_cap, dtype=np.int32)
+        tlen = C.c_int64(0)
+        st = OfflineStats()
+        i32p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+        self._ck(self.lib.ss_offline_run(self.h, C.byref(cfg), n, i32p(p_lens), i32p(p_toks), i32p(o_lens), i32p(toks),
+                                         i32p(trace), trace_cap, C.byref(tlen), C.byref(st), stream))
+        out, o = [], 0
+        for k in o_lens:
+            out.append(toks[o:o + int(k)].copy())
+            o += int(k)
+        rec, i = [], 0
+        while i < tlen.value:
+            cnt = int(trace[i + 1])
+            rec.append((int(trace[i]), [int(v) for v in trace[i + 2:i + 2 + cnt]]))
+            i += 2 + cnt
+        return out, rec, {f: getattr(st, f) for f, _ in OfflineStats._fields_}
 
     def load_head(self, embed, gf, wlm):
         e, g, w = (np.ascontiguousarray(a) for a in (embed, gf, wlm))

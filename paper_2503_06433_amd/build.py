@@ -11,7 +11,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libseesaw_rt.so")
-SOURCES = ["ss_runtime.hip", "k_elementwise.hip", "k_gemm_generic.hip", "k_gemm_mfma.hip",
+SOURCES = ["ss_runtime.hip", "ss_offline.hip", "k_elementwise.hip", "k_gemm_generic.hip", "k_gemm_mfma.hip",
            "k_attn_generic.hip", "k_attn_mfma.hip", "k_kv_repack.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

@@ -105,6 +105,39 @@ hipError_t embed_rows(int dt, const void* table, const int32_t* ids, void* out, 
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- greedy token choice
+// out[r] = index of the largest of logits[r, 0..V); the lowest index wins a tie.  One block per row.
+__global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restrict__ logits, int V, int32_t* __restrict__ out) {
+    const float* row = logits + (size_t)blockIdx.x * V;
+    float best = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int i = threadIdx.x; i < V; i += 256) {
+        const float v = row[i];
+        if (v > best || (v == best && i < bi)) { best = v; bi = i; }
+    }
+    __shared__ float sv[256];
+    __shared__ int si[256];
+    sv[threadIdx.x] = best;
+    si[threadIdx.x] = bi;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if ((int)threadIdx.x < o) {
+            const float v = sv[threadIdx.x + o];
+            const int i = si[threadIdx.x + o];
+            if (v > sv[threadIdx.x] || (v == sv[threadIdx.x] && i < si[threadIdx.x])) { sv[threadIdx.x] = v; si[threadIdx.x] = i; }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[blockIdx.x] = si[0] == 0x7fffffff ? 0 : si[0];
+}
+
+hipError_t argmax_rows(const float* logits, int n, int V, int32_t* out, hipStream_t s) {
+    if (n <= 0) return hipSuccess;
+    if (V <= 0) return hipErrorInvalidValue;
+    argmax_rows_kernel<<<n, 256, 0, s>>>(logits, V, out);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- RoPE + KV page write
 // One block per (page unit, kv head): the new tokens of one sequence that fall into one page (up to 16),
 // with the q heads of that kv head's group, the k head and the v head.  q is rotated in place; the rotated

@@ -130,6 +130,9 @@ hipError_t kv_scatter(int dt, void* const* k_pools, void* const* v_pools, int n_
 hipError_t slice_transpose(int dt, const void* src, int64_t ld_src, int K, int c0, int n,
                            void* dst, int blk, int blk_stride, int row_off, hipStream_t s);
 
+// out[r] = argmax of logits[r, 0..V), lowest index on ties (greedy decoding).
+hipError_t argmax_rows(const float* logits, int n, int V, int32_t* out, hipStream_t s);
+
 // dst[i] = src[i] for i < n (elements of the model dtype); used for gains.
 hipError_t copy_elems(int dt, const void* src, void* dst, int64_t n, hipStream_t s);
 

@@ -1886,6 +1886,20 @@ int ss_lm_head(ss_ctx* c, const void* x, int n, float* logits, void* stream) {
     return SS_OK;
 }
 
+int ss_get_config(ss_ctx* c, ss_model_cfg* model_out, ss_runtime_cfg* rt_out) {
+    if (!c) return SS_EINVAL;
+    if (model_out) *model_out = c->m;
+    if (rt_out) *rt_out = c->rt;
+    return SS_OK;
+}
+
+// for the offline loop (ss_offline.hip), which reports through the context's error text
+int ss_offline_set_error(ss_ctx* c, const char* text) {
+    if (!c || !text) return SS_EINVAL;
+    c->err = text;
+    return SS_OK;
+}
+
 int ss_prof_enable(ss_ctx* c, int on) {
     if (!c) return SS_EINVAL;
     c->prof_on = on != 0;

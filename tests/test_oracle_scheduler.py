@@ -61,6 +61,12 @@ def test_long_prompt_forms_its_own_batch():
     assert [ids for c, ids in trace if c == P] == [[0], [1], [2]]
 
 
+def test_prefill_batch_is_bounded_by_the_gpu_pages():
+    # pages of 4 tokens, 3 pages: prompts of 3 tokens take a page each, so a batch holds three of them
+    trace, _ = sc.simulate([3] * 5, [2] * 5, tier_tokens=100, gpu_pages=3, max_prefill_tokens=100, max_decode_seqs=8, page_size=4)
+    assert [ids for c, ids in trace if c == P] == [[0, 1, 2], [3, 4]]
+
+
 def _replay_and_check(prompt, out, tier, pages, mpt, mds, page_size=16):
     trace, st = sc.simulate(prompt, out, tier, pages, mpt, mds, page_size)
     n = len(prompt)
@@ -75,6 +81,7 @@ def _replay_and_check(prompt, out, tier, pages, mpt, mds, page_size=16):
             assert stage == "prefill"
             assert ids == list(range(next_waiting, next_waiting + len(ids)))           # arrival order
             assert sum(prompt[i] for i in ids) <= mpt or len(ids) == 1
+            assert sum(sc.pages_of(prompt[i], page_size) for i in ids) <= pages
             next_waiting += len(ids)
             for i in ids:
                 assert state[i] == "waiting"
