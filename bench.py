@@ -83,6 +83,45 @@ def cpu_baseline(work, vals, budget_tokens=16384, n_decode=32):
             "seconds": secs}
 
 
+def offline_loop_bench(torch, wl, ss, hz):
+    """Constant-length requests (prompt 3000 tokens, as in the paper's study of the prompt : output ratio,
+    section 6.5; 64 output tokens), two layers of the configuration-2 shape with a small vocabulary, greedy
+    decoding.  The CPU store holds all, a quarter or a sixteenth of the requests: the smaller it is, the more
+    often the engine changes stage (and reloads its weights)."""
+    base = wl.config2().cfg
+    cfg = wl.ModelCfg(hidden=base.hidden, n_q_heads=base.n_q_heads, n_kv_heads=base.n_kv_heads, head_dim=base.head_dim,
+                      ffn=base.ffn, n_layers=2, vocab=2048, dtype=wl.BF16)
+    n_req, p_len, o_len = 64, 3000, 64
+    raws = [wl.make_layer_weights(cfg, 6001 + l)[1] for l in range(cfg.n_layers)]
+    _, hr = wl.make_head_weights(cfg, 6099)
+    rng = np.random.default_rng(6100)
+    prompts = [rng.integers(0, cfg.vocab, size=p_len).astype(np.int32) for _ in range(n_req)]
+    tok_bytes = 2 * cfg.n_kv_heads * cfg.head_dim * 2 * cfg.n_layers
+    per_seq_pages = -(-(p_len + o_len) // 16)
+    compute = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    runs = {}
+    for label, in_store in (("store_all", n_req), ("store_quarter", n_req // 4), ("store_sixteenth", n_req // 16)):
+        ctx = hz.make_context(cfg, pages=n_req * per_seq_pages, tier_bytes=in_store * p_len * tok_bytes,
+                              pinned_bytes=256 << 20, max_seq_len=4096)
+        ctx.load_head(hr["embed"], hr["gf"], hr["wlm"])
+        for l in range(cfg.n_layers):
+            ctx.host_weights_put(l, raws[l])
+        P, D = hz.pp_desc(cfg), hz.tp_desc(cfg, 1, 0)
+        for rep in range(2):                                 # the first run allocates pools, staging and workspaces
+            _, _, st = ctx.offline_run(P, D, prompts, [o_len] * n_req, 8 * p_len, n_req, True, compute.cuda_stream)
+        total_tokens = n_req * (p_len + o_len)
+        runs[label] = {"tokens_per_s": total_tokens / st["total_seconds"], "output_tokens_per_s": st["tokens"] / st["total_seconds"],
+                       "switches": st["to_decode"] + st["to_prefill"], "prefill_batches": st["prefill_batches"],
+                       "decode_steps": st["decode_steps"], "prefill_s": st["prefill_seconds"],
+                       "decode_s": st["decode_seconds"], "switch_s": st["switch_seconds"], "total_s": st["total_seconds"]}
+        ctx.destroy()
+    print(json.dumps({"metric": "offline loop, prompt+output tokens/s", "unit": "tokens/s", "n_gpus": 1, "dtype": "bf16",
+                      "data": "synthetic", "config": {"workload": "c2_shape_2_layers_const_3000_in_64_out", "requests": n_req,
+                                                      "weight_reshard_at_every_switch": True},
+                      "value": runs["store_all"]["tokens_per_s"], "runs": runs}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -93,6 +132,9 @@ def main():
     ap.add_argument("--pinned-mb", type=int, default=256, help="pinned staging ring of the KV movers (two lanes x two slots)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--offline-loop", action="store_true",
+                    help="instead of the layer step: the whole offline engine loop (scheduler, swaps, weight re-shards) on a "
+                         "two-layer model of the configuration-2 layer shape, for three sizes of the CPU store")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives); --gpus %d is not supported" % args.gpus,
@@ -114,6 +156,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.offline_loop:
+        offline_loop_bench(torch, wl, ss, hz)
+        return
     work = wl.config2()
     cfg = work.cfg
     p_lens = [int(v) for v in work.prefill_lens]
