@@ -101,7 +101,8 @@ def offline_loop_bench(torch, wl, ss, hz):
     compute = torch.cuda.Stream()
     torch.cuda.synchronize()
     runs = {}
-    for label, in_store in (("store_all", n_req), ("store_quarter", n_req // 4), ("store_sixteenth", n_req // 16)):
+    for label, in_store, group in (("store_all", n_req, 0), ("store_all_swap_in_groups_of_4", n_req, 4),
+                                   ("store_quarter", n_req // 4, 0), ("store_sixteenth", n_req // 16, 0)):
         ctx = hz.make_context(cfg, pages=n_req * per_seq_pages, tier_bytes=in_store * p_len * tok_bytes,
                               pinned_bytes=256 << 20, max_seq_len=4096)
         ctx.load_head(hr["embed"], hr["gf"], hr["wlm"])
@@ -109,7 +110,8 @@ def offline_loop_bench(torch, wl, ss, hz):
             ctx.host_weights_put(l, raws[l])
         P, D = hz.pp_desc(cfg), hz.tp_desc(cfg, 1, 0)
         for rep in range(2):                                 # the first run allocates pools, staging and workspaces
-            _, _, st = ctx.offline_run(P, D, prompts, [o_len] * n_req, 8 * p_len, n_req, True, compute.cuda_stream)
+            _, _, st = ctx.offline_run(P, D, prompts, [o_len] * n_req, 8 * p_len, n_req, True, compute.cuda_stream,
+                                       swap_in_group=group)
         total_tokens = n_req * (p_len + o_len)
         runs[label] = {"tokens_per_s": total_tokens / st["total_seconds"], "output_tokens_per_s": st["tokens"] / st["total_seconds"],
                        "switches": st["to_decode"] + st["to_prefill"], "prefill_batches": st["prefill_batches"],

@@ -242,8 +242,9 @@ int ss_get_config(ss_ctx*, ss_model_cfg* model_out, ss_runtime_cfg* rt_out);
  *   decode stage, per iteration: caches requested in the previous iteration
  *     come on board; while the head of the store fits (pages of its final
  *     length, prompt + outputs - 1 tokens, next to those promised to admitted
- *     sequences within gpu_kv_pages; at most max_decode_seqs admitted) its
- *     swap-in is requested; every sequence on board gets one token; finished
+ *     sequences within gpu_kv_pages; at most max_decode_seqs admitted; at most
+ *     swap_in_group per iteration, 0 = no limit, so that decoding can begin
+ *     while the rest of the store is still on its way) its swap-in is requested; every sequence on board gets one token; finished
  *     ones free their pages.  When the store is empty and nothing is arriving:
  *     back to prefilling if requests wait (sequences still decoding keep their
  *     pages and continue in the next decode stage), else on until all are done.
@@ -264,6 +265,7 @@ typedef struct {
     ss_shard_desc prefill, decode;
     int32_t max_prefill_tokens, max_decode_seqs;
     int32_t reshard_weights;
+    int32_t swap_in_group;
 } ss_offline_cfg;
 typedef struct {
     int64_t prefill_batches, decode_steps, to_decode, to_prefill, tokens;

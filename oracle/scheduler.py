@@ -33,7 +33,9 @@ so that two implementations can be compared action by action):
   * GPU room: a sequence is admitted when the pages of its final length
     (prompt + outputs - 1 cached tokens) fit next to those already promised to
     admitted sequences, and the number of admitted sequences stays within
-    `max_decode_seqs`; admission is first-in first-out;
+    `max_decode_seqs`; admission is first-in first-out, at most `swap_in_group`
+    sequences per iteration (0: no limit), so that decoding can begin while the
+    rest of the store is still on its way;
   * arrival of a prefetch: caches requested during iteration t are on board at
     the start of iteration t + 1;
   * sequences still decoding when the store runs empty keep their GPU pages
@@ -50,7 +52,8 @@ def pages_of(tokens, page_size=16):
     return -(-tokens // page_size)
 
 
-def simulate(prompt_lens, out_lens, tier_tokens, gpu_pages, max_prefill_tokens, max_decode_seqs, page_size=16):
+def simulate(prompt_lens, out_lens, tier_tokens, gpu_pages, max_prefill_tokens, max_decode_seqs, page_size=16,
+             swap_in_group=0):
     """Returns (trace, stats).  trace is a list of (code, [request ids]):
     PREFILL batch, TO_DECODE [], SWAP_IN requested, DECODE step over the ids,
     TO_PREFILL [], FINISH ids (after the action that produced their last token)."""
@@ -125,7 +128,8 @@ def simulate(prompt_lens, out_lens, tier_tokens, gpu_pages, max_prefill_tokens, 
             arriving = []
             asked = []
             while store and promised + final_pages(store[0]) <= gpu_pages and \
-                    len(running) + len(asked) < max_decode_seqs:
+                    len(running) + len(asked) < max_decode_seqs and \
+                    (swap_in_group <= 0 or len(asked) < swap_in_group):
                 r = store.pop(0)
                 promised += final_pages(r)
                 asked.append(r)

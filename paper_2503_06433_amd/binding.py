@@ -61,7 +61,7 @@ _lib = None
 
 class OfflineCfg(C.Structure):
     _fields_ = [("prefill", ShardDesc), ("decode", ShardDesc), ("max_prefill_tokens", C.c_int32),
-                ("max_decode_seqs", C.c_int32), ("reshard_weights", C.c_int32)]
+                ("max_decode_seqs", C.c_int32), ("reshard_weights", C.c_int32), ("swap_in_group", C.c_int32)]
 
 
 class OfflineStats(C.Structure):
@@ -214,9 +214,9 @@ class Context:
         return out
 
     def offline_run(self, prefill, decode, prompts, out_lens, max_prefill_tokens, max_decode_seqs, reshard_weights=True,
-                    stream=0, trace_cap=1 << 20):
+                    stream=0, trace_cap=1 << 20, swap_in_group=0):
         """prompts: list of int arrays.  Returns (tokens per request, trace as [(code, [ids])], stats dict)."""
-        cfg = OfflineCfg(prefill, decode, max_prefill_tokens, max_decode_seqs, 1 if reshard_weights else 0)
+        cfg = OfflineCfg(prefill, decode, max_prefill_tokens, max_decode_seqs, 1 if reshard_weights else 0, swap_in_group)
         n = len(prompts)
         p_lens = _i32([len(p) for p in prompts])
         p_toks = _i32(np.concatenate([np.asarray(p) for p in prompts]) if n else [])

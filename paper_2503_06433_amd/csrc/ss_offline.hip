@@ -11,7 +11,8 @@
 //                   finished by its prefill and never enters the store.
 //   decode stage    per iteration: (1) the caches requested in the previous iteration come on board;
 //                   (2) while the head of the store fits (pages of its final length next to those promised
-//                   to admitted sequences, at most max_decode_seqs admitted) its swap-in is requested;
+//                   to admitted sequences, at most max_decode_seqs admitted, at most swap_in_group per
+//                   iteration) its swap-in is requested;
 //                   (3) one token for every sequence on board; finished ones leave and free their pages;
 //                   (4) when the store is empty and nothing is arriving: back to prefilling if requests are
 //                   waiting (sequences still decoding keep their pages and continue in the next decode
@@ -254,7 +255,8 @@ extern "C" int ss_offline_run(ss_ctx* c, const ss_offline_cfg* cfg, int32_t n, c
             }
             std::vector<int> asked;
             while (!store.empty() && promised + final_pages(store.front()) <= gpu_pages &&
-                   (int)(running.size() + asked.size()) < cfg->max_decode_seqs) {
+                   (int)(running.size() + asked.size()) < cfg->max_decode_seqs &&
+                   (cfg->swap_in_group <= 0 || (int)asked.size() < cfg->swap_in_group)) {
                 const int r = store.front();
                 store.pop_front();
                 promised += final_pages(r);

@@ -54,7 +54,7 @@ def _check_tokens(cfg, vals, hv, prompts, out_lens, got, logit_tol):
     return compared
 
 
-def _run(cfg, seed, prompts, out_lens, tier_tokens, gpu_pages, mpt, mds, reshard, stream=0):
+def _run(cfg, seed, prompts, out_lens, tier_tokens, gpu_pages, mpt, mds, reshard, stream=0, group=0):
     vals, raws, hv, hr = _model(cfg, seed)
     ctx = make_context(cfg, pages=gpu_pages, tier_bytes=tier_tokens * _tok_bytes(cfg) + 7, pinned_bytes=4 << 20,
                        max_seq_len=512)
@@ -67,8 +67,10 @@ def _run(cfg, seed, prompts, out_lens, tier_tokens, gpu_pages, mpt, mds, reshard
         for d in (P, D):
             for l in range(cfg.n_layers):
                 ctx.load_layer(d, l, raws[l])
-    toks, trace, stats = ctx.offline_run(P, D, prompts, out_lens, mpt, mds, reshard_weights=reshard, stream=stream)
-    ref_trace, ref_stats = sc.simulate([len(p) for p in prompts], out_lens, tier_tokens, gpu_pages, mpt, mds, cfg.page_size)
+    toks, trace, stats = ctx.offline_run(P, D, prompts, out_lens, mpt, mds, reshard_weights=reshard, stream=stream,
+                                         swap_in_group=group)
+    ref_trace, ref_stats = sc.simulate([len(p) for p in prompts], out_lens, tier_tokens, gpu_pages, mpt, mds, cfg.page_size,
+                                       group)
     assert trace == ref_trace
     for key in ("prefill_batches", "decode_steps", "to_decode", "to_prefill", "tokens"):
         assert stats[key] == ref_stats[key], key
@@ -103,7 +105,7 @@ def test_loop_with_a_store_that_holds_everything_switches_once():
     compute = torch.cuda.Stream()
     torch.cuda.synchronize()
     vals, hv, toks, stats = _run(cfg, 1002, prompts, out_lens, tier_tokens=100000, gpu_pages=64, mpt=64, mds=64, reshard=True,
-                                 stream=compute.cuda_stream)
+                                 stream=compute.cuda_stream, group=3)
     assert (stats["to_decode"], stats["to_prefill"]) == (1, 0)
     assert _check_tokens(cfg, vals, hv, prompts, out_lens, toks, 1e-4) >= 0.9 * sum(out_lens)
 
@@ -114,6 +116,7 @@ def test_loop_bf16_model_trace_and_counts():
     cfg = wl.ModelCfg(hidden=512, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn=1024, n_layers=2, vocab=256, dtype=wl.BF16)
     prompts, out_lens = _requests(cfg, 10, 43, 5, 90, 2, 12)
     _run(cfg, 1003, prompts, out_lens, tier_tokens=200, gpu_pages=12, mpt=128, mds=4, reshard=True)
+    _run(cfg, 1003, prompts, out_lens, tier_tokens=400, gpu_pages=24, mpt=128, mds=8, reshard=True, group=2)
 
 
 def test_loop_argument_errors():

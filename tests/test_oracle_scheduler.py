@@ -56,6 +56,13 @@ def test_max_decode_seqs_limits_the_running_set():
     assert [ids for c, ids in trace if c == IN] == [[0, 1], [2, 3], [4]]
 
 
+def test_hand_trace_swap_in_groups_let_decoding_start_early():
+    trace, st = sc.simulate([4] * 3, [3] * 3, tier_tokens=100, gpu_pages=100, max_prefill_tokens=100, max_decode_seqs=10,
+                            swap_in_group=1)
+    assert trace == [(P, [0, 1, 2]), (TD, []), (IN, [0]), (IN, [1]), (D, [0]), (IN, [2]), (D, [0, 1]), (F, [0]),
+                     (D, [1, 2]), (F, [1]), (D, [2]), (F, [2])]
+
+
 def test_long_prompt_forms_its_own_batch():
     trace, _ = sc.simulate([3, 50, 3], [2, 2, 2], tier_tokens=100, gpu_pages=100, max_prefill_tokens=10, max_decode_seqs=8)
     assert [ids for c, ids in trace if c == P] == [[0], [1], [2]]
@@ -67,8 +74,8 @@ def test_prefill_batch_is_bounded_by_the_gpu_pages():
     assert [ids for c, ids in trace if c == P] == [[0, 1, 2], [3, 4]]
 
 
-def _replay_and_check(prompt, out, tier, pages, mpt, mds, page_size=16):
-    trace, st = sc.simulate(prompt, out, tier, pages, mpt, mds, page_size)
+def _replay_and_check(prompt, out, tier, pages, mpt, mds, page_size=16, group=0):
+    trace, st = sc.simulate(prompt, out, tier, pages, mpt, mds, page_size, group)
     n = len(prompt)
     state = ["waiting"] * n            # waiting -> store -> arriving -> running -> done
     produced = [0] * n
@@ -106,7 +113,7 @@ def _replay_and_check(prompt, out, tier, pages, mpt, mds, page_size=16):
                 assert state[i] == "store"
                 state[i] = "arriving"
                 promised += sc.pages_of(prompt[i] + out[i] - 1, page_size)
-            assert promised <= pages
+            assert promised <= pages and (group <= 0 or len(ids) <= group)
             # first in first out: everything still in the store arrived later
             assert all(j > max(ids) for j in range(n) if state[j] == "store")
             arriving_prev = arriving_prev + ids
@@ -149,7 +156,7 @@ def test_invariants_on_random_workloads(seed):
     tier = int(max(prompt) + rng.integers(0, 600))
     page = 16
     pages = int(max(sc.pages_of(p + o - 1, page) for p, o in zip(prompt, out)) + rng.integers(0, 40))
-    _replay_and_check(prompt, out, tier, pages, int(rng.integers(50, 400)), int(rng.integers(1, 12)), page)
+    _replay_and_check(prompt, out, tier, pages, int(rng.integers(50, 400)), int(rng.integers(1, 12)), page, seed % 3)
 
 
 def test_unbounded_store_changes_stage_once_and_tight_store_once_per_request():
