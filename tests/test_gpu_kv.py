@@ -184,3 +184,38 @@ def test_kv_reshard_single_call_and_pp_round_trip():
         for l in range(L):
             assert np.array_equal(ctx.kv_read(src, s, l, n_kv), complete[s][l])
     ctx.destroy()
+
+
+def test_mixed_layout_tp2pp2_to_tp4_shares_bit_exact():
+    """Mixed strategies (the paper's TP2PP2 -> TP4 style of switch, section 6.2): a device's share is a
+    tensor-parallel shard of a run of layers.  Four devices of the prefill layout (2 stages x 2 shards) push
+    their layers x heads blocks into the tier, where they form the complete cache; the devices of the decode
+    layout (4 shards, all layers) and of a second mixed layout (2 stages x 4 shards) pull theirs."""
+    dtype, d, n_kv, L = wl.BF16, 128, 4, 4
+    cfg = _cfg(dtype, d=d, n_kv=n_kv, n_layers=L)
+    lens = {3: 40, 5: 17, 6: 130}
+    ids = list(lens)
+    complete = {s: _rand_bits((L, 2, n_kv, n, d), 70 + s, dtype) for s, n in lens.items()}
+    tier_bytes = sum(kt.tier_seq_elems(L, n_kv, d, n) for n in lens.values()) * 2
+    ctx = make_context(cfg, pages=32, tier_bytes=tier_bytes, pinned_bytes=2 << 20)
+    for stage in range(2):
+        for shard in range(2):
+            desc = tp_desc(cfg, 2, shard, 2 * stage, 2 * stage + 2)
+            _import(ctx, desc, cfg, ids, [complete[s][2 * stage:2 * stage + 2, :, 2 * shard:2 * shard + 2] for s in ids])
+            ctx.kv_swap(desc, ss.SS_OUT, ids)
+    ctx.sync()
+    for s in ids:                                            # the tier holds the complete cache, layer by layer
+        for l in range(L):
+            assert np.array_equal(ctx.host_tier_read(s, l, lens[s]).reshape(2, n_kv, lens[s], d), complete[s][l])
+    targets = [(4, i, 0, L) for i in range(4)] + [(4, i, 2 * st, 2 * st + 2) for st in range(2) for i in range(4)]
+    for k, i, lb, le in targets:
+        desc = tp_desc(cfg, k, i, lb, le)
+        ctx.kv_swap(desc, ss.SS_IN, ids)
+        ctx.sync()
+        nh = n_kv // k
+        for s in ids:
+            for l in range(lb, le):
+                assert np.array_equal(ctx.kv_read(desc, s, l, nh), complete[s][l][:, i * nh:(i + 1) * nh])
+    ctx.host_tier_release(ids)
+    assert ctx.host_tier_used_bytes() == 0
+    ctx.destroy()

@@ -169,3 +169,24 @@ def test_reshard_error_paths():
         ctx.reshard_weights(None, ss.ShardDesc(ss.SS_TP, 3, 0, 0, 1))
     assert e.value.code == ss.SS_EINVAL
     ctx.destroy()
+
+
+def test_mixed_layout_weight_shares_bit_exact():
+    """A device's share under a mixed strategy is a tensor-parallel shard of a run of layers: re-sharding
+    from a (2 shards x 2 stages) share to a (4 shards, all layers) share and on to a (4 x 2) share."""
+    cfg = wl.ModelCfg(n_layers=4, dtype=wl.BF16, **SHAPES["mha_d128"])
+    _, raws = _model(cfg, 800)
+    ctx = make_context(cfg, pages=8)
+    for l in range(cfg.n_layers):
+        ctx.host_weights_put(l, raws[l])
+    a = tp_desc(cfg, 2, 1, 2, 4)                # shard 1 of 2, second stage
+    b = tp_desc(cfg, 4, 3)                      # shard 3 of 4, all layers
+    c = tp_desc(cfg, 4, 0, 0, 2)                # shard 0 of 4, first stage
+    ctx.reshard_weights(None, a)
+    _check_shard(ctx, cfg, raws, a, 2, 1)
+    ctx.reshard_weights(a, b)
+    _check_shard(ctx, cfg, raws, b, 4, 3)
+    ctx.reshard_weights(b, c)
+    _check_shard(ctx, cfg, raws, c, 4, 0)
+    assert ctx.weights_shard_bytes(c) * 2 == ctx.weights_shard_bytes(b)
+    ctx.destroy()
