@@ -16,6 +16,8 @@
 // round-robin) works on a contiguous run of tiles, and runs are ordered in
 // groups of 8 tile rows, so that the A and Wt slices an XCD touches at one time
 // stay in its own L2.
+#include <cstdlib>
+
 #include "ss_device.h"
 #include "ss_kernels.h"
 
@@ -280,14 +282,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
                                                                const bf16_t* __restrict__ Wt, bf16_t* __restrict__ C,
                                                                int ldc, const bf16_t* __restrict__ R, int M, int N,
                                                                int K, int tiles_m, int tiles_n, int per_xcd,
-                                                               int cus_per_xcd, int it0, int max_it) {
+                                                               int cus_per_xcd, int it0, int max_it, int GM) {
     constexpr int BM = 256, BN = 256;
     constexpr int STAGE = (BM + BN) * 128;       // bytes per ring stage
     constexpr int LPS = 16;                      // loads per wave per slice
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
     // ---- this block's tiles: XCD x (blocks are dealt to the XCDs round-robin) owns the contiguous run
-    // [x * per_xcd, (x+1) * per_xcd) of tiles, ordered in groups of 8 tile rows, so that the slices an XCD
+    // [x * per_xcd, (x+1) * per_xcd) of tiles, ordered in groups of GM tile rows, so that the slices an XCD
     // touches at one time stay in its own L2; inside the run the XCD's blocks take tiles round-robin
     const int xcd = blockIdx.x & 7, cu = blockIdx.x >> 3;
     const int n_tiles = tiles_m * tiles_n;
@@ -298,7 +300,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
     if (first >= xcd_end) return;
     int nt_local = (xcd_end - first + cus_per_xcd - 1) / cus_per_xcd;
     nt_local = nt_local < max_it ? nt_local : max_it;
-    constexpr int GM = 8;
     auto tile_origin = [&](int it, int& m0, int& n0) {
         const int logical = first + it * cus_per_xcd;
         const int group_size = GM * tiles_n;
@@ -563,6 +564,13 @@ static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16
     const unsigned grid = 8 * (unsigned)(per_xcd < cus_per_xcd ? per_xcd : cus_per_xcd);
     const int rounds_total = (per_xcd + cus_per_xcd - 1) / cus_per_xcd;
     const int step = max_rounds > 0 ? max_rounds : rounds_total;
+    // Tile rows per group of the walk: the 32 CUs of an XCD cover GM x 32/GM tiles at a time, so token
+    // slices are re-fetched (tiles_n * GM / 32) times and weight slices (tiles_m / GM) times.  The token
+    // operand is the larger one here, so groups are short, shorter still for wide outputs (measured on the
+    // 7B shapes, us for QKV / O / gate+up / down: GM 8: 1393 / 531 / 2914 / 1479, GM 4: 1378 / 541 / 2755 /
+    // 1447, GM 2: 1404 / 572 / 2696 / 1519).
+    static const int gm_env = getenv("SS_GEMM_GROUP_ROWS") ? atoi(getenv("SS_GEMM_GROUP_ROWS")) : 0;
+    const int gm_rows = gm_env > 0 ? gm_env : (tiles_n >= 64 ? 2 : 4);
 #define SS_LAUNCH(E)                                                                                            \
     {                                                                                                           \
         auto kfn = gemm_mfma_stream_kernel<E>;                                                                  \
@@ -575,7 +583,7 @@ static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16
         }                                                                                                       \
         for (int it0 = 0; it0 < rounds_total; it0 += step)                                                      \
             kfn<<<grid, 256, STREAM_LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd,        \
-                                              cus_per_xcd, it0, step);                                          \
+                                              cus_per_xcd, it0, step, gm_rows);                                 \
     }
     switch (epi) {
         case EPI_STORE: SS_LAUNCH(EPI_STORE) break;
