@@ -196,21 +196,31 @@ __device__ __forceinline__ void dma16a(const void* gptr, uint32_t lds_addr) {
 
 template <int D>
 __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
-                                                               int n_q, int n_kv, BatchMeta bm,
+                                                               int n_q, int n_kv, int nqb, BatchMeta bm,
                                                                const bf16_t* __restrict__ k_pool,
                                                                const bf16_t* __restrict__ v_pool, float scale_log2e) {
     static_assert(D == 128, "layout below assumes 256-byte K rows");
     constexpr int KS = D / 16, DT = D / 32, NS = 2;
     constexpr int KBYTES = 64 * D * 2, STAGE = 2 * KBYTES;     // 16 KB of K + 16 KB of V^T
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    const int sq = blockIdx.z, a = blockIdx.y;
+    // Block -> (sequence, q head, block of 256 queries).  Blocks are dealt to the 8 XCDs round-robin by their
+    // linear id; all blocks that read the K and V pages of one (sequence, kv head) -- the query blocks of
+    // every q head of its group -- are given ids of the same residue, so that they run on one XCD and those
+    // pages are fetched into one L2 instead of eight.  The blocks with the most cached tokens to visit (the
+    // last queries) come first.
+    const int G = n_q / n_kv;
+    const int per_unit = G * nqb;
+    const int chunk = blockIdx.x / (8 * per_unit), rr = blockIdx.x % (8 * per_unit);
+    const int unit = chunk * 8 + (rr & 7), j = rr >> 3;
+    if (unit >= n_kv * bm.n_seqs) return;                      // whole block: before any barrier
+    const int sq = unit / n_kv, g = unit - sq * n_kv;
+    const int a = g * G + j % G;
     const int q_begin = bm.cu_q[sq], q_len = bm.cu_q[sq + 1] - q_begin;
-    const int qb0 = blockIdx.x * 256;
+    const int qb0 = (nqb - 1 - j / G) * 256;
     if (qb0 >= q_len) return;                                  // whole block: before any barrier
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int before = bm.kv_before[sq];
-    const int g = a / (n_q / n_kv);
     const int lq = lane & 31, g2 = lane >> 5;
     const int q0 = qb0 + wave * 32;
     const int qi = q0 + lq;
@@ -380,8 +390,11 @@ hipError_t attn_prefill(int dt, const void* qkv, void* out, int n_q, int n_kv, c
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    dim3 grid((bm.max_q_len + 255) / 256, n_q, bm.n_seqs);
-    attn_prefill_lds_kernel<128><<<grid, 512, LDS, s>>>((const bf16_t*)qkv, (bf16_t*)out, n_q, n_kv, bm,
+    const int nqb = (bm.max_q_len + 255) / 256;
+    const long long units = (long long)n_kv * bm.n_seqs;            // (sequence, kv head)
+    const long long n_blocks = (units + 7) / 8 * 8 * (n_q / n_kv) * nqb;
+    if (n_blocks > 0x7fffffffll) return hipErrorInvalidValue;
+    attn_prefill_lds_kernel<128><<<(unsigned)n_blocks, 512, LDS, s>>>((const bf16_t*)qkv, (bf16_t*)out, n_q, n_kv, nqb, bm,
                                                         (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, sl2);
     return hipGetLastError();
 }
