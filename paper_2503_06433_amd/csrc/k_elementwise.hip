@@ -139,18 +139,20 @@ hipError_t argmax_rows(const float* logits, int n, int V, int32_t* out, hipStrea
 }
 
 // ---------------------------------------------------------------- RoPE + KV page write
-// One block per (page unit, kv head): the new tokens of one sequence that fall into one page (up to 16),
-// with the q heads of that kv head's group, the k head and the v head.  q is rotated in place; the rotated
+// One block per (page unit, HB kv heads): the new tokens of one sequence that fall into one page (up to 16),
+// with the q heads of those kv heads' groups, the k heads and the v heads (several heads per block at
+// prefill sizes: a thread loads the cos / sin values of its token and chunk once and reuses them over the
+// heads, and has several independent rows in flight).  q is rotated in place; the rotated
 // k rows land in the page as [slot][d] (one contiguous run); v lands transposed, [d][vslot(slot)].  A full
 // page of v goes through an LDS tile and is written as one contiguous 16-byte-per-lane run; partial pages
 // (the first and last page of a prompt, every decode step) write element by element.
-template <typename T>
+template <typename T, int HB>
 __global__ __launch_bounds__(256) void rope_kvwrite_kernel(T* __restrict__ qkv, int n_q, int n_kv, int d,
                                                            const float* __restrict__ rope, BatchMeta bm,
                                                            T* __restrict__ k_pool, T* __restrict__ v_pool) {
     constexpr int V = VecOf<T>::N;
     constexpr int PS = 16;
-    const int u = blockIdx.x, g = blockIdx.y;
+    const int u = blockIdx.x, g0 = blockIdx.y * HB;          // HB kv heads per block
     const int sq = bm.unit_seq[u], tok0 = bm.unit_tok0[u], pos0 = bm.unit_pos0[u], cnt = bm.unit_cnt[u];
     const int page = bm.page_tables[(size_t)sq * bm.pt_stride + pos0 / PS];
     const int slot0 = pos0 % PS;
@@ -159,59 +161,75 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(T* __restrict__ qkv, 
     const int cph = half / V;                     // 16-byte chunk pairs per head row
     const size_t row_stride = (size_t)(n_q + 2 * n_kv) * d;
     const size_t page_elems = (size_t)n_kv * PS * d;
-    T* kpage = k_pool + (size_t)page * page_elems + (size_t)g * PS * d;
-    T* vpage = v_pool + (size_t)page * page_elems + (size_t)g * PS * d;
+    const int nh = (n_kv - g0) < HB ? (n_kv - g0) : HB;      // kv heads of this block
 
-    // ---- rotation: (G q heads + the k head) x tokens x chunk pairs
-    const int per_head = cnt * cph;
-    for (int w = threadIdx.x; w < (G + 1) * per_head; w += 256) {
-        const int hh = w / per_head, r = w % per_head;
+    // ---- rotation: a thread keeps one (token, chunk pair) and its cos / sin values and walks over the
+    // head slots (the G q heads and the k head of each kv head of the block)
+    const int per_head = cnt * cph;               // <= 128 for d <= 128
+    const int lanes = per_head < 256 ? per_head : 256;
+    const int stride_h = 256 / (lanes > 0 ? lanes : 1);      // head slots processed side by side
+    if (per_head > 0 && (int)threadIdx.x < lanes * stride_h) {
+        const int r = threadIdx.x % lanes, h_first = threadIdx.x / lanes;
         const int tl = r / cph, i0 = (r % cph) * V;
-        const int head = hh < G ? g * G + hh : n_q + g;          // column block of the qkv row
-        T* lo_p = qkv + (size_t)(tok0 + tl) * row_stride + (size_t)head * d + i0;
-        T* hi_p = lo_p + half;
-        const float* cs = rope + (size_t)(pos0 + tl) * d;        // [half][2] = cos, sin interleaved
-        float lo[V], hi[V], olo[V], ohi[V];
-        unpack16<T>(*reinterpret_cast<const vec16*>(lo_p), lo);
-        unpack16<T>(*reinterpret_cast<const vec16*>(hi_p), hi);
+        const float* cs = rope + (size_t)(pos0 + tl) * d + 2 * i0;    // [half][2] = cos, sin interleaved
+        float c[V], sn[V];
 #pragma unroll
-        for (int j = 0; j < V; ++j) {
-            const float c = cs[2 * (i0 + j)], sn = cs[2 * (i0 + j) + 1];
-            olo[j] = lo[j] * c - hi[j] * sn;
-            ohi[j] = hi[j] * c + lo[j] * sn;
-        }
-        const vec16 plo = pack16<T>(olo), phi = pack16<T>(ohi);
-        if (hh < G) {
-            *reinterpret_cast<vec16*>(lo_p) = plo;
-            *reinterpret_cast<vec16*>(hi_p) = phi;
-        } else {
-            T* dst = kpage + (size_t)(slot0 + tl) * d + i0;
-            *reinterpret_cast<vec16*>(dst) = plo;
-            *reinterpret_cast<vec16*>(dst + half) = phi;
+        for (int j = 0; j < V; ++j) { c[j] = cs[2 * j]; sn[j] = cs[2 * j + 1]; }
+        const int slots = nh * (G + 1);
+        T* row = qkv + (size_t)(tok0 + tl) * row_stride + i0;
+#pragma unroll 4
+        for (int hs = h_first; hs < slots; hs += stride_h) {
+            const int gl = hs / (G + 1), hh = hs % (G + 1);
+            const int g = g0 + gl;
+            const int head = hh < G ? g * G + hh : n_q + g;      // column block of the qkv row
+            T* lo_p = row + (size_t)head * d;
+            T* hi_p = lo_p + half;
+            float lo[V], hi[V], olo[V], ohi[V];
+            unpack16<T>(*reinterpret_cast<const vec16*>(lo_p), lo);
+            unpack16<T>(*reinterpret_cast<const vec16*>(hi_p), hi);
+#pragma unroll
+            for (int j = 0; j < V; ++j) {
+                olo[j] = lo[j] * c[j] - hi[j] * sn[j];
+                ohi[j] = hi[j] * c[j] + lo[j] * sn[j];
+            }
+            const vec16 plo = pack16<T>(olo), phi = pack16<T>(ohi);
+            if (hh < G) {
+                *reinterpret_cast<vec16*>(lo_p) = plo;
+                *reinterpret_cast<vec16*>(hi_p) = phi;
+            } else {
+                T* dst = k_pool + (size_t)page * page_elems + (size_t)g * PS * d + (size_t)(slot0 + tl) * d + i0;
+                *reinterpret_cast<vec16*>(dst) = plo;
+                *reinterpret_cast<vec16*>(dst + half) = phi;
+            }
         }
     }
 
-    // ---- v: element (token tl, e) -> vpage[e][vslot(slot0 + tl)]
-    const T* vcol = qkv + (size_t)tok0 * row_stride + (size_t)(n_q + n_kv + g) * d;
-    __shared__ T tile[PS][128 + V];
-    if (cnt == PS && d == 128) {                   // block-uniform
-        for (int w = threadIdx.x; w < PS * (128 / V); w += 256) {
-            const int tl = w / (128 / V), c = w % (128 / V);
-            *reinterpret_cast<vec16*>(&tile[tl][c * V]) = *reinterpret_cast<const vec16*>(vcol + (size_t)tl * row_stride + c * V);
+    // ---- v: element (token tl, e) of head g -> vpage[e][vslot(slot0 + tl)]
+    __shared__ T tile[HB][PS][128 + V];
+    if (cnt == PS && d == 128) {                   // block-uniform: whole pages go through LDS
+        constexpr int CPR = 128 / V;               // 16-byte chunks per row
+        for (int w = threadIdx.x; w < nh * PS * CPR; w += 256) {
+            const int gl = w / (PS * CPR), tl = (w / CPR) % PS, cc = w % CPR;
+            const T* vcol = qkv + (size_t)(tok0 + tl) * row_stride + (size_t)(n_q + n_kv + g0 + gl) * d;
+            *reinterpret_cast<vec16*>(&tile[gl][tl][cc * V]) = *reinterpret_cast<const vec16*>(vcol + cc * V);
         }
         __syncthreads();
         // 16-byte piece `pc` of row e holds positions [V*pc, V*pc + V); position p is token vslot(p) (an involution)
-        for (int w = threadIdx.x; w < 128 * (PS / V); w += 256) {
-            const int e = w / (PS / V), pc = w % (PS / V);
+        constexpr int PPR = PS / V;
+        for (int w = threadIdx.x; w < nh * 128 * PPR; w += 256) {
+            const int gl = w / (128 * PPR), e = (w / PPR) % 128, pc = w % PPR;
             union { vec16 v; T x[V]; } o;
 #pragma unroll
-            for (int j = 0; j < V; ++j) o.x[j] = tile[vslot(pc * V + j)][e];
+            for (int j = 0; j < V; ++j) o.x[j] = tile[gl][vslot(pc * V + j)][e];
+            T* vpage = v_pool + (size_t)page * page_elems + (size_t)(g0 + gl) * PS * d;
             *reinterpret_cast<vec16*>(vpage + (size_t)e * PS + pc * V) = o.v;
         }
     } else {
-        for (int w = threadIdx.x; w < cnt * d; w += 256) {
-            const int tl = w / d, e = w % d;
-            vpage[(size_t)e * PS + vslot(slot0 + tl)] = vcol[(size_t)tl * row_stride + e];
+        for (int w = threadIdx.x; w < nh * cnt * d; w += 256) {
+            const int gl = w / (cnt * d), tl = (w / d) % cnt, e = w % d;
+            const T* vcol = qkv + (size_t)(tok0 + tl) * row_stride + (size_t)(n_q + n_kv + g0 + gl) * d;
+            T* vpage = v_pool + (size_t)page * page_elems + (size_t)(g0 + gl) * PS * d;
+            vpage[(size_t)e * PS + vslot(slot0 + tl)] = vcol[e];
         }
     }
 }
@@ -222,13 +240,20 @@ hipError_t rope_kvwrite(int dt, void* qkv, int n_q, int n_kv, const float* rope_
     const int V = dt == F32 ? 4 : 8;
     if (kv.d % (2 * V) != 0 || kv.n_heads != n_kv || kv.page_size != 16 || n_kv <= 0 || n_q % n_kv != 0 || n_kv > 65535)
         return hipErrorInvalidValue;
-    dim3 grid(bm.n_units, n_kv);
-    if (dt == F32)
-        rope_kvwrite_kernel<float><<<grid, 256, 0, s>>>((float*)qkv, n_q, n_kv, kv.d, rope_table, bm,
-                                                        (float*)kv.k_pool, (float*)kv.v_pool);
-    else
-        rope_kvwrite_kernel<bf16_t><<<grid, 256, 0, s>>>((bf16_t*)qkv, n_q, n_kv, kv.d, rope_table, bm,
-                                                         (bf16_t*)kv.k_pool, (bf16_t*)kv.v_pool);
+    if (kv.d > 128) return hipErrorInvalidValue;
+    if (dt == F32) {
+        dim3 grid(bm.n_units, n_kv);
+        rope_kvwrite_kernel<float, 1><<<grid, 256, 0, s>>>((float*)qkv, n_q, n_kv, kv.d, rope_table, bm,
+                                                           (float*)kv.k_pool, (float*)kv.v_pool);
+    } else if (n_kv >= 4 && bm.n_units >= 256) {    // prefill-sized: several kv heads per block (cos / sin reused)
+        dim3 grid(bm.n_units, (n_kv + 3) / 4);
+        rope_kvwrite_kernel<bf16_t, 4><<<grid, 256, 0, s>>>((bf16_t*)qkv, n_q, n_kv, kv.d, rope_table, bm,
+                                                            (bf16_t*)kv.k_pool, (bf16_t*)kv.v_pool);
+    } else {
+        dim3 grid(bm.n_units, n_kv);
+        rope_kvwrite_kernel<bf16_t, 1><<<grid, 256, 0, s>>>((bf16_t*)qkv, n_q, n_kv, kv.d, rope_table, bm,
+                                                            (bf16_t*)kv.k_pool, (bf16_t*)kv.v_pool);
+    }
     return hipGetLastError();
 }
 
