@@ -599,9 +599,9 @@ static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16
 
 bool gemm_mfma_supported(int M, int N, int K, int lda, int ldc, int epi) {
     if (K % 64 != 0 || lda % 8 != 0) return false;
-    if (epi == EPI_STORE_F32) return false;
+    if (epi == EPI_STORE_F32 && ldc != N) return false;      // written as plane 0 of the fp32 partials: dense rows
     if (epi == EPI_SWIGLU && (N % 64 != 0)) return false;
-    (void)M; (void)ldc;
+    (void)M;
     return true;
 }
 
@@ -623,7 +623,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
         float o = 0.f;
         for (int s = 0; s < S; ++s) o += P[s * plane + (size_t)m * N + j];
         if (EPI == EPI_RESIDUAL) o += bf2f(R[(size_t)m * ldc + j]);
-        C[(size_t)m * ldc + j] = f2bf(o);
+        if (EPI == EPI_STORE_F32) reinterpret_cast<float*>(C)[(size_t)m * ldc + j] = o;
+        else C[(size_t)m * ldc + j] = f2bf(o);
     }
 }
 
@@ -660,11 +661,13 @@ static hipError_t launch_cfg(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t*
                 splitk_reduce_kernel<EPI_RESIDUAL><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N);
                 break;
             case EPI_SWIGLU: splitk_reduce_kernel<EPI_SWIGLU><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N); break;
+            case EPI_STORE_F32: splitk_reduce_kernel<EPI_STORE_F32><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N); break;
             default: return hipErrorInvalidValue;
         }
         return hipGetLastError();
     }
     switch (epi) {
+        case EPI_STORE_F32: SS_LAUNCH(EPI_PARTIAL, C) break;      // one K range: plane 0 of the partials is the fp32 result
         case EPI_STORE: SS_LAUNCH(EPI_STORE, C) break;
         case EPI_RESIDUAL:
             if (!R) return hipErrorInvalidValue;
@@ -686,7 +689,7 @@ hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int l
     // Smaller outputs (decode batches) are bound by streaming the weights: 128 x 128 tiles with split-K
     // (partials in fp32, summed by a small second kernel).
     const long long big = (long long)((M + 255) / 256) * ((N + 255) / 256);
-    if (big >= 256 && gemm_mfma_stream_supported(C, R, ldc, M, N, K, lda, epi))
+    if (big >= 256 && epi != EPI_STORE_F32 && gemm_mfma_stream_supported(C, R, ldc, M, N, K, lda, epi))
         return launch_stream(a, lda, w, c, ldc, r, M, N, K, epi, s, max_rounds);
     const long long mid = (long long)((M + 127) / 128) * ((N + 127) / 128);
     // split K until every CU has a block, but only while the fp32 partials (8*S*M*N bytes written and

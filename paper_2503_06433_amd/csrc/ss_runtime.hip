@@ -1882,7 +1882,7 @@ int ss_lm_head(ss_ctx* c, const void* x, int n, float* logits, void* stream) {
     if (rc) return rc;
     K_TRY(c, ssk::rmsnorm(c->dt, x, c->d_gf, c->ws_h.p, n, c->m.hidden, c->m.rms_eps, st));
     K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, c->m.hidden, c->d_wlm_t, logits, c->m.vocab, nullptr, n, c->m.vocab,
-                          c->m.hidden, ssk::EPI_STORE_F32, true, st));
+                          c->m.hidden, ssk::EPI_STORE_F32, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
     return SS_OK;
 }
 

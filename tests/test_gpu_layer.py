@@ -280,3 +280,20 @@ def test_descriptor_and_argument_errors():
         ctx.layer_prefill(td, 0, ss.SS_BOTH, [1], [4], [0], x, y)
     assert e.value.code == ss.SS_EINVAL
     ctx.destroy()
+
+
+@pytest.mark.parametrize("n_rows,vocab", [(5, 256), (70, 2048), (300, 1024)])
+def test_lm_head_bf16_matches_oracle(n_rows, vocab):
+    """Final norm + LM head of a bf16 model (fp32 logits out of the MFMA GEMM, with and without split-K)."""
+    cfg = wl.ModelCfg(hidden=512, n_q_heads=4, n_kv_heads=4, head_dim=128, ffn=1024, n_layers=1, vocab=vocab, dtype=wl.BF16)
+    hv, hr = wl.make_head_weights(cfg, 77)
+    ctx = make_context(cfg, pages=4)
+    ctx.load_head(hr["embed"], hr["gf"], hr["wlm"])
+    xv, xr = wl.make_activations((n_rows, cfg.hidden), 78, cfg.dtype)
+    logits = torch.empty((n_rows, vocab), device="cuda", dtype=torch.float32)
+    for rep in range(2):                      # the second call finds the split-K workspace of the layer calls, if any
+        ctx.lm_head(to_device(xr, cfg.dtype), n_rows, logits)
+        torch.cuda.synchronize()
+        ref = lm.lm_logits(cfg, hv, xv)
+        assert rel_err(logits.cpu().numpy(), ref) <= tol(cfg.dtype)
+    ctx.destroy()
