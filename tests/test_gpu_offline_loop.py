@@ -148,4 +148,6 @@ def test_loop_argument_errors():
     assert e.value.code == ss.SS_ENOMEM
     toks, trace, stats = ctx.offline_run(P, D, one, [3], 128, 4)    # and the context is still usable
     assert stats["tokens"] == 3 and len(toks[0]) == 3
+    toks, trace, stats = ctx.offline_run(P, D, [], [], 128, 4)      # nothing to do
+    assert toks == [] and trace == [] and stats["tokens"] == 0
     ctx.destroy()
