@@ -297,3 +297,29 @@ def test_lm_head_bf16_matches_oracle(n_rows, vocab):
         ref = lm.lm_logits(cfg, hv, xv)
         assert rel_err(logits.cpu().numpy(), ref) <= tol(cfg.dtype)
     ctx.destroy()
+
+
+def test_prefill_many_pages_six_kv_heads_cache_matches_oracle():
+    """A prompt batch of more than 256 page units with a kv head count that is not a multiple of four: the
+    RoPE + page-write kernel takes four kv heads per block at this size, the last block two; the attention
+    block's output and the cache it leaves behind are compared with the oracle."""
+    cfg = wl.ModelCfg(hidden=768, n_q_heads=12, n_kv_heads=6, head_dim=128, ffn=1024, n_layers=1, dtype=wl.BF16)
+    vals, raws = _weights(cfg, 910)
+    lens = [1500, 1307, 1390, 5]
+    T = sum(lens)
+    xv, xr = wl.make_activations((T, cfg.hidden), 911, cfg.dtype)
+    ctx = make_context(cfg, pages=300)
+    d = pp_desc(cfg)
+    _load(ctx, d, cfg, raws)
+    ids = [3, 4, 5, 6]
+    batch = [(s, n, 0) for s, n in zip(ids, lens)]
+    out = empty_like_acts(T, cfg.hidden, cfg.dtype)
+    ctx.layer_prefill(d, 0, ss.SS_ATTN, ids, lens, [0] * 4, to_device(xr, cfg.dtype), out)
+    torch.cuda.synchronize()
+    cache = lm.KVCache(cfg)
+    ref = xv + lm.attn_block(cfg, vals[0], xv, batch, cache, 0, 1, 0, _round_kv(cfg))
+    assert rel_err(to_f64(out, cfg.dtype), ref) <= tol(cfg.dtype)
+    for sid, n in zip(ids, lens):
+        got = wl.storage_to_f64(ctx.kv_read(d, sid, 0, cfg.n_kv_heads), cfg.dtype)
+        assert rel_err(got, cache.data[sid][0]) <= tol(cfg.dtype)
+    ctx.destroy()
