@@ -134,6 +134,8 @@ def main():
     ap.add_argument("--pinned-mb", type=int, default=256, help="pinned staging ring of the KV movers (two lanes x two slots)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--dtype", choices=["bf16", "f16"], default="bf16",
+                    help="16-bit storage type of the model (bf16: the configuration BASELINE.json names; f16: the paper's own)")
     ap.add_argument("--offline-loop", action="store_true",
                     help="instead of the layer step: the whole offline engine loop (scheduler, swaps, weight re-shards) on a "
                          "two-layer model of the configuration-2 layer shape, for three sizes of the CPU store")
@@ -163,6 +165,7 @@ def main():
         return
     work = wl.config2()
     cfg = work.cfg
+    cfg.dtype = wl.F16 if args.dtype == "f16" else wl.BF16
     p_lens = [int(v) for v in work.prefill_lens]
     d_lens = [int(v) for v in work.decode_kv_lens]
     Tp, B = sum(p_lens), len(d_lens)
@@ -288,7 +291,7 @@ def main():
     out = {
         "metric": "prefill+decode tokens/s per GPU shard", "value": value, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": work.name, "prefill_tokens": Tp, "prefill_prompts": len(p_lens),
                    "decode_seqs": B, "decode_kv_tokens": decode_tokens, "k": 1, "layers": 1,
                    "reshard_in_step": do_reshard},

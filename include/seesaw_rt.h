@@ -10,7 +10,8 @@
  *   - "host" pointers are ordinary process memory, "device" pointers are HIP
  *     device memory of the context's GPU; every argument says which it is.
  *   - activations are row-major [tokens, hidden] in the model dtype (SS_F32:
- *     IEEE float, SS_BF16: 16-bit brain float, raw bits) and are CALLER-owned
+ *     IEEE float, SS_BF16: 16-bit brain float, SS_F16: IEEE half, raw bits;
+ *     the 16-bit types accumulate in fp32) and are CALLER-owned
  *     device buffers; weights are copied by the library at load time; KV pages,
  *     the host tier, the pinned staging ring and the side stream are
  *     library-owned.
@@ -28,7 +29,7 @@
 extern "C" {
 #endif
 
-enum { SS_F32 = 0, SS_BF16 = 1 };                 /* model dtype */
+enum { SS_F32 = 0, SS_BF16 = 1, SS_F16 = 2 };     /* model dtype (the paper runs in IEEE half, section 6.1) */
 enum { SS_PP = 0, SS_TP = 1 };                    /* shard mode */
 enum { SS_ATTN = 1, SS_MLP = 2, SS_BOTH = 3,      /* phase */
        SS_NO_RESIDUAL = 4 };                      /* flag OR-ed into phase */
@@ -42,7 +43,7 @@ typedef struct ss_ctx ss_ctx;
 typedef struct {
     int32_t hidden, n_q_heads, n_kv_heads, head_dim, ffn, n_layers, vocab;
     float rms_eps, rope_base;
-    int32_t dtype;       /* SS_F32 | SS_BF16 */
+    int32_t dtype;       /* SS_F32 | SS_BF16 | SS_F16 */
     int32_t page_size;   /* tokens per KV page */
 } ss_model_cfg;
 

@@ -7,7 +7,7 @@ import os
 
 import numpy as np
 
-SS_F32, SS_BF16 = 0, 1
+SS_F32, SS_BF16, SS_F16 = 0, 1, 2
 SS_PP, SS_TP = 0, 1
 SS_ATTN, SS_MLP, SS_BOTH, SS_NO_RESIDUAL = 1, 2, 3, 4
 SS_OUT, SS_IN = 0, 1

@@ -10,7 +10,8 @@
 #include "ss_device.h"
 #include "ss_kernels.h"
 
-namespace ssk {
+namespace SS_NS {
+using namespace ssk;
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__ qkv, T* __restrict__ out, int n_q,
@@ -102,4 +103,4 @@ hipError_t attn_generic(int dt, const void* qkv, void* out, int n_q, int n_kv, c
     return hipGetLastError();
 }
 
-}  // namespace ssk
+}  // namespace SS_NS

@@ -14,14 +14,15 @@
 #include "ss_device.h"
 #include "ss_kernels.h"
 
-namespace ssk {
+namespace SS_NS {
+using namespace ssk;
 
 // 2^x on the hardware's exponential unit (v_exp_f32, about 1 ulp for normal results; results below the
 // normal range flush to zero, which a softmax weight may).  The library exp2f wraps the same instruction
 // in range scaling for denormal results: four more VALU operations per element in the innermost loop.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef half8_t bf16x8_t;       // MFMA operand: 8 elements of the 16-bit type
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
@@ -33,15 +34,6 @@ union Frag {
     vec8 h[2];
     uint32_t w[4];
 };
-
-// two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-    const f32x2_t v = {a, b};
-    const bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
-    return *reinterpret_cast<const uint32_t*>(&r);
-}
 
 // ======================================================================
 // Prefill.  Block = 4 waves = 256 consecutive queries of one (sequence, q head);
@@ -113,7 +105,7 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const bf16_t* __
             Frag kf;
             kf.q = *reinterpret_cast<const vec16*>(kp + ks * 16);
 #pragma unroll
-            for (int t = 0; t < QT; ++t) s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[t][ks].v, s[t], 0, 0, 0);
+            for (int t = 0; t < QT; ++t) s[t] = SS_MFMA_32x32x16(kf.v, qf[t][ks].v, s[t], 0, 0, 0);
         }
         // ---- mask + streaming softmax (per query column = per lane pair l, l^32)
         const int t0 = pi * 16;
@@ -156,8 +148,8 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const bf16_t* __
             vb.q = *reinterpret_cast<const vec16*>(vB + u * 32 * 16);
 #pragma unroll
             for (int t = 0; t < QT; ++t) {
-                o[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pfA[t].v, o[t][u], 0, 0, 0);
-                o[t][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb.v, pfB[t].v, o[t][u], 0, 0, 0);
+                o[t][u] = SS_MFMA_32x32x16(va.v, pfA[t].v, o[t][u], 0, 0, 0);
+                o[t][u] = SS_MFMA_32x32x16(vb.v, pfB[t].v, o[t][u], 0, 0, 0);
             }
         }
     }
@@ -302,7 +294,7 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
             for (int ks = 0; ks < KS; ++ks) {
                 Frag kf;
                 kf.v = *reinterpret_cast<const bf16x8_t*>(st + row * 256 + (((ks * 2 + g2) ^ (row & 15)) << 4));
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.v, qf[ks].v, s, 0, 0, 0);
+                s = SS_MFMA_32x32x16(kf.v, qf[ks].v, s, 0, 0, 0);
             }
             // causal mask only on steps that reach past the wave's first query (wave-uniform test)
             if (t0 + 31 > before + q0) {
@@ -344,8 +336,8 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
                 Frag va, vb;
                 va.v = *reinterpret_cast<const bf16x8_t*>(vA + u * 1024);
                 vb.v = *reinterpret_cast<const bf16x8_t*>(vB + u * 1024);
-                o[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va.v, pfA.v, o[u], 0, 0, 0);
-                o[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb.v, pfB.v, o[u], 0, 0, 0);
+                o[u] = SS_MFMA_32x32x16(va.v, pfA.v, o[u], 0, 0, 0);
+                o[u] = SS_MFMA_32x32x16(vb.v, pfB.v, o[u], 0, 0, 0);
             }
         }
     }
@@ -456,8 +448,8 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
             Frag ka, kb;
             ka.q = *reinterpret_cast<const vec16*>(kA + ks * 32);
             kb.q = *reinterpret_cast<const vec16*>(kB + ks * 32);
-            sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka.v, qf[ks].v, sA, 0, 0, 0);
-            sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb.v, qf[ks].v, sB, 0, 0, 0);
+            sA = SS_MFMA_16x16x32(ka.v, qf[ks].v, sA, 0, 0, 0);
+            sB = SS_MFMA_16x16x32(kb.v, qf[ks].v, sB, 0, 0, 0);
         }
         const int posA = (page0 + pi) * 16 + 4 * g4;
         float mx = m;
@@ -496,7 +488,7 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
             vf.h[1] = *reinterpret_cast<const vec8*>(vB + t * 16 * 16);
 #pragma unroll
             for (int v = 0; v < 4; ++v) o[t][v] *= alpha;
-            o[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf.v, o[t], 0, 0, 0);
+            o[t] = SS_MFMA_16x16x32(vf.v, pf.v, o[t], 0, 0, 0);
         }
     }
     l += __shfl_xor(l, 16, 64);
@@ -550,4 +542,4 @@ hipError_t attn_decode(int dt, const void* qkv, void* out, int n_q, int n_kv, co
     return hipGetLastError();
 }
 
-}  // namespace ssk
+}  // namespace SS_NS

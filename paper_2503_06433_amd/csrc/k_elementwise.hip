@@ -4,7 +4,8 @@
 #include "ss_device.h"
 #include "ss_kernels.h"
 
-namespace ssk {
+namespace SS_NS {
+using namespace ssk;
 
 // ---------------------------------------------------------------- RMSNorm
 // One 256-thread block per token row.  Two passes over the row (the second hits
@@ -311,4 +312,4 @@ hipError_t copy_elems(int dt, const void* src, void* dst, int64_t n, hipStream_t
     return hipGetLastError();
 }
 
-}  // namespace ssk
+}  // namespace SS_NS

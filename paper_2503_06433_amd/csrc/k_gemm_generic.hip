@@ -5,7 +5,8 @@
 #include "ss_device.h"
 #include "ss_kernels.h"
 
-namespace ssk {
+namespace SS_NS {
+using namespace ssk;
 
 template <typename T, int EPI>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__ A, int lda,
@@ -93,4 +94,4 @@ hipError_t gemm_nt(int dt, const void* A, int lda, const void* Wt, void* C, int 
     return launch_generic<bf16_t>(A, lda, Wt, C, ldc, R, M, N, K, epi, s);
 }
 
-}  // namespace ssk
+}  // namespace SS_NS

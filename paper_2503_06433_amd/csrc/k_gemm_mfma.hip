@@ -21,9 +21,10 @@
 #include "ss_device.h"
 #include "ss_kernels.h"
 
-namespace ssk {
+namespace SS_NS {
+using namespace ssk;
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef half8_t bf16x8_t;       // MFMA operand: 8 elements of the 16-bit type
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 constexpr int EPI_PARTIAL = 100;   // internal: fp32 split-K partials
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = SS_MFMA_32x32x16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -270,13 +271,6 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 template <int V> struct VmcntImm { static constexpr int value = (V & 15) | ((V >> 4) << 14) | 0x0F70; };
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2_t;
-    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
-    const f32x2_t v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
-}
-
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __restrict__ A, int lda,
                                                                const bf16_t* __restrict__ Wt, bf16_t* __restrict__ C,
@@ -375,7 +369,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
         for (int t = 0; t < 64; ++t) {
             const int nt = t >> 3, mt = t & 7;
             // accumulators pinned to the accumulation registers, fragments to the ordinary ones
-            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[nt][mt]) : "v"(bfr[par][nt]), "v"(af[par][mt]));
+            asm volatile(SS_MFMA_16x16x32_ASM " %0, %1, %2, %0" : "+a"(acc[nt][mt]) : "v"(bfr[par][nt]), "v"(af[par][mt]));
             if (t < 32 && (t & 1)) {
                 __builtin_amdgcn_sched_barrier(0);
                 read_one(rst, rks, par ^ 1, t >> 1);
@@ -470,8 +464,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
                         const u32x4_t rv = rres[p % RD][r8];
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            o[2 * e] += __uint_as_float(rv[e] << 16);
-                            o[2 * e + 1] += __uint_as_float(rv[e] & 0xffff0000u);
+                            float r0, r1;
+                            unpack_bf16x2(rv[e], r0, r1);
+                            o[2 * e] += r0;
+                            o[2 * e + 1] += r1;
                         }
                     }
                     u32x4_t pv;
@@ -701,4 +697,4 @@ hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int l
     return launch_cfg<128, 128, 2, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s, split, ws);
 }
 
-}  // namespace ssk
+}  // namespace SS_NS

@@ -11,7 +11,8 @@
 #include "ss_device.h"
 #include "ss_kernels.h"
 
-namespace ssk {
+namespace SS_NS {
+using namespace ssk;
 
 template <typename E, bool GATHER>
 __global__ __launch_bounds__(256) void kv_repack_kernel(void* const* __restrict__ k_pools,
@@ -112,4 +113,4 @@ hipError_t kv_scatter(int dt, void* const* k_pools, void* const* v_pools, int n_
     return launch_repack<false>(dt, k_pools, v_pools, n_heads, d, page_size, u, const_cast<void*>(staging), s);
 }
 
-}  // namespace ssk
+}  // namespace SS_NS

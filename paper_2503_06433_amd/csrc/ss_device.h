@@ -1,12 +1,37 @@
 // Small device-side helpers shared by the kernel files (gfx950 only).
+//
+// The kernel files are compiled twice: once with brain-float as the 16-bit storage type (namespace ssk),
+// once, with SS_HALF_F16 defined, with IEEE half (namespace ssk16).  Both formats are 16 bits wide, are
+// multiplied by MFMA instructions of the same shape and rate and accumulate in fp32, so the kernels are the
+// same text; what differs is collected here: the conversions, the element type of the MFMA operand
+// vectors and the instruction names.  In the sources `bf16_t`, `bf2f`, `f2bf` and the BF16 dtype code
+// therefore mean "the 16-bit type of this build".
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-namespace ssk {
+#ifdef SS_HALF_F16
+#define SS_NS ssk16
+#else
+#define SS_NS ssk
+#endif
 
-typedef uint16_t bf16_t;   // raw brain-float bits
+namespace SS_NS {
 
+typedef uint16_t bf16_t;   // raw bits of the 16-bit storage type
+
+#ifdef SS_HALF_F16
+typedef _Float16 half_elem_t;
+#define SS_MFMA_32x32x16 __builtin_amdgcn_mfma_f32_32x32x16_f16
+#define SS_MFMA_16x16x32 __builtin_amdgcn_mfma_f32_16x16x32_f16
+#define SS_MFMA_16x16x32_ASM "v_mfma_f32_16x16x32_f16"
+__device__ __forceinline__ float bf2f(bf16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }   // nearest even
+#else
+typedef __bf16 half_elem_t;
+#define SS_MFMA_32x32x16 __builtin_amdgcn_mfma_f32_32x32x16_bf16
+#define SS_MFMA_16x16x32 __builtin_amdgcn_mfma_f32_16x16x32_bf16
+#define SS_MFMA_16x16x32_ASM "v_mfma_f32_16x16x32_bf16"
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
 // round to nearest, ties to even; NaN stays NaN
@@ -15,6 +40,27 @@ __device__ __forceinline__ bf16_t f2bf(float f) {
     if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
     u += 0x7fffu + ((u >> 16) & 1u);
     return (bf16_t)(u >> 16);
+}
+#endif
+
+// MFMA operand vector (8 elements) and packed pairs of the 16-bit type
+typedef __attribute__((__vector_size__(8 * sizeof(half_elem_t)))) half_elem_t half8_t;
+typedef float f32x2_cvt_t __attribute__((ext_vector_type(2)));
+typedef half_elem_t half2_cvt_t __attribute__((ext_vector_type(2)));
+// two floats -> packed pair, round to nearest even (one v_cvt_pk_* on gfx950)
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const f32x2_cvt_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, half2_cvt_t));
+}
+// packed pair -> two floats
+__device__ __forceinline__ void unpack_bf16x2(uint32_t w, float& lo, float& hi) {
+#ifdef SS_HALF_F16
+    lo = bf2f((bf16_t)(w & 0xffffu));
+    hi = bf2f((bf16_t)(w >> 16));
+#else
+    lo = __uint_as_float(w << 16);
+    hi = __uint_as_float(w & 0xffff0000u);
+#endif
 }
 
 __device__ __forceinline__ float ldf(const float* p) { return *p; }
@@ -49,10 +95,7 @@ template <> __device__ __forceinline__ void unpack16<float>(const vec16& v, floa
 }
 template <> __device__ __forceinline__ void unpack16<bf16_t>(const vec16& v, float* f) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        f[2 * i] = __uint_as_float(v.w[i] << 16);
-        f[2 * i + 1] = __uint_as_float(v.w[i] & 0xffff0000u);
-    }
+    for (int i = 0; i < 4; ++i) unpack_bf16x2(v.w[i], f[2 * i], f[2 * i + 1]);
 }
 template <typename T> __device__ __forceinline__ vec16 pack16(const float* f);
 template <> __device__ __forceinline__ vec16 pack16<float>(const float* f) {
@@ -84,4 +127,4 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
-}  // namespace ssk
+}  // namespace SS_NS

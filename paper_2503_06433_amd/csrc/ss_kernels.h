@@ -2,10 +2,15 @@
 // kernel files.  Everything here is device pointers + sizes; every launcher
 // validates what its kernel assumes and returns hipErrorInvalidValue instead of
 // launching a grid that would not fit.
-#pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// Shared types live in namespace ssk, once.  The launcher declarations follow in the namespace of the
+// build: ssk for the brain-float build of the kernel files, ssk16 for the IEEE-half build (see
+// ss_device.h).  A translation unit that calls both (the runtime) includes this file a second time with
+// SS_DECL_NS set to the other namespace.
+#ifndef SS_KERNELS_TYPES_H
+#define SS_KERNELS_TYPES_H
 namespace ssk {
 
 enum Dtype { F32 = 0, BF16 = 1 };
@@ -18,30 +23,6 @@ enum Epilogue {
                         // matching 32 up rows; C[m, j] = silu(gate_j) * up_j, C has N/2 columns
     EPI_STORE_F32 = 3,  // C is float regardless of the input dtype
 };
-
-// C[M,N] = A[M,K] * Wt[N,K]^T.  A row-major with leading dimension lda, Wt
-// row-major [N,K] (K contiguous), C row-major with leading dimension ldc.
-// force_generic selects the plain LDS-tiled FMA kernel (any shape, any dtype);
-// otherwise bf16 with K % 64 == 0 runs on the MFMA kernel.
-// `ws` is an optional float workspace of ws_bytes for split-K partial sums (used
-// when the output has too few tiles to occupy the chip, as at decode batch sizes).
-// The large-output bf16 kernel runs as persistent blocks that own their CUs until the launch is done;
-// max_rounds > 0 cuts it into launches of at most that many output tiles per block, so that kernels of
-// other streams (the KV movers' repack kernels) get the chip at the boundaries; 0 = one launch.
-hipError_t gemm_nt(int dt, const void* A, int lda, const void* Wt, void* C, int ldc,
-                   const void* R, int M, int N, int K, int epi, bool force_generic,
-                   hipStream_t s, float* ws = nullptr, size_t ws_bytes = 0, int max_rounds = 0);
-
-// out[t,:] = x[t,:] * rsqrt(mean(x[t,:]^2) + eps) * g
-hipError_t rmsnorm(int dt, const void* x, const void* g, void* out, int T, int H, float eps,
-                   hipStream_t s);
-
-// out[t, j] = silu(gu[t, j]) * gu[t, F + j]   (unfused form used by the generic GEMM path)
-hipError_t swiglu(int dt, const void* gu, void* out, int T, int F, hipStream_t s);
-
-// Gathers rows of an embedding table.
-hipError_t embed_rows(int dt, const void* table, const int32_t* ids, void* out, int n, int H,
-                      hipStream_t s);
 
 // Paged cache geometry of one shard and one layer.
 //   K page: [n_heads][page_size][d]   (token-major, d contiguous)
@@ -78,18 +59,6 @@ struct BatchMeta {
     int n_units;
 };
 
-// Rotates q and k in place inside qkv [T, (n_q + 2 n_kv) d] by the token's
-// position (half-split pairing, angles from the fp32 table rope[pos][d/2][cos,sin]),
-// then writes the rotated k and the v of every token into the pages.
-hipError_t rope_kvwrite(int dt, void* qkv, int n_q, int n_kv, const float* rope_table,
-                        const BatchMeta& bm, const KvLayer& kv, hipStream_t s);
-
-// Causal attention of the batch's new tokens against the paged cache (which
-// already holds them).  q is read from qkv (row stride (n_q + 2 n_kv) d), out is
-// [T, n_q d].  Query at absolute position p sees cache positions 0..p.
-hipError_t attn_prefill(int dt, const void* qkv, void* out, int n_q, int n_kv,
-                        const BatchMeta& bm, const KvLayer& kv, bool force_generic, hipStream_t s);
-
 // One query token per sequence.  work items (seq, first page, n pages) split long
 // sequences; partial results go through `scratch` (floats) and are merged.
 struct DecodeWork {
@@ -101,10 +70,6 @@ struct DecodeWork {
     int n_items;
     int max_items_per_seq;
 };
-size_t attn_decode_scratch_floats(int n_items, int n_q, int d);
-hipError_t attn_decode(int dt, const void* qkv, void* out, int n_q, int n_kv,
-                       const BatchMeta& bm, const KvLayer& kv, const DecodeWork& wk,
-                       float* scratch, bool force_generic, hipStream_t s);
 
 // KV repack between pages and heads-major staging.
 // unit u = one (sequence, local layer): a staging block [2][n_heads][len][d] at
@@ -119,8 +84,65 @@ struct RepackUnits {
     int n_units;
     int max_pages;               // most pages of any unit
 };
+
+}  // namespace ssk
+#endif
+
+#ifndef SS_DECL_NS
+#ifdef SS_HALF_F16
+#define SS_DECL_NS ssk16
+#else
+#define SS_DECL_NS ssk
+#endif
+#endif
+namespace SS_DECL_NS {
+using namespace ssk;
+
+// C[M,N] = A[M,K] * Wt[N,K]^T.  A row-major with leading dimension lda, Wt
+// row-major [N,K] (K contiguous), C row-major with leading dimension ldc.
+// force_generic selects the plain LDS-tiled FMA kernel (any shape, any dtype);
+// otherwise bf16 with K % 64 == 0 runs on the MFMA kernel.
+// `ws` is an optional float workspace of ws_bytes for split-K partial sums (used
+// when the output has too few tiles to occupy the chip, as at decode batch sizes).
+// The large-output bf16 kernel runs as persistent blocks that own their CUs until the launch is done;
+// max_rounds > 0 cuts it into launches of at most that many output tiles per block, so that kernels of
+// other streams (the KV movers' repack kernels) get the chip at the boundaries; 0 = one launch.
+hipError_t gemm_nt(int dt, const void* A, int lda, const void* Wt, void* C, int ldc,
+                   const void* R, int M, int N, int K, int epi, bool force_generic,
+                   hipStream_t s, float* ws = nullptr, size_t ws_bytes = 0, int max_rounds = 0);
+
+// out[t,:] = x[t,:] * rsqrt(mean(x[t,:]^2) + eps) * g
+hipError_t rmsnorm(int dt, const void* x, const void* g, void* out, int T, int H, float eps,
+                   hipStream_t s);
+
+// out[t, j] = silu(gu[t, j]) * gu[t, F + j]   (unfused form used by the generic GEMM path)
+hipError_t swiglu(int dt, const void* gu, void* out, int T, int F, hipStream_t s);
+
+// Gathers rows of an embedding table.
+hipError_t embed_rows(int dt, const void* table, const int32_t* ids, void* out, int n, int H,
+                      hipStream_t s);
+
+// Rotates q and k in place inside qkv [T, (n_q + 2 n_kv) d] by the token's
+// position (half-split pairing, angles from the fp32 table rope[pos][d/2][cos,sin]),
+// then writes the rotated k and the v of every token into the pages.
+hipError_t rope_kvwrite(int dt, void* qkv, int n_q, int n_kv, const float* rope_table,
+                        const BatchMeta& bm, const KvLayer& kv, hipStream_t s);
+
+// Causal attention of the batch's new tokens against the paged cache (which
+// already holds them).  q is read from qkv (row stride (n_q + 2 n_kv) d), out is
+// [T, n_q d].  Query at absolute position p sees cache positions 0..p.
+hipError_t attn_prefill(int dt, const void* qkv, void* out, int n_q, int n_kv,
+                        const BatchMeta& bm, const KvLayer& kv, bool force_generic, hipStream_t s);
+
+size_t attn_decode_scratch_floats(int n_items, int n_q, int d);
+
+hipError_t attn_decode(int dt, const void* qkv, void* out, int n_q, int n_kv,
+                       const BatchMeta& bm, const KvLayer& kv, const DecodeWork& wk,
+                       float* scratch, bool force_generic, hipStream_t s);
+
 hipError_t kv_gather(int dt, void* const* k_pools, void* const* v_pools, int n_heads, int d,
                      int page_size, const RepackUnits& u, void* staging, hipStream_t s);
+
 hipError_t kv_scatter(int dt, void* const* k_pools, void* const* v_pools, int n_heads, int d,
                       int page_size, const RepackUnits& u, const void* staging, hipStream_t s);
 
@@ -136,4 +158,7 @@ hipError_t argmax_rows(const float* logits, int n, int V, int32_t* out, hipStrea
 // dst[i] = src[i] for i < n (elements of the model dtype); used for gains.
 hipError_t copy_elems(int dt, const void* src, void* dst, int64_t n, hipStream_t s);
 
-}  // namespace ssk
+
+
+}  // namespace SS_DECL_NS
+#undef SS_DECL_NS

@@ -27,6 +27,8 @@
 
 #include "../../include/seesaw_rt.h"
 #include "ss_kernels.h"
+#define SS_DECL_NS ssk16
+#include "ss_kernels.h"
 
 namespace {
 
@@ -159,7 +161,8 @@ extern "C" int ss_offline_run(ss_ctx* c, const ss_offline_cfg* cfg, int32_t n, c
             int t = 0;
             for (int i = 0; i < nb; ++i) { t += q_lens[i]; b.h_idx[i] = t - 1; }
             OFF_HIP(hipMemcpyAsync(b.d_idx, b.h_idx, (size_t)nb * sizeof(int32_t), hipMemcpyHostToDevice, st));
-            hipError_t e = ssk::embed_rows(m.dtype, in, b.d_idx, b.rows, nb, m.hidden, st);
+            hipError_t e = m.dtype == SS_F16 ? ssk16::embed_rows(ssk::BF16, in, b.d_idx, b.rows, nb, m.hidden, st)
+                                             : ssk::embed_rows(m.dtype, in, b.d_idx, b.rows, nb, m.hidden, st);
             if (e != hipSuccess) OFF_FAIL(SS_EHIP, "offline loop: row gather: %s", hipGetErrorString(e));
             rows = b.rows;
         }

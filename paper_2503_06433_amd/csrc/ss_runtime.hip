@@ -24,6 +24,13 @@
 
 #include "../../include/seesaw_rt.h"
 #include "ss_kernels.h"
+#define SS_DECL_NS ssk16
+#include "ss_kernels.h"
+
+// The kernel files exist twice: built for brain-float (namespace ssk; also serves fp32 models) and for IEEE
+// half (namespace ssk16, where the 16-bit dtype code means half).  Every launcher takes the dtype first.
+#define SSK_CALL(c, fn, ...) \
+    ((c)->dt == SS_F16 ? ssk16::fn(ssk::BF16, __VA_ARGS__) : ssk::fn((c)->dt, __VA_ARGS__))
 
 namespace {
 
@@ -570,33 +577,33 @@ int run_attn_phase(ss_ctx* c, Shard* s, int ll, const ss_batch* b, bool decode, 
         size_t fl = ssk::attn_decode_scratch_floats(ms->wk.n_items, s->nq_l, d);
         if ((rc = ensure_buf(c, c->ws_scratch, fl * sizeof(float)))) return rc;
     }
-    if (c->dt == SS_BF16 && T <= 2048 && (rc = ensure_buf(c, c->ws_splitk, (size_t)128 << 20))) return rc;
+    if (c->dt != SS_F32 && T <= 2048 && (rc = ensure_buf(c, c->ws_splitk, (size_t)128 << 20))) return rc;
     const ssk::KvLayer kv = kv_layer(c, s, ll);
     {
         ProfScope ps(c, 4, st);
-        K_TRY(c, ssk::rmsnorm(c->dt, x_in, w.g1, c->ws_h.p, T, H, m.rms_eps, st));
+        K_TRY(c, SSK_CALL(c, rmsnorm, x_in, w.g1, c->ws_h.p, T, H, m.rms_eps, st));
     }
     {
         ProfScope ps(c, 0, st);
-        K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, H, w.wqkv_t, c->ws_qkv.p, nqkv, nullptr, T, nqkv, H, ssk::EPI_STORE,
+        K_TRY(c, SSK_CALL(c, gemm_nt, c->ws_h.p, H, w.wqkv_t, c->ws_qkv.p, nqkv, nullptr, T, nqkv, H, ssk::EPI_STORE,
                               c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
     }
     {
         ProfScope ps(c, 4, st);
-        K_TRY(c, ssk::rope_kvwrite(c->dt, c->ws_qkv.p, s->nq_l, s->nkv_l, c->d_rope, ms->bm, kv, st));
+        K_TRY(c, SSK_CALL(c, rope_kvwrite, c->ws_qkv.p, s->nq_l, s->nkv_l, c->d_rope, ms->bm, kv, st));
     }
     if (decode) {
         ProfScope ps(c, 2, st);
-        K_TRY(c, ssk::attn_decode(c->dt, c->ws_qkv.p, c->ws_attn.p, s->nq_l, s->nkv_l, ms->bm, kv, ms->wk,
+        K_TRY(c, SSK_CALL(c, attn_decode, c->ws_qkv.p, c->ws_attn.p, s->nq_l, s->nkv_l, ms->bm, kv, ms->wk,
                                   (float*)c->ws_scratch.p, c->force_generic, st));
     } else {
         ProfScope ps(c, 1, st);
-        K_TRY(c, ssk::attn_prefill(c->dt, c->ws_qkv.p, c->ws_attn.p, s->nq_l, s->nkv_l, ms->bm, kv,
+        K_TRY(c, SSK_CALL(c, attn_prefill, c->ws_qkv.p, c->ws_attn.p, s->nq_l, s->nkv_l, ms->bm, kv,
                                    c->force_generic, st));
     }
     {
         ProfScope ps(c, 0, st);
-        K_TRY(c, ssk::gemm_nt(c->dt, c->ws_attn.p, s->nq_l * d, w.wo_t, out, H, residual ? x_in : nullptr, T, H,
+        K_TRY(c, SSK_CALL(c, gemm_nt, c->ws_attn.p, s->nq_l * d, w.wo_t, out, H, residual ? x_in : nullptr, T, H,
                               s->nq_l * d, residual ? ssk::EPI_RESIDUAL : ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
     }
     return mark_meta_used(c, ms, st);
@@ -609,28 +616,28 @@ int run_mlp_phase(ss_ctx* c, Shard* s, int ll, int T, const void* x1, void* out,
     int rc;
     if ((rc = ensure_buf(c, c->ws_h, (size_t)T * H * c->es))) return rc;
     if ((rc = ensure_buf(c, c->ws_act, (size_t)T * F * c->es))) return rc;
-    if (c->dt == SS_BF16 && T <= 2048 && (rc = ensure_buf(c, c->ws_splitk, (size_t)128 << 20))) return rc;
+    if (c->dt != SS_F32 && T <= 2048 && (rc = ensure_buf(c, c->ws_splitk, (size_t)128 << 20))) return rc;
     {
         ProfScope ps(c, 4, st);
-        K_TRY(c, ssk::rmsnorm(c->dt, x1, w.g2, c->ws_h.p, T, H, m.rms_eps, st));
+        K_TRY(c, SSK_CALL(c, rmsnorm, x1, w.g2, c->ws_h.p, T, H, m.rms_eps, st));
     }
     if (w.gu_interleaved) {
         ProfScope ps(c, 0, st);
-        K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, H, w.wgu_t, c->ws_act.p, F, nullptr, T, 2 * F, H, ssk::EPI_SWIGLU,
+        K_TRY(c, SSK_CALL(c, gemm_nt, c->ws_h.p, H, w.wgu_t, c->ws_act.p, F, nullptr, T, 2 * F, H, ssk::EPI_SWIGLU,
                               false, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
     } else {
         if ((rc = ensure_buf(c, c->ws_gu, (size_t)T * 2 * F * c->es))) return rc;
         {
             ProfScope ps(c, 0, st);
-            K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, H, w.wgu_t, c->ws_gu.p, 2 * F, nullptr, T, 2 * F, H,
+            K_TRY(c, SSK_CALL(c, gemm_nt, c->ws_h.p, H, w.wgu_t, c->ws_gu.p, 2 * F, nullptr, T, 2 * F, H,
                                   ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
         }
         ProfScope ps(c, 4, st);
-        K_TRY(c, ssk::swiglu(c->dt, c->ws_gu.p, c->ws_act.p, T, F, st));
+        K_TRY(c, SSK_CALL(c, swiglu, c->ws_gu.p, c->ws_act.p, T, F, st));
     }
     {
         ProfScope ps(c, 0, st);
-        K_TRY(c, ssk::gemm_nt(c->dt, c->ws_act.p, F, w.wd_t, out, H, residual ? x1 : nullptr, T, H, F,
+        K_TRY(c, SSK_CALL(c, gemm_nt, c->ws_act.p, F, w.wd_t, out, H, residual ? x1 : nullptr, T, H, F,
                               residual ? ssk::EPI_RESIDUAL : ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
     }
     return SS_OK;
@@ -850,7 +857,7 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
         HIP_TRY(c, hipMemcpyAsync(L.mv_meta_dev, L.mv_meta_host, mbytes, hipMemcpyHostToDevice, L.side));
         if (job.dir == SS_OUT) {
             ProfScope ps(c, 3, L.side);
-            K_TRY(c, ssk::kv_gather(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru,
+            K_TRY(c, SSK_CALL(c, kv_gather, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru,
                                     L.dev_staging, L.side));
         }
         // runs of this group: (unit, K|V) -> contiguous in staging and in the tier
@@ -926,7 +933,7 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
         }
         if (job.dir == SS_IN) {
             ProfScope ps(c, 3, L.side);
-            K_TRY(c, ssk::kv_scatter(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru,
+            K_TRY(c, SSK_CALL(c, kv_scatter, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru,
                                      L.dev_staging, L.side));
         }
         g0 = g1;
@@ -1027,7 +1034,7 @@ int slice_into(ss_ctx* c, const void* src, int location, size_t src_rows, size_t
     int rc = upload_matrix(c, src, location, src_rows * ld * c->es, &tmp, &dsrc);
     if (rc) return rc;
     const uint8_t* base = (const uint8_t*)dsrc + row0 * ld * c->es;
-    hipError_t e = ssk::slice_transpose(c->dt, base, (int64_t)ld, K, c0, n, dst, blk, blk_stride, row_off, 0);
+    hipError_t e = SSK_CALL(c, slice_transpose, base, (int64_t)ld, K, c0, n, dst, blk, blk_stride, row_off, 0);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (tmp) (void)hipFree(tmp);
     if (e != hipSuccess) return fail(c, SS_EHIP, "weight slicing: %s", hipGetErrorString(e));
@@ -1182,14 +1189,14 @@ int reload_layer(ss_ctx* c, Shard* s, int ll) {
         if ((size_t)n == ld) HIP_TRY(c, hipMemcpyAsync(c->w_staging.p, src, (size_t)K * n * es, hipMemcpyHostToDevice, ws));
         else HIP_TRY(c, hipMemcpy2DAsync(c->w_staging.p, (size_t)n * es, src, ld * es, (size_t)n * es, (size_t)K,
                                          hipMemcpyHostToDevice, ws));
-        K_TRY(c, ssk::slice_transpose(c->dt, c->w_staging.p, (int64_t)n, K, 0, n, dst, blk, blk_stride, row_off, ws));
+        K_TRY(c, SSK_CALL(c, slice_transpose, c->w_staging.p, (int64_t)n, K, 0, n, dst, blk, blk_stride, row_off, ws));
         return SS_OK;
     };
     // rows [r0, r0+K) of the host matrix [*, n] (contiguous) -> staging [K, n] -> dst = its transpose
     auto rows = [&](int which, size_t r0, int K, int n, void* dst) -> int {
         const uint8_t* src = hl.base + hl.off[which] + r0 * (size_t)n * es;
         HIP_TRY(c, hipMemcpyAsync(c->w_staging.p, src, (size_t)K * n * es, hipMemcpyHostToDevice, ws));
-        K_TRY(c, ssk::slice_transpose(c->dt, c->w_staging.p, (int64_t)n, K, 0, n, dst, n, n, 0, ws));
+        K_TRY(c, SSK_CALL(c, slice_transpose, c->w_staging.p, (int64_t)n, K, 0, n, dst, n, n, 0, ws));
         return SS_OK;
     };
     uint8_t* qkv = (uint8_t*)L.wqkv_t;
@@ -1197,7 +1204,7 @@ int reload_layer(ss_ctx* c, Shard* s, int ll) {
     if ((rc = cols(SS_W_K, H, kd, (size_t)s->g0 * dh, nkv, qkv + (size_t)nq * H * es, nkv, nkv, 0))) return rc;
     if ((rc = cols(SS_W_V, H, kd, (size_t)s->g0 * dh, nkv, qkv + (size_t)(nq + nkv) * H * es, nkv, nkv, 0))) return rc;
     if ((rc = rows(SS_W_O, (size_t)s->q0 * dh, nq, H, L.wo_t))) return rc;
-    L.gu_interleaved = (c->dt == SS_BF16) && !c->force_generic && (F % 32 == 0) && (H % 64 == 0);
+    L.gu_interleaved = (c->dt != SS_F32) && !c->force_generic && (F % 32 == 0) && (H % 64 == 0);
     if (L.gu_interleaved) {
         if ((rc = cols(SS_W_G, H, m.ffn, s->f0, F, L.wgu_t, 32, 64, 0))) return rc;
         if ((rc = cols(SS_W_U, H, m.ffn, s->f0, F, L.wgu_t, 32, 64, 32))) return rc;
@@ -1221,7 +1228,7 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
     if (m.hidden <= 0 || m.n_q_heads <= 0 || m.n_kv_heads <= 0 || m.ffn <= 0 || m.n_layers <= 0) return SS_EINVAL;
     if ((m.head_dim != 64 && m.head_dim != 128) || m.page_size != 16) return SS_EINVAL;
     if (m.n_q_heads % m.n_kv_heads) return SS_EINVAL;
-    if (m.dtype != SS_F32 && m.dtype != SS_BF16) return SS_EINVAL;
+    if (m.dtype != SS_F32 && m.dtype != SS_BF16 && m.dtype != SS_F16) return SS_EINVAL;
     if (rt->gpu_kv_pages <= 0 || rt->gpu_kv_pages > (1ll << 30) || rt->max_seq_len <= 0 || rt->host_tier_bytes < 0 ||
         rt->pinned_bytes < 0)
         return SS_EINVAL;
@@ -1382,7 +1389,7 @@ int ss_load_layer(ss_ctx* c, const ss_shard_desc* d, int layer, const ss_layer_w
     // Wo rows of this shard's heads -> Wo^T [H, nq]
     if ((rc = slice_into(c, w->wo, w->location, qd, H, (size_t)s->q0 * dh, nq, 0, H, L.wo_t, H, H, 0))) return rc;
     // gate / up: interleaved in blocks of 32 rows when the fused SwiGLU epilogue can run
-    L.gu_interleaved = (c->dt == SS_BF16) && !c->force_generic && (F % 32 == 0) && (H % 64 == 0);
+    L.gu_interleaved = (c->dt != SS_F32) && !c->force_generic && (F % 32 == 0) && (H % 64 == 0);
     if (L.gu_interleaved) {
         if ((rc = slice_into(c, w->wg, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, 32, 64, 0))) return rc;
         if ((rc = slice_into(c, w->wu, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, 32, 64, 32))) return rc;
@@ -1753,9 +1760,9 @@ static int xfer_dev(ss_ctx* c, const ss_shard_desc* d, const int64_t* seq_ids, c
         {
             ProfScope ps(c, 3, st);
             if (import)
-                K_TRY(c, ssk::kv_scatter(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru, stg, st));
+                K_TRY(c, SSK_CALL(c, kv_scatter, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru, stg, st));
             else
-                K_TRY(c, ssk::kv_gather(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru, stg, st));
+                K_TRY(c, SSK_CALL(c, kv_gather, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru, stg, st));
         }
         for (size_t u = u0; u < u1; ++u) stage_off += units[u].bytes;
         if (u1 < units.size()) HIP_TRY(c, hipStreamSynchronize(st));
@@ -1816,7 +1823,7 @@ int ss_kv_read(ss_ctx* c, const ss_shard_desc* d, int64_t seq, int layer, void* 
     HIP_TRY(c, hipMemcpy(c->lane[0].mv_meta_dev, img.data(), mbytes, hipMemcpyHostToDevice));
     void* tmp = nullptr;
     HIP_TRY(c, hipMalloc(&tmp, units[0].bytes));
-    hipError_t e = ssk::kv_gather(c->dt, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru, tmp, 0);
+    hipError_t e = SSK_CALL(c, kv_gather, s->d_k_pools, s->d_v_pools, s->nkv_l, c->m.head_dim, c->m.page_size, ru, tmp, 0);
     if (e == hipSuccess) e = hipMemcpy(host_out, tmp, units[0].bytes, hipMemcpyDeviceToHost);
     (void)hipFree(tmp);
     if (e != hipSuccess) return fail(c, SS_EHIP, "kv read: %s", hipGetErrorString(e));
@@ -1870,7 +1877,7 @@ int ss_embed(ss_ctx* c, const int32_t* ids, int n, void* x_out, void* stream) {
         c->d_ids_cap = (size_t)n * 2;
     }
     HIP_TRY(c, hipMemcpy(c->d_ids, ids, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice));
-    K_TRY(c, ssk::embed_rows(c->dt, c->d_embed, c->d_ids, x_out, n, c->m.hidden, st));
+    K_TRY(c, SSK_CALL(c, embed_rows, c->d_embed, c->d_ids, x_out, n, c->m.hidden, st));
     return SS_OK;
 }
 
@@ -1880,8 +1887,8 @@ int ss_lm_head(ss_ctx* c, const void* x, int n, float* logits, void* stream) {
     hipStream_t st = (hipStream_t)stream;
     int rc = ensure_buf(c, c->ws_h, (size_t)n * c->m.hidden * c->es);
     if (rc) return rc;
-    K_TRY(c, ssk::rmsnorm(c->dt, x, c->d_gf, c->ws_h.p, n, c->m.hidden, c->m.rms_eps, st));
-    K_TRY(c, ssk::gemm_nt(c->dt, c->ws_h.p, c->m.hidden, c->d_wlm_t, logits, c->m.vocab, nullptr, n, c->m.vocab,
+    K_TRY(c, SSK_CALL(c, rmsnorm, x, c->d_gf, c->ws_h.p, n, c->m.hidden, c->m.rms_eps, st));
+    K_TRY(c, SSK_CALL(c, gemm_nt, c->ws_h.p, c->m.hidden, c->d_wlm_t, logits, c->m.vocab, nullptr, n, c->m.vocab,
                           c->m.hidden, ssk::EPI_STORE_F32, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
     return SS_OK;
 }

@@ -21,7 +21,7 @@ def make_context(cfg, pages, tier_bytes=0, pinned_bytes=0, max_seq_len=4608):
 
 
 def torch_dtype(dtype):
-    return torch.float32 if dtype == wl.F32 else torch.bfloat16
+    return {wl.F32: torch.float32, wl.BF16: torch.bfloat16, wl.F16: torch.float16}[dtype]
 
 
 def to_device(raw, dtype):
@@ -29,7 +29,7 @@ def to_device(raw, dtype):
     raw = np.ascontiguousarray(raw)
     if dtype == wl.F32:
         return torch.from_numpy(raw).cuda()
-    return torch.from_numpy(raw.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(raw.view(np.int16)).cuda().view(torch_dtype(dtype))
 
 
 def to_f64(t, dtype):
@@ -37,7 +37,7 @@ def to_f64(t, dtype):
     if dtype == wl.F32:
         return t.detach().cpu().numpy().astype(np.float64)
     bits = t.detach().view(torch.int16).cpu().numpy().view(np.uint16)
-    return wl.bf16_to_f32(bits).astype(np.float64)
+    return wl.storage_to_f64(bits, dtype)
 
 
 def to_raw(t, dtype):

@@ -37,7 +37,7 @@ def _import(ctx, desc, cfg, ids, contents):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("dtype,d", [(wl.BF16, 128), (wl.BF16, 64), (wl.F32, 64), (wl.F32, 128)])
+@pytest.mark.parametrize("dtype,d", [(wl.BF16, 128), (wl.BF16, 64), (wl.F32, 64), (wl.F32, 128), (wl.F16, 128)])
 def test_import_read_export_round_trip(dtype, d):
     cfg = _cfg(dtype, d=d)
     desc = pp_desc(cfg)
@@ -57,7 +57,7 @@ def test_import_read_export_round_trip(dtype, d):
     # export of a subset, in a different order, in the documented staging layout
     order = [4, 1, 3]
     off = kt.staging_offsets([lens[i] for i in order], cfg.n_layers, cfg.n_kv_heads, d)
-    stg = torch.zeros(int(off[-1]), device="cuda", dtype=torch.float32 if dtype == wl.F32 else torch.bfloat16)
+    stg = torch.zeros(int(off[-1]), device="cuda", dtype=torch.float32 if dtype == wl.F32 else torch.int16)
     ctx.kv_export_dev(desc, [ids[i] for i in order], stg)
     torch.cuda.synchronize()
     raw = to_raw(stg, dtype)

@@ -37,7 +37,7 @@ def _weights(cfg, seed):
 def _round_kv(cfg):
     if cfg.dtype == wl.F32:
         return None
-    return lambda a: wl.bf16_to_f32(wl.bf16_bits(a.astype(np.float32))).astype(np.float64)
+    return lambda a: wl.round_to_storage(a, cfg.dtype)
 
 
 SMALL = {
@@ -51,6 +51,7 @@ SMALL = {
 @pytest.mark.parametrize("name,dtype,k", [
     ("mha_d128", wl.BF16, 1), ("mha_d128", wl.BF16, 2), ("gqa4_d128", wl.BF16, 2), ("gqa8_d128", wl.BF16, 1),
     ("mha_d64_generic", wl.BF16, 2), ("mha_d64_generic", wl.F32, 1), ("mha_d128", wl.F32, 2),
+    ("mha_d128", wl.F16, 1), ("gqa4_d128", wl.F16, 2), ("mha_d64_generic", wl.F16, 2),
 ])
 def test_prefill_then_decode_matches_oracle(name, dtype, k):
     cfg = wl.ModelCfg(n_layers=1, dtype=dtype, **SMALL[name])

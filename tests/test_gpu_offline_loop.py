@@ -110,10 +110,11 @@ def test_loop_with_a_store_that_holds_everything_switches_once():
     assert _check_tokens(cfg, vals, hv, prompts, out_lens, toks, 1e-4) >= 0.9 * sum(out_lens)
 
 
-def test_loop_bf16_model_trace_and_counts():
-    # bf16, head_dim 128 (the MFMA kernels): the order of actions is what is compared; tokens of a bf16 run
-    # are not expected to equal those of the float64 oracle beyond the first few
-    cfg = wl.ModelCfg(hidden=512, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn=1024, n_layers=2, vocab=256, dtype=wl.BF16)
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F16])
+def test_loop_16bit_model_trace_and_counts(dtype):
+    # 16-bit storage, head_dim 128 (the MFMA kernels): the order of actions is what is compared; tokens of such
+    # a run are not expected to equal those of the float64 oracle beyond the first few
+    cfg = wl.ModelCfg(hidden=512, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn=1024, n_layers=2, vocab=256, dtype=dtype)
     prompts, out_lens = _requests(cfg, 10, 43, 5, 90, 2, 12)
     _run(cfg, 1003, prompts, out_lens, tier_tokens=200, gpu_pages=12, mpt=128, mds=4, reshard=True)
     _run(cfg, 1003, prompts, out_lens, tier_tokens=400, gpu_pages=24, mpt=128, mds=8, reshard=True, group=2)

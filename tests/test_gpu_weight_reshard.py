@@ -49,7 +49,7 @@ def _check_shard(ctx, cfg, raws, desc, k, i):
 
 @pytest.mark.parametrize("name,dtype,k", [
     ("mha_d128", wl.BF16, 2), ("mha_d128", wl.BF16, 4), ("gqa4_d128", wl.BF16, 2), ("mha_d64_ragged", wl.BF16, 2),
-    ("mha_d64_ragged", wl.F32, 2), ("mha_d128", wl.F32, 1),
+    ("mha_d64_ragged", wl.F32, 2), ("mha_d128", wl.F32, 1), ("mha_d128", wl.F16, 2),
 ])
 def test_resharded_slices_are_bit_exact(name, dtype, k):
     cfg = wl.ModelCfg(n_layers=3, dtype=dtype, **SHAPES[name])
@@ -82,7 +82,8 @@ def test_resharded_slices_are_bit_exact(name, dtype, k):
     ctx.destroy()
 
 
-@pytest.mark.parametrize("name,dtype,k", [("mha_d128", wl.BF16, 2), ("gqa4_d128", wl.BF16, 2), ("mha_d64_ragged", wl.F32, 2)])
+@pytest.mark.parametrize("name,dtype,k", [("mha_d128", wl.BF16, 2), ("gqa4_d128", wl.BF16, 2), ("mha_d64_ragged", wl.F32, 2),
+                                          ("gqa4_d128", wl.F16, 2)])
 def test_layer_after_reshard_equals_direct_load_and_oracle(name, dtype, k):
     cfg = wl.ModelCfg(n_layers=2, dtype=dtype, **SHAPES[name])
     vals, raws = _model(cfg, 600)
@@ -137,7 +138,7 @@ def test_layer_after_reshard_equals_direct_load_and_oracle(name, dtype, k):
         for l, (y, z) in enumerate(outs):
             assert np.array_equal(to_raw(y, dtype), direct[i][l][0]), (i, l, "attention half")
             assert np.array_equal(to_raw(z, dtype), direct[i][l][1]), (i, l, "mlp half")
-            rk = None if dtype == wl.F32 else (lambda a: wl.bf16_to_f32(wl.bf16_bits(a.astype(np.float32))).astype(np.float64))
+            rk = None if dtype == wl.F32 else (lambda a: wl.round_to_storage(a, dtype))
             ref_a = lm.attn_block(cfg, vals[l], xv, batch, lm.KVCache(cfg), l, k, i, rk)
             ref_m = lm.mlp_block(cfg, vals[l], xv, k, i)
             assert rel_err(to_f64(y, dtype), ref_a) <= tol(dtype)
@@ -145,7 +146,7 @@ def test_layer_after_reshard_equals_direct_load_and_oracle(name, dtype, k):
     # the stage's output was computed before its weights were released
     cache = lm.KVCache(cfg)
     _, ref = lm.layer_forward(cfg, vals[0], xv, batch, cache, 0, 1,
-                              None if dtype == wl.F32 else (lambda a: wl.bf16_to_f32(wl.bf16_bits(a.astype(np.float32))).astype(np.float64)))
+                              None if dtype == wl.F32 else (lambda a: wl.round_to_storage(a, dtype)))
     assert rel_err(to_f64(y_pp, dtype), ref) <= tol(dtype)
     ctx.destroy()
 

@@ -18,6 +18,7 @@ import numpy as np
 
 F32 = 0
 BF16 = 1
+F16 = 2          # IEEE half, the paper's own precision (section 6.1)
 
 
 @dataclass
@@ -71,6 +72,9 @@ def quantize(x, dtype):
     x32 = np.ascontiguousarray(x, dtype=np.float32)
     if dtype == F32:
         return x32.astype(np.float64), x32
+    if dtype == F16:
+        h = x32.astype(np.float16)                      # numpy rounds to nearest even
+        return h.astype(np.float64), h.view(np.uint16)
     bits = bf16_bits(x32)
     return bf16_to_f32(bits).astype(np.float64), bits
 
@@ -78,7 +82,16 @@ def quantize(x, dtype):
 def storage_to_f64(raw, dtype):
     if dtype == F32:
         return np.asarray(raw, dtype=np.float32).astype(np.float64)
+    if dtype == F16:
+        return np.ascontiguousarray(raw, dtype=np.uint16).view(np.float16).astype(np.float64)
     return bf16_to_f32(raw).astype(np.float64)
+
+
+def round_to_storage(a, dtype):
+    """float64 array rounded to the storage type and back (what a cache kept in that type holds)."""
+    if dtype == F32:
+        return np.asarray(a, dtype=np.float32).astype(np.float64)
+    return quantize(np.asarray(a, dtype=np.float32), dtype)[0]
 
 
 def storage_np_dtype(dtype):
@@ -210,7 +223,7 @@ def device_normal(shape, seed, dtype, std=1.0, device="cuda"):
     import torch
     g = torch.Generator(device=device)
     g.manual_seed(int(seed))
-    t = torch.empty(shape, device=device, dtype=torch.float32 if dtype == F32 else torch.bfloat16)
+    t = torch.empty(shape, device=device, dtype={F32: torch.float32, BF16: torch.bfloat16, F16: torch.float16}[dtype])
     t.normal_(0.0, std, generator=g)
     return t
 
