@@ -127,8 +127,8 @@ def offline_loop_bench(torch, wl, ss, hz):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=6)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-reshard", action="store_true", help="leave the KV re-shard out of the step")
     ap.add_argument("--pinned-mb", type=int, default=256, help="pinned staging ring of the KV movers (two lanes x two slots)")
