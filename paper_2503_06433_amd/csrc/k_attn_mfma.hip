@@ -410,7 +410,7 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
                                                               float* __restrict__ scratch, float scale_log2e) {
     constexpr int KS = D / 32;
     constexpr int DT = D / 16;
-    const int item = wk.item_order[blockIdx.x], g = blockIdx.y;
+    const int item = wk.item_order[blockIdx.x / n_kv], g = blockIdx.x % n_kv;     // the heads of an item side by side
     const int G = n_q / n_kv;
     const int sq = wk.item_seq[item];
     const int page0 = wk.item_page0[item], npg = wk.item_npages[item];
@@ -534,7 +534,8 @@ hipError_t attn_decode(int dt, const void* qkv, void* out, int n_q, int n_kv, co
     if (kv.page_size != 16 || kv.n_heads != n_kv || !scratch || wk.n_items <= 0) return hipErrorInvalidValue;
     if (n_kv > 65535 || bm.n_seqs > 65535) return hipErrorInvalidValue;
     const float sl2 = 1.4426950408889634f / sqrtf((float)kv.d);
-    dim3 grid(wk.n_items, n_kv);
+    if ((long long)wk.n_items * n_kv > 0x7fffffffll) return hipErrorInvalidValue;
+    dim3 grid((unsigned)(wk.n_items * n_kv));
     attn_decode_mfma_kernel<128><<<grid, 64, 0, s>>>((const bf16_t*)qkv, n_q, n_kv, bm, wk,
                                                      (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, scratch, sl2);
     dim3 mgrid((n_q + 7) / 8, bm.n_seqs);
