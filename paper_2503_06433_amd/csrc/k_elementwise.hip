@@ -153,7 +153,9 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(T* __restrict__ qkv, 
                                                            T* __restrict__ k_pool, T* __restrict__ v_pool) {
     constexpr int V = VecOf<T>::N;
     constexpr int PS = 16;
-    const int u = blockIdx.x, g0 = blockIdx.y * HB;          // HB kv heads per block
+    // the head groups of a page unit are adjacent blocks: together they read whole rows of the qkv buffer
+    const int n_hg = (n_kv + HB - 1) / HB;
+    const int u = blockIdx.x / n_hg, g0 = (blockIdx.x % n_hg) * HB;          // HB kv heads per block
     const int sq = bm.unit_seq[u], tok0 = bm.unit_tok0[u], pos0 = bm.unit_pos0[u], cnt = bm.unit_cnt[u];
     const int page = bm.page_tables[(size_t)sq * bm.pt_stride + pos0 / PS];
     const int slot0 = pos0 % PS;
@@ -241,17 +243,17 @@ hipError_t rope_kvwrite(int dt, void* qkv, int n_q, int n_kv, const float* rope_
     const int V = dt == F32 ? 4 : 8;
     if (kv.d % (2 * V) != 0 || kv.n_heads != n_kv || kv.page_size != 16 || n_kv <= 0 || n_q % n_kv != 0 || n_kv > 65535)
         return hipErrorInvalidValue;
-    if (kv.d > 128) return hipErrorInvalidValue;
+    if (kv.d > 128 || (long long)bm.n_units * n_kv > 0x7fffffffll) return hipErrorInvalidValue;
     if (dt == F32) {
-        dim3 grid(bm.n_units, n_kv);
+        dim3 grid((unsigned)(bm.n_units * n_kv));
         rope_kvwrite_kernel<float, 1><<<grid, 256, 0, s>>>((float*)qkv, n_q, n_kv, kv.d, rope_table, bm,
                                                            (float*)kv.k_pool, (float*)kv.v_pool);
     } else if (n_kv >= 4 && bm.n_units >= 256) {    // prefill-sized: several kv heads per block (cos / sin reused)
-        dim3 grid(bm.n_units, (n_kv + 3) / 4);
+        dim3 grid((unsigned)(bm.n_units * ((n_kv + 3) / 4)));
         rope_kvwrite_kernel<bf16_t, 4><<<grid, 256, 0, s>>>((bf16_t*)qkv, n_q, n_kv, kv.d, rope_table, bm,
                                                             (bf16_t*)kv.k_pool, (bf16_t*)kv.v_pool);
     } else {
-        dim3 grid(bm.n_units, n_kv);
+        dim3 grid((unsigned)(bm.n_units * n_kv));
         rope_kvwrite_kernel<bf16_t, 1><<<grid, 256, 0, s>>>((bf16_t*)qkv, n_q, n_kv, kv.d, rope_table, bm,
                                                             (bf16_t*)kv.k_pool, (bf16_t*)kv.v_pool);
     }
