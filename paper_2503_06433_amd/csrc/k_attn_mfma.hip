@@ -22,6 +22,13 @@ using namespace ssk;
 // in range scaling for denormal results: four more VALU operations per element in the innermost loop.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// max of a value with the one held by the lane 32 positions away (v_permlane32_swap: no LDS round trip)
+__device__ __forceinline__ float max_with_other_half(float x) {
+    const unsigned u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 typedef half8_t bf16x8_t;       // MFMA operand: 8 elements of the 16-bit type
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
@@ -174,7 +181,7 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const bf16_t* __
 
 // ----------------------------------------------------------------------
 // Prefill, LDS-staged.  Block = 8 waves = 256 consecutive queries of one (sequence, q head).  The K
-// and V^T chunks of 64 tokens (4 pages, 32 KB) are brought into a two-stage LDS ring with direct
+// and V^T chunks of 64 tokens (4 pages, 32 KB) are brought into a three-stage LDS ring (two tiles in flight) with direct
 // global->LDS loads and shared by all eight waves, which cuts the L2 traffic of the attention by 8
 // against every wave fetching its own operands.  K rows (256 bytes) are stored with the 16-byte
 // chunk index XOR-ed with the row number, so the 16 rows one pass of a fragment read touches fall
@@ -192,7 +199,7 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
                                                                const bf16_t* __restrict__ k_pool,
                                                                const bf16_t* __restrict__ v_pool, float scale_log2e) {
     static_assert(D == 128, "layout below assumes 256-byte K rows");
-    constexpr int KS = D / 16, DT = D / 32, NS = 2;
+    constexpr int KS = D / 16, DT = D / 32, NS = 3;
     constexpr int KBYTES = 64 * D * 2, STAGE = 2 * KBYTES;     // 16 KB of K + 16 KB of V^T
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     // Block -> (sequence, q head, block of 256 queries).  Blocks are dealt to the 8 XCDs round-robin by their
@@ -245,19 +252,21 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
 
     // DMA assignment per stage: wave w brings K rows [8w, 8w+8) (two loads of 4 rows) and V^T pieces 2w, 2w+1
     // (piece i = page i/4 of the tile, d rows [32*(i%4), +32): 1 KB contiguous in the page).  All of a wave's
-    // rows and pieces lie in page w/2 of the tile, so one page-table entry per wave and tile is needed; it
-    // is fetched one tile ahead (page_next), off the path between the barrier and the requests.
-    auto tile_page = [&](int tile) {
-        const int tl = tile < n_tiles ? tile : n_tiles - 1;     // past the end: harmless repeat, keeps vmcnt uniform
-        int pg = tl * 4 + (wave >> 1);
+    // rows and pieces lie in page w/2 of the tile, so one page-table entry per wave and tile is needed.  Lane i
+    // holds the entry for tile pages_base + i (refilled every 64 tiles) and the loop picks it with a lane
+    // read: no memory access, and so no wait for one, sits between the barrier and the requests.  Entries
+    // past the last page repeat it: a tile issued past the end is a harmless repeat that keeps vmcnt uniform.
+    int pages_vec;
+    auto load_pages = [&](int base) {
+        int pg = (base + lane) * 4 + (wave >> 1);
         pg = pg < n_pages ? pg : n_pages - 1;
-        return pt[pg];
+        pages_vec = pt[pg];
     };
-    int page_next = tile_page(0);
+    load_pages(0);
     auto issue = [&](int tile) {
         const uint32_t st = lds_base + (uint32_t)(tile % NS) * STAGE;
-        const size_t page_off = (size_t)page_next * page_elems + head_off;
-        page_next = tile_page(tile + 1);
+        const int page = __builtin_amdgcn_readlane(pages_vec, tile & 63);
+        const size_t page_off = (size_t)page * page_elems + head_off;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int row = wave * 8 + i * 4 + (lane >> 4);     // token row of the tile
@@ -273,72 +282,148 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
         }
     };
 
+    // One step of the streaming softmax (base 2, scale folded into the exponent) on the 32 tokens of a
+    // score accumulator: updates m and l, leaves the weights packed as the B operands of the two P V
+    // products and returns the factor the accumulated output has to be multiplied by.  The reference
+    // maximum m follows the true running maximum only when that has grown by more than 8 (in the exponent's
+    // units): until then weights may reach 2^8 instead of 1, which fp32 sums and the 16-bit weights hold
+    // without loss, the result o / l is the same, and the 64 multiplications of the output accumulator
+    // are skipped in all but the first steps of a row.
+    auto softmax_step = [&](f32x16_t& sc, Frag& pfA, Frag& pfB) {
+        float mr = fmaxf(fmaxf(sc[0], sc[1]), sc[2]);
+#pragma unroll
+        for (int v = 3; v < 15; v += 2) mr = fmaxf(fmaxf(mr, sc[v]), sc[v + 1]);
+        mr = fmaxf(mr, sc[15]);
+        mr = max_with_other_half(mr);
+        const float mx = fmaxf(m, mr * scale_log2e);
+        const bool moved = mx - m > 8.0f;               // also true for the first step (m = -inf)
+        const float alpha = moved ? fast_exp2(m - mx) : 1.0f;
+        m = moved ? mx : m;
+        float rs = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { sc[v] = fast_exp2(fmaf(sc[v], scale_log2e, -m)); rs += sc[v]; }
+        l = l * alpha + rs;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            pfA.w[i] = pack_bf16x2(sc[2 * i], sc[2 * i + 1]);
+            pfB.w[i] = pack_bf16x2(sc[8 + 2 * i], sc[8 + 2 * i + 1]);
+        }
+        // the weights are complete here, not wherever their first use is moved to
+        asm volatile("" : "+v"(pfA.w[0]), "+v"(pfA.w[1]), "+v"(pfA.w[2]), "+v"(pfA.w[3]), "+v"(pfB.w[0]), "+v"(pfB.w[1]),
+                          "+v"(pfB.w[2]), "+v"(pfB.w[3]));
+        return alpha;
+    };
+    // causal mask of a score accumulator whose first token is t0
+    auto mask_step = [&](f32x16_t& sc, int t0) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int tpos = t0 + 8 * (v >> 2) + 4 * g2 + (v & 3);
+            sc[v] = (tpos <= p) ? sc[v] : -INFINITY;
+        }
+    };
+    auto rescale = [&](float alpha) {
+        if (__ballot(alpha != 1.0f) != 0ull) {          // the reference maximum moved for some query of the wave
+#pragma unroll
+            for (int u = 0; u < DT; ++u)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[u][v] *= alpha;
+        }
+    };
+
+    // The query fragments and the page-table entries are loads into registers; the tiles are loads into
+    // LDS.  The two kinds do not complete in issue order with respect to each other, so the counter
+    // arithmetic of the loop (vmcnt <= 4: everything but the newest tile has landed) holds only while
+    // nothing but tile loads is in flight: everything else is waited for before the first request.
+    // (the empty statements make the loaded registers inputs of something that precedes the requests)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks].w[0]), "+v"(qf[ks].w[1]), "+v"(qf[ks].w[2]), "+v"(qf[ks].w[3]));
+    asm volatile("" : "+v"(pages_vec));
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_sched_barrier(0);
     issue(0);
+    issue(1);
     for (int it = 0; it < n_tiles; ++it) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt == 0: this wave's part of tile `it` has landed
+        __builtin_amdgcn_s_waitcnt(0x0F74);            // vmcnt <= 4: this wave's part of tile `it` has landed
         __builtin_amdgcn_s_barrier();                  // everyone's part landed; stage (it-1)%NS is free
         __builtin_amdgcn_sched_barrier(0);
-        issue(it + 1);
+        if (((it + 2) & 63) == 0) {                    // every 64 tiles; waited for here, so that no wait
+            load_pages(it + 2);                        // is due where the entries are picked
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+        }
+        issue(it + 2);
         if (!wave_active || it * 64 > wave_last) continue;     // nothing visible to this wave in the tile
         const uint8_t* st = smem + (it % NS) * STAGE;
+        // The two halves of 32 tokens are software-pipelined so that the MFMA pipe and the vector ALU work at
+        // the same time: the score product of the second half is issued next to the softmax of the first,
+        // the P V product of the first half next to the softmax of the second, and every LDS fragment read
+        // is issued a phase ahead of its use.  Only the last tile or two of a wave hold tokens that some of
+        // its queries must not see (wave-uniform test); a half that is hidden altogether is computed and
+        // masked like the rest (weights 0).
+        const bool diag = it * 64 + 63 > before + q0;
+        const uint8_t* kp = st + lq * 256;
+        const int sw = lq & 15;                         // rows lq and 32 + lq share the swizzle
+        Frag ka[KS], kb[KS];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int t0 = it * 64 + h * 32;
-            if (t0 > wave_last) break;
-            // ---- S^T = K Q^T for 32 tokens
-            const int row = h * 32 + lq;
-            f32x16_t s;
+        for (int ks = 0; ks < KS; ++ks) ka[ks].v = *reinterpret_cast<const bf16x8_t*>(kp + (((ks * 2 + g2) ^ sw) << 4));
 #pragma unroll
-            for (int v = 0; v < 16; ++v) s[v] = 0.f;
+        for (int ks = 0; ks < KS; ++ks) kb[ks].v = *reinterpret_cast<const bf16x8_t*>(kp + 32 * 256 + (((ks * 2 + g2) ^ sw) << 4));
+        f32x16_t s0, s1;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                Frag kf;
-                kf.v = *reinterpret_cast<const bf16x8_t*>(st + row * 256 + (((ks * 2 + g2) ^ (row & 15)) << 4));
-                s = SS_MFMA_32x32x16(kf.v, qf[ks].v, s, 0, 0, 0);
-            }
-            // causal mask only on steps that reach past the wave's first query (wave-uniform test)
-            if (t0 + 31 > before + q0) {
+        for (int v = 0; v < 16; ++v) { s0[v] = 0.f; s1[v] = 0.f; }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int tpos = t0 + 8 * (v >> 2) + 4 * g2 + (v & 3);
-                    s[v] = (tpos <= p) ? s[v] : -INFINITY;
-                }
-            }
-            // streaming softmax in base 2 on the raw scores: exp2(s*c - max*c) with c = log2(e)/sqrt(d)
-            float mr = s[0];
+        for (int ks = 0; ks < KS; ++ks) s0 = SS_MFMA_32x32x16(ka[ks].v, qf[ks].v, s0, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        const uint8_t* vp = st + KBYTES + lq * 32 + g2 * 16;
+        Frag va[DT], vb[DT];
 #pragma unroll
-            for (int v = 1; v < 16; ++v) mr = fmaxf(mr, s[v]);
-            mr = fmaxf(mr, __shfl_xor(mr, 32, 64));
-            const float mx = fmaxf(m, mr * scale_log2e);
-            const float alpha = fast_exp2(m - mx);
-            m = mx;
-            float rs = 0.f;
+        for (int u = 0; u < DT; ++u) {
+            va[u].v = *reinterpret_cast<const bf16x8_t*>(vp + u * 1024);
+            vb[u].v = *reinterpret_cast<const bf16x8_t*>(vp + 4096 + u * 1024);
+        }
+        if (diag) mask_step(s0, it * 64);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { s[v] = fast_exp2(fmaf(s[v], scale_log2e, -mx)); rs += s[v]; }
-            l = l * alpha + rs;
-            if (__ballot(alpha != 1.0f) != 0ull) {       // the running maximum moved for some query of the wave
+        for (int ks = 0; ks < KS; ++ks) s1 = SS_MFMA_32x32x16(kb[ks].v, qf[ks].v, s1, 0, 0, 0);
+        Frag pA, pB;
+        float alpha = softmax_step(s0, pA, pB);
 #pragma unroll
-                for (int u = 0; u < DT; ++u)
+        for (int i = 0; i < KS; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);      // vector ALU work of the softmax
+            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);      // two exponentials
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (diag) mask_step(s1, it * 64 + 32);
+        rescale(alpha);
+        Frag vc[DT], vd[DT];
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) o[u][v] *= alpha;
-            }
-            Frag pfA, pfB;
+        for (int u = 0; u < DT; ++u) {
+            vc[u].v = *reinterpret_cast<const bf16x8_t*>(vp + 8192 + u * 1024);
+            vd[u].v = *reinterpret_cast<const bf16x8_t*>(vp + 12288 + u * 1024);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                pfA.w[i] = pack_bf16x2(s[2 * i], s[2 * i + 1]);
-                pfB.w[i] = pack_bf16x2(s[8 + 2 * i], s[8 + 2 * i + 1]);
-            }
-            // ---- O^T += V^T P^T : pages 2h and 2h+1 of the tile
-            const uint8_t* vA = st + KBYTES + (2 * h) * 4096 + lq * 32 + g2 * 16;
-            const uint8_t* vB = vA + 4096;
+        for (int u = 0; u < DT; ++u) {
+            o[u] = SS_MFMA_32x32x16(va[u].v, pA.v, o[u], 0, 0, 0);
+            o[u] = SS_MFMA_32x32x16(vb[u].v, pB.v, o[u], 0, 0, 0);
+        }
+        Frag pC, pD;
+        alpha = softmax_step(s1, pC, pD);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);          // the row maximum has to be there before
+        __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);         // the first exponential
 #pragma unroll
-            for (int u = 0; u < DT; ++u) {
-                Frag va, vb;
-                va.v = *reinterpret_cast<const bf16x8_t*>(vA + u * 1024);
-                vb.v = *reinterpret_cast<const bf16x8_t*>(vB + u * 1024);
-                o[u] = SS_MFMA_32x32x16(va.v, pfA.v, o[u], 0, 0, 0);
-                o[u] = SS_MFMA_32x32x16(vb.v, pfB.v, o[u], 0, 0, 0);
-            }
+        for (int i = 1; i < 2 * DT; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 3, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        rescale(alpha);
+#pragma unroll
+        for (int u = 0; u < DT; ++u) {
+            o[u] = SS_MFMA_32x32x16(vc[u].v, pC.v, o[u], 0, 0, 0);
+            o[u] = SS_MFMA_32x32x16(vd[u].v, pD.v, o[u], 0, 0, 0);
         }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);                // drain the repeats issued past the end
@@ -374,7 +459,7 @@ hipError_t attn_prefill(int dt, const void* qkv, void* out, int n_q, int n_kv, c
                                                                (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, sl2);
         return hipGetLastError();
     }
-    constexpr int LDS = 2 * 32768;
+    constexpr int LDS = 3 * 32768;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)attn_prefill_lds_kernel<128>,
