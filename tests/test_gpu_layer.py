@@ -324,3 +324,26 @@ def test_prefill_many_pages_six_kv_heads_cache_matches_oracle():
         got = wl.storage_to_f64(ctx.kv_read(d, sid, 0, cfg.n_kv_heads), cfg.dtype)
         assert rel_err(got, cache.data[sid][0]) <= tol(cfg.dtype)
     ctx.destroy()
+
+
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.F16])
+def test_prefill_wide_score_range_matches_oracle(dtype):
+    """Weights three times the usual scale make the attention scores nine times as wide (standard deviation
+    about 2.7 in the exponent's base-2 units, row maxima near 9): the running maximum of a row then grows both
+    in small steps and by more than the slack the prefill kernel allows its reference maximum before it rescales
+    the accumulated output, so both branches of that rule are exercised on rows of up to 57 steps."""
+    cfg = wl.ModelCfg(n_layers=1, dtype=dtype, **SMALL["mha_d128"])
+    v, r = wl.make_layer_weights(cfg, 300, std=0.06)
+    lens = [900, 300, 77]
+    T = sum(lens)
+    xv, xr = wl.make_activations((T, cfg.hidden), 17, dtype)
+    ctx = make_context(cfg, pages=128)
+    d = pp_desc(cfg)
+    ctx.load_layer(d, 0, r)
+    ids = [5, 6, 7]
+    out = empty_like_acts(T, cfg.hidden, dtype)
+    ctx.layer_prefill(d, 0, ss.SS_ATTN | ss.SS_NO_RESIDUAL, ids, lens, [0] * 3, to_device(xr, dtype), out)
+    torch.cuda.synchronize()
+    ref = lm.attn_block(cfg, v, xv, [(i, n, 0) for i, n in zip(ids, lens)], lm.KVCache(cfg), 0, round_kv=_round_kv(cfg))
+    assert rel_err(to_f64(out, dtype), ref) <= tol(dtype)
+    ctx.destroy()
