@@ -11,6 +11,8 @@
 // The contraction order inside one MFMA is free as long as both operands agree:
 // the token <-> k-slot assignment below is chosen to match what the S^T
 // accumulator holds, and the V^T operand is gathered with the same assignment.
+#include <type_traits>
+
 #include "ss_device.h"
 #include "ss_kernels.h"
 
@@ -521,21 +523,48 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
     const int32_t* pt = bm.page_tables + (size_t)sq * bm.pt_stride + page0;
     const size_t page_elems = (size_t)n_kv * 16 * D;
     const size_t head_off = (size_t)g * 16 * D;
-    for (int pi = 0; pi < npg; pi += 2) {
+    // tokens 4*g4 .. 4*g4+3 sit at piece ((g4 & 1) << 1 | g4 >> 1) of a V^T row (see vslot)
+    const int vpiece = ((g4 & 1) << 1) | (g4 >> 1);
+    const size_t k_lane = head_off + (size_t)lq * D + g4 * 8, v_lane = head_off + (size_t)lq * 16 + 4 * vpiece;
+    // The loop is software-pipelined over page pairs: the K fragments of the next pair (8 KB per wave) are
+    // requested right after the score product of this pair has consumed its own, and the V^T fragments of
+    // this pair before that product, so that a wave always has 8 to 16 KB on their way instead of the 2 KB
+    // the plain order (load two fragments, multiply, load the next two) keeps in flight.  Past the last
+    // pair the prefetch repeats the last page (a cache hit), which keeps the loop free of a branch that
+    // would make the load counter's bookkeeping conservative.
+    auto pair_pages = [&](int pi, int& pgA, int& pgB) {
+        const int ia = pi < npg ? pi : npg - 1, ib = pi + 1 < npg ? pi + 1 : npg - 1;
+        pgA = pt[ia];
+        pgB = pt[ib];
+    };
+    auto load_k = [&](int pgA, int pgB, Frag* fa, Frag* fb) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            fa[ks].q = *reinterpret_cast<const vec16*>(k_pool + (size_t)pgA * page_elems + k_lane + ks * 32);
+            fb[ks].q = *reinterpret_cast<const vec16*>(k_pool + (size_t)pgB * page_elems + k_lane + ks * 32);
+        }
+    };
+    // one pair of pages: fragments ka / kb hold its K, na / nb receive the K of the next pair
+    auto step = [&](auto prefetch, int pi, int pA, int pB, const Frag* ka, const Frag* kb, int nA, int nB, Frag* na, Frag* nb) {
         const bool hasB = pi + 1 < npg;
-        const int pA = pt[pi];
-        const int pB = pt[hasB ? pi + 1 : pi];
-        const bf16_t* kA = k_pool + (size_t)pA * page_elems + head_off + (size_t)lq * D + g4 * 8;
-        const bf16_t* kB = k_pool + (size_t)pB * page_elems + head_off + (size_t)lq * D + g4 * 8;
+        const bf16_t* vA = v_pool + (size_t)pA * page_elems + v_lane;
+        const bf16_t* vB = v_pool + (size_t)pB * page_elems + v_lane;
+        Frag vf[DT];
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+            vf[t].h[0] = *reinterpret_cast<const vec8*>(vA + t * 16 * 16);
+            vf[t].h[1] = *reinterpret_cast<const vec8*>(vB + t * 16 * 16);
+        }
+        __builtin_amdgcn_sched_barrier(0);
         f32x4_t sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            Frag ka, kb;
-            ka.q = *reinterpret_cast<const vec16*>(kA + ks * 32);
-            kb.q = *reinterpret_cast<const vec16*>(kB + ks * 32);
-            sA = SS_MFMA_16x16x32(ka.v, qf[ks].v, sA, 0, 0, 0);
-            sB = SS_MFMA_16x16x32(kb.v, qf[ks].v, sB, 0, 0, 0);
+            sA = SS_MFMA_16x16x32(ka[ks].v, qf[ks].v, sA, 0, 0, 0);
+            sB = SS_MFMA_16x16x32(kb[ks].v, qf[ks].v, sB, 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (decltype(prefetch)::value) load_k(nA, nB, na, nb);
+        __builtin_amdgcn_sched_barrier(0);
         const int posA = (page0 + pi) * 16 + 4 * g4;
         float mx = m;
 #pragma unroll
@@ -562,20 +591,28 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
         pf.w[1] = pack_bf16x2(sA[2], sA[3]);
         pf.w[2] = pack_bf16x2(sB[0], sB[1]);
         pf.w[3] = pack_bf16x2(sB[2], sB[3]);
-        // tokens 4*g4 .. 4*g4+3 sit at piece ((g4 & 1) << 1 | g4 >> 1) of the row (see vslot)
-        const int vpiece = ((g4 & 1) << 1) | (g4 >> 1);
-        const bf16_t* vA = v_pool + (size_t)pA * page_elems + head_off + (size_t)lq * 16 + 4 * vpiece;
-        const bf16_t* vB = v_pool + (size_t)pB * page_elems + head_off + (size_t)lq * 16 + 4 * vpiece;
 #pragma unroll
         for (int t = 0; t < DT; ++t) {
-            Frag vf;
-            vf.h[0] = *reinterpret_cast<const vec8*>(vA + t * 16 * 16);
-            vf.h[1] = *reinterpret_cast<const vec8*>(vB + t * 16 * 16);
 #pragma unroll
             for (int v = 0; v < 4; ++v) o[t][v] *= alpha;
-            o[t] = SS_MFMA_16x16x32(vf.v, pf.v, o[t], 0, 0, 0);
+            o[t] = SS_MFMA_16x16x32(vf[t].v, pf.v, o[t], 0, 0, 0);
         }
+    };
+    // two steps per trip, the two fragment sets changing roles, so that no set is ever copied; a last
+    // single pair runs without a prefetch
+    int pA, pB;
+    pair_pages(0, pA, pB);
+    Frag k0a[KS], k0b[KS], k1a[KS], k1b[KS];
+    load_k(pA, pB, k0a, k0b);
+    int pi = 0;
+    for (; pi + 2 < npg; pi += 4) {
+        int nA, nB;
+        pair_pages(pi + 2, nA, nB);
+        step(std::true_type{}, pi, pA, pB, k0a, k0b, nA, nB, k1a, k1b);
+        pair_pages(pi + 4, pA, pB);
+        step(std::true_type{}, pi + 2, nA, nB, k1a, k1b, pA, pB, k0a, k0b);
     }
+    if (pi < npg) step(std::false_type{}, pi, pA, pB, k0a, k0b, pA, pB, k1a, k1b);
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
     if (lq < G) {

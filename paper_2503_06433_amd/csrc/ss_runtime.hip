@@ -387,6 +387,19 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
         max_q = std::max(max_q, ql);
     }
     if (T > (1 << 30)) return fail(c, SS_EINVAL, "batch too large");
+    {   // all or nothing: a batch that does not fit leaves no sequence with pages it did not have before
+        size_t more = 0;
+        const int ps = c->m.page_size;
+        for (int i = 0; i < n; ++i) {
+            const size_t need = (size_t)((b->kv_lens_before[i] + b->q_lens[i] + ps - 1) / ps);
+            auto it = s->seqs.find(b->seq_ids[i]);
+            const size_t have = it == s->seqs.end() ? 0 : it->second.pages.size();
+            if (need > have) more += need - have;
+        }
+        if (more > s->free_pages.size())
+            return fail(c, SS_ENOMEM, "page pool exhausted: the batch needs %zu more pages, %zu free", more,
+                        s->free_pages.size());
+    }
     for (int i = 0; i < n; ++i) {
         int rc = ensure_pages(c, s, b->seq_ids[i], b->kv_lens_before[i] + b->q_lens[i]);
         if (rc) return rc;

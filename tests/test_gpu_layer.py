@@ -275,6 +275,12 @@ def test_descriptor_and_argument_errors():
         big = empty_like_acts(80, cfg.hidden, cfg.dtype)
         ctx.layer_prefill(d, 0, ss.SS_BOTH, [0], [80], [0], big, empty_like_acts(80, cfg.hidden, cfg.dtype))
     assert e.value.code == ss.SS_ENOMEM
+    assert ctx.kv_free_pages(d) == 4
+    with pytest.raises(ss.SeesawError) as e:        # 2 + 3 pages: the batch fails as a whole and keeps no page
+        xb = empty_like_acts(70, cfg.hidden, cfg.dtype)
+        ctx.layer_prefill(d, 0, ss.SS_BOTH, [1, 2], [30, 40], [0, 0], xb, empty_like_acts(70, cfg.hidden, cfg.dtype))
+    assert e.value.code == ss.SS_ENOMEM
+    assert ctx.kv_free_pages(d) == 4
     td = tp_desc(cfg, 2, 0)
     _load(ctx, td, cfg, raws)
     with pytest.raises(ss.SeesawError) as e:        # fused phases need k == 1
