@@ -34,6 +34,7 @@ __device__ __forceinline__ float max_with_other_half(float x) {
 typedef half8_t bf16x8_t;       // MFMA operand: 8 elements of the 16-bit type
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef int i32x8_t __attribute__((ext_vector_type(8)));
 
 struct __attribute__((aligned(8))) vec8 { uint32_t w[2]; };
 
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const bf16_t* __
 }
 
 // ----------------------------------------------------------------------
-// Prefill, LDS-staged.  Block = 8 waves = 256 consecutive queries of one (sequence, q head).  The K
+// Prefill, LDS-staged.  A block of 8 waves works on one item at a time: 256 consecutive queries of one (sequence, q head).  The K
 // and V^T chunks of 64 tokens (4 pages, 32 KB) are brought into a three-stage LDS ring (two tiles in flight) with direct
 // global->LDS loads and shared by all eight waves, which cuts the L2 traffic of the attention by 8
 // against every wave fetching its own operands.  K rows (256 bytes) are stored with the 16-byte
@@ -197,32 +198,36 @@ __device__ __forceinline__ void dma16a(const void* gptr, uint32_t lds_addr) {
 
 template <int D>
 __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
-                                                               int n_q, int n_kv, int nqb, BatchMeta bm,
+                                                               int n_q, int n_kv, BatchMeta bm,
                                                                const bf16_t* __restrict__ k_pool,
                                                                const bf16_t* __restrict__ v_pool, float scale_log2e) {
     static_assert(D == 128, "layout below assumes 256-byte K rows");
     constexpr int KS = D / 16, DT = D / 32, NS = 3;
     constexpr int KBYTES = 64 * D * 2, STAGE = 2 * KBYTES;     // 16 KB of K + 16 KB of V^T
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    // Block -> (sequence, q head, block of 256 queries).  Blocks are dealt to the 8 XCDs round-robin by their
-    // linear id; all blocks that read the K and V pages of one (sequence, kv head) -- the query blocks of
-    // every q head of its group -- are given ids of the same residue, so that they run on one XCD and those
-    // pages are fetched into one L2 instead of eight.  The blocks with the most cached tokens to visit (the
-    // last queries) come first.
+    // Persistent blocks, one per compute unit: block b walks its list of items (sequence, q head, block of
+    // 256 queries) that the host has laid out (see BatchMeta::pf_items): launching a block of this size per
+    // item costs 3-4 us of dispatch each, a sixth of the kernel's time on prompts of one or two thousand tokens.
     const int G = n_q / n_kv;
-    const int per_unit = G * nqb;
-    const int chunk = blockIdx.x / (8 * per_unit), rr = blockIdx.x % (8 * per_unit);
-    const int unit = chunk * 8 + (rr & 7), j = rr >> 3;
-    if (unit >= n_kv * bm.n_seqs) return;                      // whole block: before any barrier
-    const int sq = unit / n_kv, g = unit - sq * n_kv;
-    const int a = g * G + j % G;
-    const int q_begin = bm.cu_q[sq], q_len = bm.cu_q[sq + 1] - q_begin;
-    const int qb0 = (nqb - 1 - j / G) * 256;
-    if (qb0 >= q_len) return;                                  // whole block: before any barrier
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int before = bm.kv_before[sq];
     const int lq = lane & 31, g2 = lane >> 5;
+    const size_t row_stride = (size_t)(n_q + 2 * n_kv) * D;
+    const size_t page_elems = (size_t)n_kv * 16 * D;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
+    for (int pj = 0;; ++pj) {
+    // the item's record through the scalar cache: one load, a few hundred nanoseconds (as ordinary loads the
+    // six values would be as many dependent round trips, the loop's memory clobbers keep them from being merged)
+    const int32_t* item = bm.pf_items + ((size_t)blockIdx.x * bm.pf_stride + pj) * 8;
+    i32x8_t rec;
+    asm volatile("s_load_dwordx8 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(rec) : "s"(item) : "memory");
+    const int sq = rec[0];
+    if (sq < 0) break;                                         // end of the list: the whole block leaves
+    const int a = rec[1], qb0 = rec[2], q_begin = rec[3], q_len = rec[4];
+    const int g = a / G;
+    // every wave is done with the LDS stages of the previous item before the first requests of this one
+    __builtin_amdgcn_s_barrier();
+    const int before = rec[5];
     const int q0 = qb0 + wave * 32;
     const int qi = q0 + lq;
     const bool valid = qi < q_len;
@@ -233,18 +238,9 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
     const int blk_last = before + ((qb0 + 255 < q_len) ? qb0 + 255 : q_len - 1);
     const int n_pages = blk_last / 16 + 1;
     const int n_tiles = (n_pages + 3) / 4;
-    const size_t row_stride = (size_t)(n_q + 2 * n_kv) * D;
     const int32_t* pt = bm.page_tables + (size_t)sq * bm.pt_stride;
-    const size_t page_elems = (size_t)n_kv * 16 * D;
     const size_t head_off = (size_t)g * 16 * D;
-    const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
 
-    Frag qf[KS];
-    {
-        const bf16_t* qp = qkv + (size_t)(q_begin + (valid ? qi : 0)) * row_stride + (size_t)a * D + g2 * 8;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks].q = *reinterpret_cast<const vec16*>(qp + ks * 16);
-    }
     f32x16_t o[DT];
 #pragma unroll
     for (int u = 0; u < DT; ++u)
@@ -256,8 +252,7 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
     // (piece i = page i/4 of the tile, d rows [32*(i%4), +32): 1 KB contiguous in the page).  All of a wave's
     // rows and pieces lie in page w/2 of the tile, so one page-table entry per wave and tile is needed.  Lane i
     // holds the entry for tile pages_base + i (refilled every 64 tiles) and the loop picks it with a lane
-    // read: no memory access, and so no wait for one, sits between the barrier and the requests.  Entries
-    // past the last page repeat it: a tile issued past the end is a harmless repeat that keeps vmcnt uniform.
+    // read: no memory access, and so no wait for one, sits between the barrier and the requests.
     int pages_vec;
     auto load_pages = [&](int base) {
         int pg = (base + lane) * 4 + (wave >> 1);
@@ -332,27 +327,42 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
         }
     };
 
-    // The query fragments and the page-table entries are loads into registers; the tiles are loads into
-    // LDS.  The two kinds do not complete in issue order with respect to each other, so the counter
-    // arithmetic of the loop (vmcnt <= 4: everything but the newest tile has landed) holds only while
-    // nothing but tile loads is in flight: everything else is waited for before the first request.
-    // (the empty statements make the loaded registers inputs of something that precedes the requests)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks].w[0]), "+v"(qf[ks].w[1]), "+v"(qf[ks].w[2]), "+v"(qf[ks].w[3]));
+    // Start of a block: the page-table entries first (the tile requests need them), then the requests for
+    // the first two tiles, then the query fragments, whose load latency the tile requests overlap.  The query
+    // fragments are loads into registers, the tiles loads into LDS; the two kinds do not complete in issue
+    // order with respect to each other, so the counter arithmetic of the loop (vmcnt <= 4: everything but
+    // the newest tile has landed) holds only while nothing but tile loads is in flight: the loop is entered
+    // with everything landed.  (The empty statements make the loaded registers inputs of something that
+    // precedes, in program order, what must follow the load.)
     asm volatile("" : "+v"(pages_vec));
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __builtin_amdgcn_sched_barrier(0);
     issue(0);
-    issue(1);
+    if (n_tiles > 1) issue(1);
+    Frag qf[KS];
+    {
+        const bf16_t* qp = qkv + (size_t)(q_begin + (valid ? qi : 0)) * row_stride + (size_t)a * D + g2 * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks].q = *reinterpret_cast<const vec16*>(qp + ks * 16);
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[ks].w[0]), "+v"(qf[ks].w[1]), "+v"(qf[ks].w[2]), "+v"(qf[ks].w[3]));
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_sched_barrier(0);
+    // No tile is requested past the last one (the block would only have to wait for it at the end), so the
+    // last iteration waits for everything and the others for all but the newest tile.
     for (int it = 0; it < n_tiles; ++it) {
-        __builtin_amdgcn_s_waitcnt(0x0F74);            // vmcnt <= 4: this wave's part of tile `it` has landed
+        if (it + 1 < n_tiles) __builtin_amdgcn_s_waitcnt(0x0F74);     // vmcnt <= 4: this wave's part of tile `it` has landed
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
         __builtin_amdgcn_s_barrier();                  // everyone's part landed; stage (it-1)%NS is free
         __builtin_amdgcn_sched_barrier(0);
-        if (((it + 2) & 63) == 0) {                    // every 64 tiles; waited for here, so that no wait
-            load_pages(it + 2);                        // is due where the entries are picked
-            __builtin_amdgcn_s_waitcnt(0x0F70);
+        if (it + 2 < n_tiles) {
+            if (((it + 2) & 63) == 0) {                // every 64 tiles; waited for here, so that no wait
+                load_pages(it + 2);                    // is due where the entries are picked
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+            }
+            issue(it + 2);
         }
-        issue(it + 2);
         if (!wave_active || it * 64 > wave_last) continue;     // nothing visible to this wave in the tile
         const uint8_t* st = smem + (it % NS) * STAGE;
         // The two halves of 32 tokens are software-pipelined so that the MFMA pipe and the vector ALU work at
@@ -428,7 +438,6 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
             o[u] = SS_MFMA_32x32x16(vd[u].v, pD.v, o[u], 0, 0, 0);
         }
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);                // drain the repeats issued past the end
     l += __shfl_xor(l, 32, 64);
     if (valid) {
         const float inv = 1.0f / l;
@@ -443,6 +452,7 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
                 *reinterpret_cast<vec8*>(op + u * 32 + 8 * j + 4 * g2) = w;
             }
     }
+    }   // items
 }
 
 hipError_t attn_generic(int dt, const void* qkv, void* out, int n_q, int n_kv, const BatchMeta& bm,
@@ -455,7 +465,7 @@ hipError_t attn_prefill(int dt, const void* qkv, void* out, int n_q, int n_kv, c
     if (kv.page_size != 16 || n_kv <= 0 || n_q % n_kv != 0 || kv.n_heads != n_kv) return hipErrorInvalidValue;
     if (bm.n_seqs > 65535 || n_q > 65535) return hipErrorInvalidValue;
     const float sl2 = 1.4426950408889634f / sqrtf((float)kv.d);
-    if (bm.max_q_len <= 64) {       // short prompts: per-wave operand loads, no ring to fill
+    if (bm.max_q_len <= 64 || !bm.pf_items || bm.pf_blocks <= 0) {       // short prompts (or no work lists): per-wave operand loads, no ring to fill
         dim3 grid((bm.max_q_len + 127) / 128, n_q, bm.n_seqs);
         attn_prefill_mfma_kernel<128, 1><<<grid, 256, 0, s>>>((const bf16_t*)qkv, (bf16_t*)out, n_q, n_kv, bm,
                                                                (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, sl2);
@@ -469,11 +479,7 @@ hipError_t attn_prefill(int dt, const void* qkv, void* out, int n_q, int n_kv, c
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int nqb = (bm.max_q_len + 255) / 256;
-    const long long units = (long long)n_kv * bm.n_seqs;            // (sequence, kv head)
-    const long long n_blocks = (units + 7) / 8 * 8 * (n_q / n_kv) * nqb;
-    if (n_blocks > 0x7fffffffll) return hipErrorInvalidValue;
-    attn_prefill_lds_kernel<128><<<(unsigned)n_blocks, 512, LDS, s>>>((const bf16_t*)qkv, (bf16_t*)out, n_q, n_kv, nqb, bm,
+    attn_prefill_lds_kernel<128><<<(unsigned)bm.pf_blocks, 512, LDS, s>>>((const bf16_t*)qkv, (bf16_t*)out, n_q, n_kv, bm,
                                                         (const bf16_t*)kv.k_pool, (const bf16_t*)kv.v_pool, sl2);
     return hipGetLastError();
 }

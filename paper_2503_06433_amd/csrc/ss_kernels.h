@@ -57,6 +57,14 @@ struct BatchMeta {
     const int32_t* unit_pos0;
     const int32_t* unit_cnt;
     int n_units;
+    // work lists of the LDS-staged prefill attention (null for decode batches): block b of pf_blocks walks the
+    // items pf_items[(b * pf_stride + j) * 8 .. +7] = (sequence, q head, first query of a block of 256, first batch
+    // token of the sequence, its new tokens, its cached tokens, 0, 0), j = 0, 1, ... up to a sequence of -1 (32-byte
+    // records, 32-byte aligned).  All items that read the pages of one (sequence, kv head) are in lists of blocks
+    // with the same b % 8; within a list the item with the most cached tokens to visit comes first.
+    const int32_t* pf_items;
+    int pf_stride;
+    int pf_blocks;
 };
 
 // One query token per sequence.  work items (seq, first page, n pages) split long

@@ -154,6 +154,7 @@ struct ss_ctx {
     int gemm_rounds_busy = 4;                    // GEMM launch granularity while mover jobs are pending
     int gemm_rounds = 0;                         // ... of the layer call in progress (0 = one launch)
     int copy_threads = 4;
+    int n_cus = 256;                             // compute units of the device (blocks of the persistent kernels)
     size_t copy_max_bytes = (size_t)8 << 20;      // adjacent runs of the direct tier path are merged up to this size
     bool trace_mover = false;
     std::string err;
@@ -471,6 +472,60 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
     }
     const size_t n_units = unit_seq.size();
     const size_t n_items = item_seq.size();
+    // Prefill attention work lists.  An item is (sequence, q head, block of 256 queries); its cost is the
+    // number of 64-token tiles it visits plus a fixed part.  The blocks of the kernel (one per compute unit)
+    // are dealt to the 8 XCDs round-robin by their index, so the items of one (sequence, kv head) -- which
+    // read the same K and V pages -- all go to blocks of one residue modulo 8 and find those pages in one
+    // L2; within a residue every item goes to the block with the least work so far, heaviest items first.
+    std::vector<int32_t> pf_items;
+    int pf_stride = 0, pf_blocks = 0;
+    if (!decode && max_q > 64) {
+        struct PfItem { int32_t sq, a, qb, cost; };
+        const int G = s->nq_l / s->nkv_l;
+        const int per_x = std::max(1, c->n_cus / 8);
+        std::vector<std::vector<PfItem>> by_x(8);
+        for (int i = 0; i < n; ++i) {
+            const int nqb_i = (b->q_lens[i] + 255) / 256;
+            for (int g = 0; g < s->nkv_l; ++g) {
+                const int x = (int)(((int64_t)i * s->nkv_l + g) % 8);
+                for (int jg = 0; jg < G; ++jg)
+                    for (int qb = 0; qb < nqb_i; ++qb) {
+                        const int last = b->kv_lens_before[i] + std::min(qb * 256 + 255, b->q_lens[i] - 1);
+                        by_x[x].push_back({i, g * G + jg, qb, last / 64 + 1 + 2});
+                    }
+            }
+        }
+        std::vector<std::vector<PfItem>> lists((size_t)8 * per_x);
+        for (int x = 0; x < 8; ++x) {
+            std::stable_sort(by_x[x].begin(), by_x[x].end(), [](const PfItem& p, const PfItem& q) { return p.cost > q.cost; });
+            std::priority_queue<std::pair<int64_t, int>, std::vector<std::pair<int64_t, int>>, std::greater<std::pair<int64_t, int>>> load;
+            for (int k = 0; k < per_x; ++k) load.push({0, k});
+            for (const PfItem& it : by_x[x]) {
+                auto top = load.top();
+                load.pop();
+                lists[(size_t)top.second * 8 + x].push_back(it);
+                load.push({top.first + it.cost, top.second});
+            }
+        }
+        pf_blocks = 8 * per_x;
+        size_t longest = 0;
+        for (const auto& l : lists) longest = std::max(longest, l.size());
+        pf_stride = (int)longest + 1;
+        // one 32-byte record per item, everything the block needs to start on it: sequence (-1 ends the
+        // list), q head, first query of the block, first token of the sequence in the batch, its number of
+        // new tokens, its number of cached tokens
+        pf_items.assign((size_t)pf_blocks * pf_stride * 8, -1);
+        int t0 = 0;
+        std::vector<int> q_begin(n);
+        for (int i = 0; i < n; ++i) { q_begin[i] = t0; t0 += b->q_lens[i]; }
+        for (int blk = 0; blk < pf_blocks; ++blk)
+            for (size_t j = 0; j < lists[blk].size(); ++j) {
+                int32_t* r = &pf_items[((size_t)blk * pf_stride + j) * 8];
+                const PfItem& it = lists[blk][j];
+                r[0] = it.sq; r[1] = it.a; r[2] = it.qb * 256; r[3] = q_begin[it.sq]; r[4] = b->q_lens[it.sq];
+                r[5] = b->kv_lens_before[it.sq]; r[6] = 0; r[7] = 0;
+            }
+    }
     // launch order: longest items first, so that the last waves of the grid are the short ones
     std::vector<int32_t> item_order(n_items);
     for (size_t i = 0; i < n_items; ++i) item_order[i] = (int32_t)i;
@@ -490,7 +545,8 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
     size_t off_utok = off_useq + al(4 * n_units);
     size_t off_upos = off_utok + al(4 * n_units);
     size_t off_ucnt = off_upos + al(4 * n_units);
-    size_t total = off_ucnt + al(4 * n_units);
+    size_t off_pf = off_ucnt + al(4 * n_units);
+    size_t total = off_pf + al(4 * pf_items.size());
     if (total > ms.cap) {
         if (ms.host) { HIP_TRY(c, hipHostFree(ms.host)); ms.host = nullptr; }
         if (ms.dev) { HIP_TRY(c, hipFree(ms.dev)); ms.dev = nullptr; }
@@ -528,6 +584,7 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
     memcpy(ms.host + off_utok, unit_tok0.data(), 4 * n_units);
     memcpy(ms.host + off_upos, unit_pos0.data(), 4 * n_units);
     memcpy(ms.host + off_ucnt, unit_cnt.data(), 4 * n_units);
+    if (!pf_items.empty()) memcpy(ms.host + off_pf, pf_items.data(), 4 * pf_items.size());
     HIP_TRY(c, hipMemcpyAsync(ms.dev, ms.host, total, hipMemcpyHostToDevice, stream));
     ms.bm.tok_seq = (const int32_t*)(ms.dev + off_tok_seq);
     ms.bm.tok_pos = (const int32_t*)(ms.dev + off_tok_pos);
@@ -543,6 +600,9 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
     ms.bm.unit_pos0 = (const int32_t*)(ms.dev + off_upos);
     ms.bm.unit_cnt = (const int32_t*)(ms.dev + off_ucnt);
     ms.bm.n_units = (int)n_units;
+    ms.bm.pf_items = pf_items.empty() ? nullptr : (const int32_t*)(ms.dev + off_pf);
+    ms.bm.pf_stride = pf_stride;
+    ms.bm.pf_blocks = pf_blocks;
     ms.wk.item_seq = (const int32_t*)(ms.dev + off_iseq);
     ms.wk.item_page0 = (const int32_t*)(ms.dev + off_ip0);
     ms.wk.item_npages = (const int32_t*)(ms.dev + off_inp);
@@ -1257,6 +1317,11 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
     if (const char* gr = getenv("SS_GEMM_ROUNDS")) c->gemm_rounds_busy = std::max(0, atoi(gr));
     if (const char* cm = getenv("SS_COPY_MAX_MB")) c->copy_max_bytes = (size_t)std::max(1, atoi(cm)) << 20;
     if (const char* ct = getenv("SS_COPY_THREADS")) c->copy_threads = std::max(1, std::min(16, atoi(ct)));
+    {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, rt->device) == hipSuccess && n >= 8) c->n_cus = n;
+        else (void)hipGetLastError();
+    }
     int rc = SS_OK;
     auto boot = [&]() -> int {
         // rotary table: cos/sin of p * base^(-2i/d), evaluated in double, stored as float pairs
