@@ -40,7 +40,7 @@ class Hardware:
 MI355X_PEAK = Hardware(hbm_bw=8e12, flops=2.5e15, link_bw=153e9 / 2, mem_bytes=288e9)
 # measured in this repository on the LLaMA-2-7B layer shapes (bench.py, configuration 2)
 MI355X_MEASURED = Hardware(hbm_bw=8e12, flops=2.5e15, link_bw=153e9 / 2, mem_bytes=288e9, eff_linear_prefill=0.52,
-                           eff_linear_decode=0.22, eff_attn_prefill=0.20, eff_attn_decode=0.72)
+                           eff_linear_decode=0.22, eff_attn_prefill=0.23, eff_attn_decode=0.72)
 
 LLAMA2_7B = Model(W=202.4e6, L=32, h_q=32, h_kv=32, d=128)
 LLAMA2_13B = Model(W=317.2e6, L=40, h_q=40, h_kv=40, d=128)
