@@ -956,7 +956,7 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
             // The device-to-host copies of a swap-out go to a stream of their own, ordered behind the gather
             // by an event: measured, the pipelined step (prefill + re-shard + decode) is 4 % shorter and its
             // time steadier than with the copies on the gather's stream.  The runtime executes them as copy
-            // kernels either way; what changes is presumably which streams share a hardware queue.
+            // kernels either way.
             hipStream_t out_stream = L.side;
             if (job.dir == SS_OUT && L.copy) {
                 HIP_TRY(c, hipEventRecord(L.copy_ev[0], L.side));
