@@ -353,3 +353,33 @@ def test_prefill_wide_score_range_matches_oracle(dtype):
     ref = lm.attn_block(cfg, v, xv, [(i, n, 0) for i, n in zip(ids, lens)], lm.KVCache(cfg), 0, round_kv=_round_kv(cfg))
     assert rel_err(to_f64(out, dtype), ref) <= tol(dtype)
     ctx.destroy()
+
+
+def test_prefill_prompt_longer_than_64_tiles_matches_oracle():
+    """A prompt of 4500 tokens is 71 tiles of 64 cached tokens for its last queries: the prefill attention keeps
+    the page-table entries of 64 tiles in a register and has to refill it once; a second, short prompt shares
+    the batch.  Then one decode step on the long sequence (several work items)."""
+    cfg = wl.ModelCfg(n_layers=1, dtype=wl.BF16, **SMALL["gqa4_d128"])
+    v, r = wl.make_layer_weights(cfg, 500)
+    lens = [4500, 90]
+    T = sum(lens)
+    xv, xr = wl.make_activations((T, cfg.hidden), 23, cfg.dtype)
+    ctx = make_context(cfg, pages=300, max_seq_len=4608)
+    d = pp_desc(cfg)
+    ctx.load_layer(d, 0, r)
+    ids = [3, 4]
+    out = empty_like_acts(T, cfg.hidden, cfg.dtype)
+    ctx.layer_prefill(d, 0, ss.SS_ATTN | ss.SS_NO_RESIDUAL, ids, lens, [0, 0], to_device(xr, cfg.dtype), out)
+    torch.cuda.synchronize()
+    cache = lm.KVCache(cfg)
+    ref = lm.attn_block(cfg, v, xv, [(i, n, 0) for i, n in zip(ids, lens)], cache, 0, round_kv=_round_kv(cfg))
+    got = to_f64(out, cfg.dtype)
+    assert rel_err(got[:lens[0]], ref[:lens[0]]) <= tol(cfg.dtype)
+    assert rel_err(got[lens[0]:], ref[lens[0]:]) <= tol(cfg.dtype)
+    dv, dr = wl.make_activations((2, cfg.hidden), 24, cfg.dtype)
+    out = empty_like_acts(2, cfg.hidden, cfg.dtype)
+    ctx.layer_decode(d, 0, ss.SS_ATTN | ss.SS_NO_RESIDUAL, ids, lens, to_device(dr, cfg.dtype), out)
+    torch.cuda.synchronize()
+    ref = lm.attn_block(cfg, v, dv, [(3, 1, 4500), (4, 1, 90)], cache, 0, round_kv=_round_kv(cfg))
+    assert rel_err(to_f64(out, cfg.dtype), ref) <= tol(cfg.dtype)
+    ctx.destroy()
