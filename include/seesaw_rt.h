@@ -134,9 +134,9 @@ int ss_weights_wait(ss_ctx*, const ss_shard_desc*);
 int64_t ss_weights_shard_bytes(ss_ctx*, const ss_shard_desc*);
 int ss_weights_read(ss_ctx*, const ss_shard_desc*, int layer, int which, void* host_out);
 
-/* ---- the layer (paper section 2.1: "several linear layers and an attention
- * layer"; prefill handles all prompt tokens at once, decode one token per
- * sequence against its KV cache) --------------------------------------------
+/* ---- the layer (paper section 2.1: linear layers around one attention layer;
+ * prefill handles all prompt tokens at once, decode one token per sequence
+ * against its KV cache) ------------------------------------------------------
  *
  * x_in [T, hidden] device, out [T, hidden] device; out must not alias x_in.
  * T = sum of q_lens (prefill) or n_seqs (decode, every q_len must be 1).

@@ -4,9 +4,10 @@ Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
 this package; the product path (the HIP library and its Python binding) never
 does, and shares no code with it.
 
-What is computed.  The paper describes a decoder layer only as "several linear
-layers and an attention layer" with grouped-query attention (paper section 2.1
-"Transformer Architecture", section 6.1 "Model") and gives no formulas; the
+What is computed.  The paper says of a decoder layer only that it is made of
+linear layers around one attention layer, with grouped-query attention in the
+models it runs (section 2.1 "Transformer Architecture", section 6.1 "Model"),
+and gives no formulas; the
 LLaMA-style definitions below (RMSNorm, rotary embedding in the half-split
 pairing, 1/sqrt(d) scaled causal softmax attention, SwiGLU, pre-norm residual
 layout, no biases) are the reading this build fixes.  What the paper does fix

@@ -337,6 +337,105 @@ def test_config1_pp_and_tp2_agree_end_to_end():
     assert c1.length(0) == 8 + 3 and t1.shape == (2, 4)
 
 
+# ---------------------------------------------------------------- whole model (embedding, LM head, greedy, generate)
+def test_embed_is_a_row_lookup_on_a_labelled_table():
+    # table entry (t, j) = 100 t + j: every output element names its token and its column
+    vocab, hidden = 7, 5
+    table = 100.0 * np.arange(vocab)[:, None] + np.arange(hidden)[None, :]
+    toks = np.array([3, 0, 6, 3])
+    out = lm.embed({"embed": table}, toks)
+    assert out.shape == (4, hidden)
+    for r, t in enumerate(toks):
+        for j in range(hidden):
+            assert out[r, j] == 100.0 * t + j
+
+
+def test_lm_logits_hand_values_and_torch_library_form():
+    # hand-worked: H = 2, vocab = 3, row (3, 4): mean square 12.5, eps 0 -> h = (3, 4) / sqrt(12.5) * gf
+    cfg = wl.ModelCfg(hidden=2, n_q_heads=1, n_kv_heads=1, head_dim=2, ffn=2, vocab=3, dtype=wl.F32, rms_eps=0.0)
+    head = {"gf": np.array([2.0, 0.5]), "wlm": np.array([[1.0, 0.0, 2.0], [0.0, 1.0, -1.0]])}
+    r = math.sqrt(12.5)
+    h0, h1 = 3.0 / r * 2.0, 4.0 / r * 0.5
+    got = lm.lm_logits(cfg, head, np.array([[3.0, 4.0]]))
+    assert got.shape == (1, 3)
+    assert np.allclose(got[0], [h0, h1, 2.0 * h0 - h1], atol=1e-15)
+    # library form on a non-square head [H, vocab] (a transposed operand cannot even multiply)
+    cfg = wl.ModelCfg(hidden=12, n_q_heads=1, n_kv_heads=1, head_dim=4, ffn=8, vocab=29, dtype=wl.F32)
+    rng = np.random.default_rng(70)
+    head = {"gf": 1.0 + 0.3 * rng.standard_normal(12), "wlm": rng.standard_normal((12, 29))}
+    x = rng.standard_normal((6, 12))
+    want = torch.nn.functional.linear(
+        torch.nn.functional.rms_norm(torch.tensor(x), (12,), torch.tensor(head["gf"]), cfg.rms_eps),
+        torch.tensor(head["wlm"]).T.contiguous())
+    assert np.allclose(lm.lm_logits(cfg, head, x), want.numpy(), atol=1e-12)
+
+
+def test_greedy_takes_the_lowest_index_among_equal_maxima():
+    logits = np.array([[0.5, 2.0, -1.0, 2.0, 2.0],      # three equal maxima -> the first of them
+                       [-3.0, -3.0, -7.0, -3.0, -9.0],  # negative values, tie at 0, 1, 3
+                       [1.0, 1.5, 1.25, 1.5, 9.0]])     # unique maximum at the end
+    assert lm.greedy(logits).tolist() == [1, 0, 4]
+
+
+def permutation_model(vocab, n_layers, seed):
+    """A model whose greedy continuation is known in closed form: the output projections Wo and Wd are zero,
+    so every layer is the identity on the residual stream (the attention and MLP blocks still run); the
+    embedding of token t is c_t * e_t (one scaled unit vector per token); the final gain is 1 and the LM head
+    sends unit vector t to unit vector pi(t).  RMSNorm keeps the direction of c_t * e_t, so the largest logit
+    after token t sits at pi(t): every emitted token is pi of the token before it."""
+    cfg = wl.ModelCfg(hidden=vocab, n_q_heads=2, n_kv_heads=1, head_dim=4, ffn=6, n_layers=n_layers, vocab=vocab,
+                      dtype=wl.F32)
+    ws = []
+    for l in range(n_layers):
+        w = dict(wl.make_layer_weights(cfg, seed + l, std=0.3)[0])
+        w["wo"] = np.zeros_like(w["wo"])
+        w["wd"] = np.zeros_like(w["wd"])
+        ws.append(w)
+    rng = np.random.default_rng(seed + 100)
+    pi = rng.permutation(vocab)
+    head = {"embed": np.diag(1.0 + rng.random(vocab)), "gf": np.ones(vocab), "wlm": np.zeros((vocab, vocab))}
+    head["wlm"][np.arange(vocab), pi] = 1.0
+    return cfg, ws, head, pi
+
+
+def test_generate_follows_the_permutation_closed_form_on_ragged_prompts():
+    cfg, ws, head, pi = permutation_model(vocab=11, n_layers=2, seed=71)
+    # unequal lengths, and every prompt ends in a token whose image differs from that of any other prompt row a
+    # wrong "last position" index could pick (row 0 of the batch, the first token of the next prompt, ...)
+    prompts = [np.array([4, 9, 1]), np.array([7]), np.array([2, 2, 5, 0, 8]), np.array([3, 6])]
+    steps = 6
+    toks, logits, cache = lm.generate(cfg, ws, head, prompts, steps)
+    assert toks.shape == (4, steps + 1) and len(logits) == steps + 1
+    for s, p in enumerate(prompts):
+        want, t = [], p[-1]
+        for _ in range(steps + 1):           # token 1 comes from the prefill (last prompt position), then `steps` more
+            t = pi[t]
+            want.append(t)
+        assert toks[s].tolist() == want
+        assert cache.length(s) == len(p) + steps     # the last emitted token is not fed back
+
+
+def test_generate_equals_recomputation_of_every_step_from_the_whole_prefix():
+    # Every step's logits must equal those of a fresh prefill over prompt + tokens emitted so far (run_layers on
+    # an empty cache, last row), which uses neither generate's bookkeeping of lengths nor its cache.
+    cfg = tiny_cfg()
+    ws = rand_weights(cfg, 72)
+    head = wl.make_head_weights(cfg, 73, std=0.3)[0]
+    rng = np.random.default_rng(74)
+    prompts = [rng.integers(0, cfg.vocab, size=n) for n in (5, 1, 9)]
+    steps = 4
+    toks, logits, cache = lm.generate(cfg, ws, head, prompts, steps)
+    for s, p in enumerate(prompts):
+        for j in range(steps + 1):
+            prefix = np.concatenate([p, toks[s, :j]])
+            run = lm.run_layers(cfg, ws, lm.embed(head, prefix), [(0, len(prefix), 0)], lm.KVCache(cfg), 0,
+                                    cfg.n_layers)
+            want = lm.lm_logits(cfg, head, run[-1:])[0]
+            assert np.allclose(logits[j][s], want, atol=1e-10), (s, j)
+            assert toks[s, j] == int(np.argmax(want))
+        assert cache.length(s) == len(p) + steps
+
+
 # ---------------------------------------------------------------- tier / paging
 def test_tier_index_is_c_order_of_layer_kv_head_pos_dim():
     L, n_kv, s, d = 3, 4, 5, 2
