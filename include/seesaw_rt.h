@@ -19,6 +19,16 @@
  *     asynchronous on it.  KV movement runs on the library's side stream, driven
  *     by a library-owned host thread, and is complete after ss_sync().
  *   - one context per GPU, calls on one context come from one thread at a time.
+ *   - ONE compute stream per context: the layer calls, ss_embed, ss_lm_head and
+ *     the device-side export / import of a context share its workspaces and
+ *     cached batch metadata, which are ordered by stream order alone.  Pass the
+ *     same stream to all of them (or synchronise the device between calls that
+ *     use different streams).  The `stream` arguments of ss_kv_swap,
+ *     ss_kv_reshard and ss_reshard_weights only name what the movement has to
+ *     come after; they may be any stream.
+ *   - ss_kv_swap(SS_IN) and ss_kv_import_dev are all or nothing: when the pages
+ *     of the listed sequences do not fit the pool together, SS_ENOMEM is
+ *     returned, no page is taken and no sequence becomes resident.
  */
 #ifndef SEESAW_RT_H
 #define SEESAW_RT_H

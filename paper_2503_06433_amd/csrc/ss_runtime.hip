@@ -323,14 +323,19 @@ int ensure_pools(ss_ctx* c, Shard* s) {
 }
 
 // Grow a sequence's page list to cover `length` tokens: lowest free id first.
+// A sequence the shard does not know yet is entered only once its pages are certain.
 int ensure_pages(ss_ctx* c, Shard* s, int64_t seq, int32_t length) {
-    SeqState& st = s->seqs[seq];
     const int ps = c->m.page_size;
     const size_t need = (size_t)((length + ps - 1) / ps);
-    if (need > st.pages.size()) {
-        if (need - st.pages.size() > s->free_pages.size())
+    {
+        auto it = s->seqs.find(seq);
+        const size_t have = it == s->seqs.end() ? 0 : it->second.pages.size();
+        if (need > have && need - have > s->free_pages.size())
             return fail(c, SS_ENOMEM, "page pool exhausted: sequence %lld needs %zu more pages, %zu free",
-                        (long long)seq, need - st.pages.size(), s->free_pages.size());
+                        (long long)seq, need - have, s->free_pages.size());
+    }
+    SeqState& st = s->seqs[seq];
+    if (need > st.pages.size()) {
         while (st.pages.size() < need) {
             st.pages.push_back(s->free_pages.top());
             s->free_pages.pop();
@@ -338,6 +343,18 @@ int ensure_pages(ss_ctx* c, Shard* s, int64_t seq, int32_t length) {
         s->version++;
     }
     if (length > st.len) st.len = length;
+    return SS_OK;
+}
+
+// All or nothing for calls that bring whole sequences on board (swap-in, device import): the pages of
+// every listed sequence must fit together, otherwise nothing is allocated and no sequence is entered.
+int check_new_seqs_fit(ss_ctx* c, Shard* s, const int32_t* lens, int n) {
+    const int ps = c->m.page_size;
+    size_t need = 0;
+    for (int i = 0; i < n; ++i) need += (size_t)((lens[i] + ps - 1) / ps);
+    if (need > s->free_pages.size())
+        return fail(c, SS_ENOMEM, "page pool exhausted: the %d sequences need %zu pages, %zu free", n, need,
+                    s->free_pages.size());
     return SS_OK;
 }
 
@@ -1731,6 +1748,15 @@ int ss_kv_swap(ss_ctx* c, const ss_shard_desc* d, int dir, const int64_t* seq_id
             if (s->seqs.count(seq_ids[i]))
                 return fail(c, SS_EINVAL, "sequence %lld already resident in this shard", (long long)seq_ids[i]);
         }
+        {
+            std::vector<int32_t> lens(n);
+            for (int i = 0; i < n; ++i) {
+                lens[i] = c->tier_slots[seq_ids[i]].len;
+                for (int j = 0; j < i; ++j)
+                    if (seq_ids[j] == seq_ids[i]) return fail(c, SS_EINVAL, "sequence %lld listed twice", (long long)seq_ids[i]);
+            }
+            if ((rc = check_new_seqs_fit(c, s, lens.data(), n))) return rc;
+        }
         for (int i = 0; i < n; ++i) {
             const TierSlot& ts = c->tier_slots[seq_ids[i]];
             if ((rc = ensure_pages(c, s, seq_ids[i], ts.len))) return rc;
@@ -1836,6 +1862,10 @@ static int xfer_dev(ss_ctx* c, const ss_shard_desc* d, const int64_t* seq_ids, c
             if (lens[i] <= 0) return fail(c, SS_EINVAL, "sequence %d has length %d", i, lens[i]);
             if (s->seqs.count(seq_ids[i])) return fail(c, SS_EINVAL, "sequence %lld already resident", (long long)seq_ids[i]);
         }
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < i; ++j)
+                if (seq_ids[j] == seq_ids[i]) return fail(c, SS_EINVAL, "sequence %lld listed twice", (long long)seq_ids[i]);
+        if ((rc = check_new_seqs_fit(c, s, lens, n))) return rc;
         for (int i = 0; i < n; ++i) {
             if ((rc = ensure_pages(c, s, seq_ids[i], lens[i]))) return rc;
             seqs.push_back({seq_ids[i], lens[i], s->seqs[seq_ids[i]].pages, 0});
@@ -1854,7 +1884,7 @@ static int xfer_dev(ss_ctx* c, const ss_shard_desc* d, const int64_t* seq_ids, c
     HIP_TRY(c, hipStreamSynchronize(st));
     std::vector<uint8_t> img(c->mv_meta_cap / 2);
     static_assert(sizeof(size_t) == 8, "64-bit only");
-    wait_idle(c);   // shares the mover's device metadata region (second half)
+    wait_idle(c);   // shares lane 0's device metadata region with the mover, which is idle from here on
     uint8_t* md = c->lane[0].mv_meta_dev;
     size_t stage_off = 0;
     for (size_t u0 = 0; u0 < units.size(); u0 += 32768) {

@@ -18,10 +18,16 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     import paper_2503_06433_amd as ss
-    from paper_2503_06433_amd.harness import (make_context, to_device, to_f64, to_raw, empty_like_acts, rel_err,
+    from paper_2503_06433_amd.harness import (make_context, to_device, to_f64, to_raw, empty_like_acts, rel_err, ROW_TOL_FULL,
                                               pp_desc, tp_desc)
+    from paper_2503_06433_amd.harness import parity as _parity
 
 TOL = 2e-2
+
+
+def parity(got, ref, dtype, label, spans=None):
+    """the harness check with the per-row bound of the full-size class"""
+    return _parity(got, ref, dtype, label, spans, ROW_TOL_FULL[dtype])
 
 
 def _round_kv(a):
@@ -77,10 +83,10 @@ def test_config2_prefill_full_batch_sampled_rows():
         o = lm.attn_block(cfg, vals, xv[a:b], [(i, lens[i], 0)], cache, 0, round_kv=_round_kv)
         x1 = xv[a:b] + o
         x2 = x1 + lm.mlp_block(cfg, vals, x1)
-        assert rel_err(got_o[a:b], o) <= TOL, "attention block, sequence %d (%d tokens)" % (i, lens[i])
-        assert rel_err(got[a:b], x2) <= TOL, "layer output, sequence %d" % i
+        parity(got_o[a:b], o, cfg.dtype, "C2 prefill attention block, sequence %d (%d tokens)" % (i, lens[i]))
+        parity(got[a:b], x2, cfg.dtype, "C2 prefill layer output, sequence %d (%d tokens)" % (i, lens[i]))
         kv = wl.storage_to_f64(ctx.kv_read(desc, i, 0, cfg.n_kv_heads), cfg.dtype)
-        assert rel_err(kv, cache.data[i][0]) <= TOL
+        parity(kv, cache.data[i][0], cfg.dtype, "C2 prefill cached K/V, sequence %d" % i)
     ctx.destroy()
 
 
@@ -116,17 +122,19 @@ def _run_decode_case(work, k, shard, w_seed, kv_seed, x_seed, n_extra):
         # the step appended the new token's K and V at position lens[i]
         kv = wl.storage_to_f64(ctx.kv_read(desc, ids[i], 0, nh), cfg.dtype)
         assert kv.shape[2] == lens[i] + 1
-        assert rel_err(kv[:, :, lens[i]], cache.data[i][0, :, g0:g1, lens[i]]) <= TOL
-    assert rel_err(got_o[picks], ref_o) <= TOL, "attention partial"
+        parity(kv[:, :, lens[i]], cache.data[i][0, :, g0:g1, lens[i]], cfg.dtype,
+               "%s decode, appended K/V of sequence %d" % (work.name, i))
+    each = [(j, j + 1) for j in range(len(picks))]
+    parity(got_o[picks], ref_o, cfg.dtype, "%s decode attention partial (%d sampled sequences)" % (work.name, len(picks)), each)
     ref_y = lm.mlp_block(cfg, vals, dv[picks], k, shard)
-    assert rel_err(got_y[picks], ref_y) <= TOL, "MLP partial"
+    parity(got_y[picks], ref_y, cfg.dtype, "%s decode MLP partial" % work.name, each)
     if k == 1:
         out = empty_like_acts(B, cfg.hidden, cfg.dtype)
         ctx.layer_decode(desc, 0, ss.SS_BOTH, ids, lens, dx, out)
         torch.cuda.synchronize()
         x1 = dv[picks] + ref_o
         x2 = x1 + lm.mlp_block(cfg, vals, x1)
-        assert rel_err(to_f64(out, cfg.dtype)[picks], x2) <= TOL
+        parity(to_f64(out, cfg.dtype)[picks], x2, cfg.dtype, "%s decode layer output" % work.name, each)
     ctx.destroy()
 
 
@@ -159,10 +167,10 @@ def test_config3_pp_prefill_full_layer_sampled_rows():
     got = to_f64(out, cfg.dtype)
     starts = np.concatenate([[0], np.cumsum(lens)])
     order = np.argsort(lens)
-    for i in (int(order[0]), int(order[len(order) // 2])):
+    for i in (int(order[0]), int(order[len(order) // 2]), int(order[-1])):      # shortest, median, longest prompt
         a, b = int(starts[i]), int(starts[i + 1])
         _, x2 = lm.layer_forward(cfg, vals, xv[a:b], [(i, lens[i], 0)], lm.KVCache(cfg), 0, round_kv=_round_kv)
-        assert rel_err(got[a:b], x2) <= TOL, "sequence %d (%d tokens)" % (i, lens[i])
+        parity(got[a:b], x2, cfg.dtype, "C3 prefill layer output, sequence %d (%d tokens)" % (i, lens[i]))
     ctx.destroy()
 
 
@@ -218,14 +226,35 @@ def test_config5_pp_slice_prefill_and_overlapped_reshard():
             cache = lm.KVCache(cfg)
             _, ref = lm.layer_forward(cfg, host_w[l], to_f64(xin[a:b], cfg.dtype), [(i, lens[i], 0)], cache, l,
                                       round_kv=_round_kv)
-            assert rel_err(to_f64(xout[a:b], cfg.dtype), ref) <= TOL, "layer %d sequence %d" % (l, i)
+            parity(to_f64(xout[a:b], cfg.dtype), ref, cfg.dtype,
+                   "C5 layer %d output, sequence %d (%d tokens)" % (l, i, lens[i]))
             kv = wl.storage_to_f64(ctx.kv_read(pp, i, l, n_kv), cfg.dtype)
-            assert rel_err(kv, cache.data[i][l]) <= TOL
+            parity(kv, cache.data[i][l], cfg.dtype, "C5 layer %d cached K/V, sequence %d" % (l, i))
+    w0 = host_w[0]
     del kept, host_w
     # ---- re-shard of batch 1 overlapped with the prefill of batch 2
     alone, _ = run_slice(x2, ids2, lens2, ())
     torch.cuda.synchronize()
     alone = alone.clone()
+    # ---- a long prompt at the 70B GQA shape (the next batch holds one of 3931 tokens; the first batch none above
+    # 2627): the attention block of layer 0 and the cache it writes.  The MLP of that many tokens at this width
+    # would take the CPU minutes; it is per token and is covered by the short sequences above.
+    order2 = np.argsort(lens2)
+    long_i = int(order2[-1])
+    assert lens2[long_i] >= 3000
+    starts2 = np.concatenate([[0], np.cumsum(lens2)])
+    part = torch.empty_like(x2)
+    ctx.layer_prefill(pp, 0, ss.SS_ATTN | ss.SS_NO_RESIDUAL, ids2, lens2, [0] * len(lens2), x2, part)
+    torch.cuda.synchronize()
+    a, b = int(starts2[long_i]), int(starts2[long_i + 1])
+    cache = lm.KVCache(cfg)
+    ref_o = lm.attn_block(cfg, w0, to_f64(x2[a:b], cfg.dtype), [(long_i, lens2[long_i], 0)], cache, 0,
+                          round_kv=_round_kv)
+    parity(to_f64(part[a:b], cfg.dtype), ref_o, cfg.dtype,
+           "C5 layer 0 attention block, long sequence (%d tokens)" % lens2[long_i])
+    kv = wl.storage_to_f64(ctx.kv_read(pp, ids2[long_i], 0, n_kv), cfg.dtype)
+    parity(kv, cache.data[long_i][0], cfg.dtype, "C5 layer 0 cached K/V, long sequence")
+    del part, w0, ref_o, kv, cache
     ctx.kv_free(pp, ids2)
     snap = {i: [ctx.kv_read(pp, i, l, n_kv) for l in (0, L - 1)] for i in (int(order[0]), int(order[-1]))}
     ctx.kv_reshard(pp, tp, ids)

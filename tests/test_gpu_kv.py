@@ -83,12 +83,78 @@ def test_page_policy_matches_oracle_through_growth_and_free():
     for sid in (1, 3, 4):
         assert list(ctx.kv_page_table(desc, sid)) == alloc.tables[sid]
     assert ctx.kv_free_pages(desc) == len(alloc.free)
+    free_before = ctx.kv_free_pages(desc)
     with pytest.raises(ss.SeesawError) as e:
         _import(ctx, desc, cfg, [5], [mk(16 * 6, 5)])
     assert e.value.code == ss.SS_ENOMEM
+    # a refused import leaves nothing behind: no pages taken, the sequence unknown, the others untouched
+    assert ctx.kv_free_pages(desc) == free_before
+    with pytest.raises(ss.SeesawError) as e:
+        ctx.kv_seq_len(desc, 5)
+    assert e.value.code == ss.SS_ENOENT
+    # ... also when an earlier sequence of the same call would have fitted alone
+    with pytest.raises(ss.SeesawError) as e:
+        _import(ctx, desc, cfg, [6, 5], [mk(16, 6), mk(16 * 6, 5)])
+    assert e.value.code == ss.SS_ENOMEM
+    assert ctx.kv_free_pages(desc) == free_before
+    for sid in (5, 6):
+        with pytest.raises(ss.SeesawError) as e:
+            ctx.kv_seq_len(desc, sid)
+        assert e.value.code == ss.SS_ENOENT
+    # once pages are free again the same call goes through, with the pages the policy gives
+    ctx.kv_free(desc, [4])
+    alloc.release(4)
+    c6, c5 = mk(16, 6), mk(16 * 6, 5)
+    _import(ctx, desc, cfg, [6, 5], [c6, c5])
+    alloc.ensure(6, 16)
+    alloc.ensure(5, 96)
+    for sid, cont in ((6, c6), (5, c5)):
+        assert list(ctx.kv_page_table(desc, sid)) == alloc.tables[sid]
+        assert np.array_equal(ctx.kv_read(desc, sid, 0, cfg.n_kv_heads), cont[0])
     with pytest.raises(ss.SeesawError) as e:
         ctx.kv_free(desc, [99])
     assert e.value.code == ss.SS_ENOENT
+    ctx.destroy()
+
+
+def test_swap_in_that_does_not_fit_is_all_or_nothing():
+    """A swap-in whose sequences do not all fit the shard's pool is refused as a whole: no pages are taken, no
+    sequence becomes resident, and the same call succeeds once pages have been freed."""
+    cfg = _cfg(wl.BF16, n_layers=2)
+    L, n_kv, d = 2, cfg.n_kv_heads, 128
+    lens = {1: 40, 2: 100, 3: 30}                       # 3 + 7 + 2 pages
+    complete = {s: _rand_bits((L, 2, n_kv, n, d), 50 + s, wl.BF16) for s, n in lens.items()}
+    ctx = make_context(cfg, pages=14, tier_bytes=8 << 20, pinned_bytes=4 << 20)
+    src, dst = pp_desc(cfg), tp_desc(cfg, 2, 1)
+    ids = list(lens)
+    _import(ctx, src, cfg, ids, [complete[s] for s in ids])
+    ctx.kv_swap(src, ss.SS_OUT, ids)
+    ctx.sync()
+    blocker = _rand_bits((L, 2, n_kv // 2, 16 * 4, d), 60, wl.BF16)     # 4 of the 14 pages of the target pool
+    _import(ctx, dst, cfg, [900], [blocker])
+    assert ctx.kv_free_pages(dst) == 10
+    with pytest.raises(ss.SeesawError) as e:
+        ctx.kv_swap(dst, ss.SS_IN, ids)                 # needs 12
+    assert e.value.code == ss.SS_ENOMEM
+    ctx.sync()
+    assert ctx.kv_free_pages(dst) == 10
+    for s in ids:
+        with pytest.raises(ss.SeesawError) as e:
+            ctx.kv_seq_len(dst, s)
+        assert e.value.code == ss.SS_ENOENT
+    with pytest.raises(ss.SeesawError) as e:
+        ctx.kv_swap(dst, ss.SS_IN, [1, 1])              # listed twice
+    assert e.value.code == ss.SS_EINVAL
+    ctx.kv_free(dst, [900])
+    ctx.kv_swap(dst, ss.SS_IN, ids)
+    ctx.sync()
+    alloc = kt.PageAllocator(14)
+    for s in ids:
+        alloc.ensure(s, lens[s])
+    for s in ids:
+        assert list(ctx.kv_page_table(dst, s)) == alloc.tables[s]
+        for l in range(L):
+            assert np.array_equal(ctx.kv_read(dst, s, l, n_kv // 2), complete[s][l][:, n_kv // 2:])
     ctx.destroy()
 
 
