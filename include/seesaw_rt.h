@@ -230,6 +230,19 @@ int ss_embed(ss_ctx*, const int32_t* token_ids_host, int n, void* x_out, void* s
 /* logits [n, vocab] float32 device = RMSNorm(x; gf) * wlm */
 int ss_lm_head(ss_ctx*, const void* x, int n, float* logits, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid it): ss_lm_head with its scratch --
+ * the normed rows and the split-K partial sums of the GEMM -- in a fixed 32 MiB
+ * device array that every GPU the library runs on holds until the process ends,
+ * instead of workspaces that grow on demand.  Same arguments and result as
+ * ss_lm_head; calls no hipMalloc / hipFree and no allocating library routine.
+ * Limit: n * hidden * (bytes per element) <= 8 MiB (e.g. 512 rows of hidden 8192
+ * in a 16-bit type); above it SS_EINVAL with the sizes in ss_last_error, and
+ * nothing is launched.  All calls on one GPU (from any context) share that GPU's
+ * array: calls that overlap in time on one GPU race; issue them on one stream or
+ * order them with events. */
+int ss_lm_head_noalloc(ss_ctx*, const void* x, int n, float* logits, void* stream);
+
 /* The shapes the context was created with. */
 int ss_get_config(ss_ctx*, ss_model_cfg* model_out, ss_runtime_cfg* rt_out);
 

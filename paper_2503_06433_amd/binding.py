@@ -111,6 +111,7 @@ def load_library():
         "ss_load_head": (I, [V, V, V, V]),
         "ss_embed": (I, [V, P(C.c_int32), I, V, V]),
         "ss_lm_head": (I, [V, V, I, V, V]),
+        "ss_lm_head_noalloc": (I, [V, V, I, V, V]),
         "ss_get_config": (I, [V, P(ModelCfg), P(RuntimeCfg)]),
         "ss_offline_run": (I, [V, P(OfflineCfg), C.c_int32, P(C.c_int32), P(C.c_int32), P(C.c_int32), P(C.c_int32),
                                P(C.c_int32), L, P(L), P(OfflineStats), V]),
@@ -130,7 +131,7 @@ EXPORTED = ("ss_create ss_destroy ss_last_error ss_load_layer ss_host_weights_pu
             "ss_weights_shard_bytes ss_weights_read ss_layer_prefill ss_layer_decode ss_kv_swap "
             "ss_kv_reshard ss_sync ss_kv_jobs_issued ss_kv_wait ss_kv_free ss_host_tier_release ss_kv_export_dev ss_kv_import_dev "
             "ss_kv_page_table ss_kv_seq_len ss_kv_read ss_host_tier_read ss_host_tier_used_bytes "
-            "ss_kv_free_pages ss_load_head ss_embed ss_lm_head ss_get_config ss_offline_run ss_prof_enable ss_prof_read ss_prof_reset").split()
+            "ss_kv_free_pages ss_load_head ss_embed ss_lm_head ss_lm_head_noalloc ss_get_config ss_offline_run ss_prof_enable ss_prof_read ss_prof_reset").split()
 
 
 W_NAMES = ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")     # index = SS_W_* of the header
@@ -334,6 +335,9 @@ class Context:
 
     def lm_head(self, x, n, logits, stream=0):
         self._ck(self.lib.ss_lm_head(self.h, _ptr(x), n, _ptr(logits), stream))
+
+    def lm_head_noalloc(self, x, n, logits, stream=0):
+        self._ck(self.lib.ss_lm_head_noalloc(self.h, _ptr(x), n, _ptr(logits), stream))
 
     # ---- timing hooks
     def prof_enable(self, on):

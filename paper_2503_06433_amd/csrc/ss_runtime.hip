@@ -145,6 +145,17 @@ struct ProfRec {
     hipEvent_t a, b;
 };
 
+// Fixed scratch of the entry point that allocates nothing (ss_lm_head_noalloc): the normed rows and the
+// split-K partial sums of its GEMM.  One copy per GPU the library runs on, held until the process ends.  In
+// host code the array's name is only a handle for hipGetSymbolAddress: the device address of each GPU's copy
+// is looked up once per device (ss_create) and kept in g_noalloc_scratch; kernels and copies get that pointer.
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)32 << 20;
+constexpr size_t NOALLOC_ROWS_BYTES = (size_t)8 << 20;        // first part: normed rows; the rest: partial sums
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+void* g_noalloc_scratch[NOALLOC_MAX_DEVICES] = {};
+std::mutex g_noalloc_mu;
+
 }  // namespace
 
 struct ss_ctx {
@@ -1348,6 +1359,19 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
         rt->pinned_bytes < 0)
         return SS_EINVAL;
     if (hipSetDevice(rt->device) != hipSuccess) return SS_EHIP;
+    if (rt->device < 0 || rt->device >= NOALLOC_MAX_DEVICES) return SS_EINVAL;
+    {   // this device's copy of the fixed scratch array: address looked up once, with the device current
+        std::lock_guard<std::mutex> lk(g_noalloc_mu);
+        if (!g_noalloc_scratch[rt->device]) {
+            void* p = nullptr;
+            const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p) {
+                fprintf(stderr, "ss_create: hipGetSymbolAddress(scratch): %s\n", hipGetErrorString(e));
+                return SS_EHIP;
+            }
+            g_noalloc_scratch[rt->device] = p;
+        }
+    }
     ss_ctx* c = new ss_ctx();
     c->m = m;
     c->rt = *rt;
@@ -2027,6 +2051,27 @@ int ss_lm_head(ss_ctx* c, const void* x, int n, float* logits, void* stream) {
     K_TRY(c, SSK_CALL(c, rmsnorm, x, c->d_gf, c->ws_h.p, n, c->m.hidden, c->m.rms_eps, st));
     K_TRY(c, SSK_CALL(c, gemm_nt, c->ws_h.p, c->m.hidden, c->d_wlm_t, logits, c->m.vocab, nullptr, n, c->m.vocab,
                           c->m.hidden, ssk::EPI_STORE_F32, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap));
+    return SS_OK;
+}
+
+int ss_lm_head_noalloc(ss_ctx* c, const void* x, int n, float* logits, void* stream) {
+    if (!c || !x || !logits || n <= 0) return SS_EINVAL;
+    if (!c->d_wlm_t) return fail(c, SS_EINVAL, "head weights not loaded");
+    uint8_t* base = (uint8_t*)g_noalloc_scratch[c->rt.device];
+    if (!base) return fail(c, SS_EHIP, "no fixed scratch on device %d", c->rt.device);
+    const size_t rows_bytes = (size_t)n * c->m.hidden * c->es;
+    if (rows_bytes > NOALLOC_ROWS_BYTES)
+        return fail(c, SS_EINVAL, "ss_lm_head_noalloc: %d rows of %d elements need %zu bytes of scratch, the fixed limit is %zu",
+                    n, c->m.hidden, rows_bytes, NOALLOC_ROWS_BYTES);
+    hipStream_t st = (hipStream_t)stream;
+    void* rows = base;
+    float* partials = (float*)(base + NOALLOC_ROWS_BYTES);
+    const size_t partial_bytes = NOALLOC_SCRATCH_BYTES - NOALLOC_ROWS_BYTES;
+    // nothing in the scratch has to start at zero: the norm writes every row before the GEMM reads it, and the
+    // GEMM writes every partial sum it later adds up
+    K_TRY(c, SSK_CALL(c, rmsnorm, x, c->d_gf, rows, n, c->m.hidden, c->m.rms_eps, st));
+    K_TRY(c, SSK_CALL(c, gemm_nt, rows, c->m.hidden, c->d_wlm_t, logits, c->m.vocab, nullptr, n, c->m.vocab,
+                          c->m.hidden, ssk::EPI_STORE_F32, c->force_generic, st, partials, partial_bytes));
     return SS_OK;
 }
 
