@@ -162,6 +162,74 @@ def test_chunked_prefill_and_long_decode_split():
     ctx.destroy()
 
 
+@pytest.mark.parametrize("name,dtype", [("gqa4_d128", wl.BF16), ("mha_d128", wl.F16), ("mha_d64_generic", wl.F32)])
+def test_mixed_batch_of_prompt_chunks_and_decode_tokens(name, dtype):
+    """One layer call over a batch that mixes whole prompts, chunks of prompts and single decode tokens (the batches
+    a chunked-prefill engine forms, paper section 6.1 "Baselines" and section 7.1): a decode token is a sequence
+    with one new token behind its cached ones, so `ss_layer_prefill` takes the mix as it is.  Compared with the
+    oracle on the same batches, and with the same work issued as separate prefill and decode calls."""
+    cfg = wl.ModelCfg(n_layers=1, dtype=dtype, **SMALL[name])
+    vals, raws = _weights(cfg, 400)
+    d = pp_desc(cfg)
+    ctx = make_context(cfg, pages=160)
+    twin = make_context(cfg, pages=160)                  # the same work as separate calls
+    for c in (ctx, twin):
+        _load(c, d, cfg, raws)
+    cache = lm.KVCache(cfg)
+    rk = _round_kv(cfg)
+
+    def run(c, fn_name, batch, xr):
+        ids = [b[0] for b in batch]
+        T = sum(b[1] for b in batch)
+        out = empty_like_acts(T, cfg.hidden, dtype)
+        x = to_device(xr, dtype)
+        if fn_name == "prefill":
+            c.layer_prefill(d, 0, ss.SS_BOTH, ids, [b[1] for b in batch], [b[2] for b in batch], x, out)
+        else:
+            c.layer_decode(d, 0, ss.SS_BOTH, ids, [b[2] for b in batch], x, out)
+        torch.cuda.synchronize()
+        return to_f64(out, dtype)
+
+    def spans_of(batch):
+        st = np.concatenate([[0], np.cumsum([b[1] for b in batch])])
+        return [(int(st[i]), int(st[i + 1])) for i in range(len(batch))]
+
+    # two sequences are on board already (100 and 300 tokens)
+    warm = [(1, 100, 0), (2, 300, 0)]
+    xv, xr = wl.make_activations((400, cfg.hidden), 31, dtype)
+    for c in (ctx, twin):
+        run(c, "prefill", warm, xr)
+    lm.layer_forward(cfg, vals[0], xv, warm, cache, 0, round_kv=rk)
+    # mixed call 1: decode token of 1, a whole new prompt 3 (200), decode token of 2, first chunk (64 of 150) of prompt 4
+    # mixed call 2: the rest of prompt 4 behind its first chunk, the next decode token of 1, a one-token prompt 5
+    calls = [[(1, 1, 100), (3, 200, 0), (2, 1, 300), (4, 64, 0)],
+             [(4, 86, 64), (1, 1, 101), (5, 1, 0)]]
+    for n_call, batch in enumerate(calls):
+        T = sum(b[1] for b in batch)
+        xv, xr = wl.make_activations((T, cfg.hidden), 32 + n_call, dtype)
+        got = run(ctx, "prefill", batch, xr)
+        _, ref = lm.layer_forward(cfg, vals[0], xv, batch, cache, 0, round_kv=rk)
+        sp = spans_of(batch)
+        parity(got, ref, dtype, "mixed batch %d (%s) against the oracle" % (n_call, name), sp)
+        # the same rows from separate calls: the prompt parts in one prefill call, the decode tokens in one decode call
+        pre = [i for i, b in enumerate(batch) if not (b[1] == 1 and b[2] > 0)]
+        dec = [i for i, b in enumerate(batch) if b[1] == 1 and b[2] > 0]
+        rows = lambda idx: np.concatenate([np.arange(sp[i][0], sp[i][1]) for i in idx])
+        sep = np.zeros_like(got)
+        sep[rows(pre)] = run(twin, "prefill", [batch[i] for i in pre], xr[rows(pre)])
+        sep[rows(dec)] = run(twin, "decode", [batch[i] for i in dec], xr[rows(dec)])
+        parity(got, sep, dtype, "mixed batch %d (%s) against separate calls" % (n_call, name), sp)
+    # the caches the two ways leave behind hold the same tokens
+    for sid, n in ((1, 102), (2, 301), (3, 200), (4, 150), (5, 1)):
+        a = wl.storage_to_f64(ctx.kv_read(d, sid, 0, cfg.n_kv_heads), dtype)
+        assert a.shape[2] == n
+        parity(a, cache.data[sid][0], dtype, "mixed batches (%s), cached K/V of sequence %d" % (name, sid))
+        b = wl.storage_to_f64(twin.kv_read(d, sid, 0, cfg.n_kv_heads), dtype)     # (split-K choices differ with the batch size)
+        parity(a, b, dtype, "mixed batches (%s), cache of sequence %d against separate calls" % (name, sid))
+    ctx.destroy()
+    twin.destroy()
+
+
 def test_generic_kernels_forced_for_bf16():
     os.environ["SS_FORCE_GENERIC"] = "1"
     try:

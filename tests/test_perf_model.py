@@ -66,3 +66,39 @@ def test_the_two_observations_on_pcie_class_hardware():
 def test_report_runs():
     text = pm.report()
     assert "LLaMA-3-70B" in text and "measured kernel rates" in text
+
+
+def test_efficiencies_follow_a_bench_record(tmp_path):
+    rec = {"rooflines": {"c5.prefill_gemms": {"frac": 0.45}, "c5.prefill_attention": {"frac": 0.25},
+                         "c4.decode_gemms": {"frac": 0.08}, "c4.decode_attention": {"frac": 0.58},
+                         "c2.decode_gemms": {"frac": 0.2}}}
+    hw = pm.hardware_from_bench(rec, "LLaMA-3-70B")
+    assert (hw.eff_linear_prefill, hw.eff_attn_prefill, hw.eff_linear_decode, hw.eff_attn_decode) == (0.45, 0.25, 0.08, 0.58)
+    assert hw.hbm_bw == pm.MI355X_PEAK.hbm_bw
+    hw7 = pm.hardware_from_bench(rec, "LLaMA-2-7B")            # classes the record lacks keep the fallback
+    assert hw7.eff_linear_decode == 0.2 and hw7.eff_linear_prefill == pm.MI355X_MEASURED.eff_linear_prefill
+    import json
+    path = tmp_path / "BENCH.json"
+    path.write_text(json.dumps({"parsed": rec}))               # the driver's record form
+    assert pm.hardware_from_bench(str(path), "LLaMA-3-70B").eff_attn_decode == 0.58
+    # a slower decode GEMM makes the modelled decode step slower, nothing else
+    slow = pm.hardware_from_bench({"rooflines": {"c4.decode_gemms": {"frac": 0.04}}}, "LLaMA-3-70B")
+    a = pm.components(pm.LLAMA3_70B, hw, "decode", 64, 2000)["dm_lin"]
+    b = pm.components(pm.LLAMA3_70B, slow, "decode", 64, 2000)["dm_lin"]
+    assert b == pytest.approx(2 * a)
+
+
+def test_link_sweep_resharding_never_loses_and_pays_on_slow_links():
+    # A10-class hardware (the paper's testbed class): re-sharding can always keep one strategy, so it never loses
+    # by more than its (upper-bound) movement charge, and with PCIe-class links it wins (sections 6.2, 6.5)
+    a10 = pm.Hardware(hbm_bw=600e9, flops=125e12, link_bw=8e9, mem_bytes=24e9)
+    rows = pm.link_sweep(pm.LLAMA2_13B, a10, 4, s_in=1000, s_out=200, host_bw=8e9)
+    gains = [r[6] for r in rows]
+    assert all(g >= 0.999 for g in gains)
+    switched = [r for r in rows if r[3] != r[4]]
+    assert switched and all(r[3] < r[4] and r[6] > 1.03 for r in switched)   # pipeline-heavier prefill, tensor-heavier decode
+    assert rows[0][3] == rows[0][4] == 1                       # links ten times slower: pipeline parallelism throughout
+    assert rows[-1][3] == rows[-1][4] == 4                     # links fifty times faster: tensor parallelism throughout
+    # request_time is the sum of its parts: no outputs -> the prefill term alone
+    t = pm.request_time(pm.LLAMA2_13B, a10, 4, 1000, 0, 1, 1)
+    assert t == pytest.approx(pm.inv_throughput(pm.LLAMA2_13B, a10, "prefill", 16, 1000, tp=1, pp=4))
