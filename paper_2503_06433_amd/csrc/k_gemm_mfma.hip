@@ -312,32 +312,35 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
     const uint32_t lds_base = (uint32_t)(uintptr_t)smem;
 
     // ---- loads: waves 0-1 bring A rows [128w, 128w+128), waves 2-3 bring Wt rows [128(w-2), ...);
-    // one load = 8 rows.  roff[i] = byte offset of this lane's 16 bytes inside slice 0 of the tile whose
-    // slices are being requested (rows beyond the matrix are clamped: their products are never stored)
+    // one load = 8 rows.  tbase = first row of the tile whose slices are being requested (a 64-bit scalar
+    // address, so operands of any size are addressed), roff[i] = byte offset of this lane's 16 bytes inside
+    // slice 0 of that tile (rows beyond the matrix are clamped: their products are never stored)
     const bool isA = wave < 2;
     const int row_base = (wave & 1) * 128;
     const uint8_t* gbase = reinterpret_cast<const uint8_t*>(isA ? A : Wt);
     const int ld = isA ? lda : K;
     const int row_lim = isA ? M : N;
     uint32_t roff[LPS];
+    const uint8_t* tbase = gbase;
     auto set_roff = [&](int it) {
         int m0, n0;
         tile_origin(it < nt_local ? it : nt_local - 1, m0, n0);
         const int row0 = isA ? m0 : n0;
+        tbase = gbase + (size_t)row0 * (size_t)ld * 2;
 #pragma unroll
         for (int i = 0; i < LPS; ++i) {
             const int row = row_base + i * 8 + (lane >> 3);
             const int kc = (lane & 7) ^ ((row >> 1) & 7);
             int gr = row0 + row;
             gr = gr < row_lim ? gr : row_lim - 1;
-            roff[i] = (uint32_t)gr * (uint32_t)ld * 2u + (uint32_t)kc * 16u;
+            roff[i] = (uint32_t)(gr - row0) * (uint32_t)ld * 2u + (uint32_t)kc * 16u;
         }
     };
     const uint32_t dst0 = lds_base + (isA ? 0 : BM * 128) + row_base * 128;
     const int nsl = K / 64;
     const int g_last = nt_local * nsl - 1;       // last slice of this block's stream
     auto issue1 = [&](int stage, int ksl, int i) {
-        const uint8_t* sb = gbase + (size_t)ksl * 128;
+        const uint8_t* sb = tbase + (size_t)ksl * 128;
         const uint32_t d = dst0 + (uint32_t)stage * STAGE + i * 1024;
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(roff[i]), "s"(sb), "s"(d) : "memory");
     };
@@ -533,8 +536,9 @@ constexpr size_t STREAM_LDS = (size_t)2 * 512 * 128 + 4 * 8192;     // ring + st
 bool gemm_mfma_stream_supported(const void* C, const void* R, int ldc, int M, int N, int K, int lda, int epi) {
     if (K % 64 != 0 || K < 128 || N % 16 != 0 || ldc % 8 != 0) return false;
     if (((uintptr_t)C & 15) != 0 || (epi == EPI_RESIDUAL && ((uintptr_t)R & 15) != 0)) return false;
-    // 32-bit byte offsets inside the operands
-    if ((long long)M * lda * 2 >= (1ll << 32) || (long long)N * K * 2 >= (1ll << 32)) return false;
+    // 32-bit byte offsets inside one 256-row tile of an operand
+    if ((long long)256 * lda * 2 >= (1ll << 32) || (long long)256 * K * 2 >= (1ll << 32)) return false;
+    (void)M;
     return true;
 }
 

@@ -1,0 +1,224 @@
+"""Condenses rocprofv3 output of `bench.py` runs into the short tables under profiles/ and into
+bench_traffic.json (the `traffic` fields of the bench line).  Reads the CSV files rocprofv3 writes, nothing else;
+no GPU is needed.
+
+The runs it expects (from the repository root on the MI355X machine, after `cd /tmp && export TMPDIR=/tmp`; N = 2..5,
+`--only` keeps the other configurations' kernels out of the run):
+
+    rocprofv3 --kernel-trace --stats -d OUT/trace_cN -o t --output-format csv -- python3 bench.py --config N --only --no-cpu-baseline
+    rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 SQ_LDS_BANK_CONFLICT SQ_ACTIVE_INST_LDS \\
+              SQ_WAVE_CYCLES SQ_WAIT_INST_ANY SQ_WAIT_INST_LDS -d OUT/sq_cN -o t --output-format csv -- python3 bench.py --config N --only --no-cpu-baseline --steps 2 --warmup 1 --class-reps 2
+    rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum GRBM_GUI_ACTIVE -d OUT/tcc_cN -o t --output-format csv -- python3 bench.py ... (same flags)
+    rocprofv3 --pmc FETCH_SIZE -d OUT/fetch_cN -o t --output-format csv -- python3 bench.py ... (same flags) --calibrate-copy
+    rocprofv3 --pmc WRITE_SIZE -d OUT/write_cN -o t --output-format csv -- python3 bench.py ... (same flags) --calibrate-copy
+
+and then
+
+    python -m paper_2503_06433_amd.profile_summary --config N --dir OUT --profiles profiles --traffic bench_traffic.json
+
+`--calibrate-copy` makes bench.py run a plain 1 GiB device-to-device copy first; FETCH_SIZE and WRITE_SIZE (KiB per
+dispatch) are scaled by what they read for that copy of known size.
+"""
+import argparse
+import collections
+import csv
+import glob
+import json
+import os
+import re
+import statistics
+
+WORKLOAD = {2: "c2_llama2_7b_layer", 3: "c3_llama2_13b_tp4", 4: "c4_llama3_70b_tp8", 5: "c5_llama3_70b_pp8_slice"}
+
+# kernel class of the bench line <- substring of the kernel name
+CLASSES = (
+    ("prefill_gemms", ("gemm_mfma_stream_kernel",)),
+    ("prefill_attention", ("attn_prefill_lds_kernel", "attn_prefill_mfma_kernel")),
+    ("decode_attention", ("attn_decode_mfma_kernel", "attn_decode_merge_kernel")),
+    ("decode_gemms", ("gemm_mfma_kernel<", "splitk_reduce_kernel")),
+    ("kv_repack", ("kv_repack_kernel",)),
+)
+
+
+def short(name):
+    name = re.sub(r"^void ", "", name)
+    name = re.sub(r"^ssk(16)?::", "", name)
+    name = re.sub(r"\(.*$", "", name)
+    return name[:64]
+
+
+def find(directory, suffix):
+    hits = sorted(glob.glob(os.path.join(directory, "**", "*" + suffix), recursive=True))
+    return hits[0] if hits else None
+
+
+def read_counters(directory):
+    """{kernel: {counter: [value per dispatch]}} of one --pmc run."""
+    path = find(directory, "counter_collection.csv")
+    per = collections.defaultdict(lambda: collections.defaultdict(list))
+    if not path:
+        return per
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            per[short(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    return per
+
+
+def avg(v):
+    return sum(v) / len(v) if v else 0.0
+
+
+def kernel_trace_tables(directory):
+    stats, trace = find(directory, "kernel_stats.csv"), find(directory, "kernel_trace.csv")
+    lines, durations = [], collections.defaultdict(list)
+    if stats:
+        lines += ["| kernel | calls | avg us | total ms | % |", "|---|---|---|---|---|"]
+        with open(stats) as f:
+            for r in list(csv.DictReader(f))[:18]:
+                lines.append("| `%s` | %s | %.1f | %.2f | %s |" % (short(r["Name"]), r["Calls"], float(r["AverageNs"]) / 1e3,
+                                                                 float(r["TotalDurationNs"]) / 1e6, r["Percentage"]))
+    if trace:
+        shapes = collections.defaultdict(list)
+        with open(trace) as f:
+            for r in csv.DictReader(f):
+                us = (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3
+                shapes[(short(r["Kernel_Name"]), r["Grid_Size_X"], r["Grid_Size_Y"])].append(us)
+                durations[short(r["Kernel_Name"])].append(us)
+        lines += ["", "Per launch shape (grid in threads; launches of 15 us and more, at least 3 of them):", "",
+                  "| kernel | grid | launches | min us | median us |", "|---|---|---|---|---|"]
+        for (k, gx, gy), v in sorted(shapes.items(), key=lambda kv: -sum(kv[1])):
+            if len(v) >= 3 and statistics.median(v) >= 15:
+                lines.append("| `%s` | %s x %s | %d | %.1f | %.1f |" % (k, gx, gy, len(v), min(v), statistics.median(v)))
+    return lines, durations
+
+
+def counter_table(sq, tcc, durations):
+    lines = ["| kernel | launches | GPU cycles | clock GHz | MFMA busy | MFMA ops (bf16) | LDS conflict cycles / active LDS cycle | "
+             "waiting / wave cycles | L2 hit rate |", "|---|---|---|---|---|---|---|---|---|"]
+    rows = []
+    for k in sorted(set(sq) | set(tcc)):
+        gui = avg(tcc[k]["GRBM_GUI_ACTIVE"]) / 8 if k in tcc else 0.0            # summed over the 8 XCDs
+        if gui < 20000:
+            continue
+        mf = avg(sq[k]["SQ_VALU_MFMA_BUSY_CYCLES"]) / 1024                        # summed over 256 CUs x 4 SIMDs
+        us = statistics.median(durations[k]) if durations.get(k) else 0.0
+        req, hit = avg(tcc[k]["TCC_REQ_sum"]), avg(tcc[k]["TCC_HIT_sum"])
+        act = avg(sq[k]["SQ_ACTIVE_INST_LDS"])
+        wc = avg(sq[k]["SQ_WAVE_CYCLES"])
+        rows.append((gui, "| `%s` | %d | %.0f | %s | %.1f %% | %.3g | %.2f | %.2f | %s |" % (
+            k, len(tcc[k]["GRBM_GUI_ACTIVE"]), gui, ("%.2f" % (gui / us / 1e3)) if us else "-", 100 * mf / gui if gui else 0,
+            avg(sq[k]["SQ_INSTS_VALU_MFMA_MOPS_BF16"]), avg(sq[k]["SQ_LDS_BANK_CONFLICT"]) / act if act else 0,
+            avg(sq[k]["SQ_WAIT_INST_ANY"]) / wc if wc else 0, ("%.1f %%" % (100 * hit / req)) if req else "-")))
+    return lines + [r[1] for r in sorted(rows, key=lambda r: -r[0])]
+
+
+def traffic(fetch, write):
+    """HBM-side GB per class and the per-kernel table; counters scaled by the 1 GiB calibration copy."""
+    def calib(per, ctr):
+        vals = [v for k, c in per.items() if "copy" in k.lower() or "elementwise" in k.lower() for v in c[ctr]]
+        return max(vals) if vals else None
+    cf, cw = calib(fetch, "FETCH_SIZE"), calib(write, "WRITE_SIZE")
+    kib = float(1 << 20)                                      # the copy reads and writes 1 048 576 KiB
+    sf = kib / cf if cf else 2.0
+    sw = kib / cw if cw else 1.0
+    lines = ["| kernel | launches | FETCH_SIZE avg (KiB, raw) | WRITE_SIZE avg (KiB, raw) | scaled read GB | scaled write GB |",
+             "|---|---|---|---|---|---|"]
+    total = {}
+    for k in sorted(fetch, key=lambda k: -sum(fetch[k]["FETCH_SIZE"])):
+        f, w = fetch[k]["FETCH_SIZE"], (write[k]["WRITE_SIZE"] if k in write else [])
+        if not f:
+            continue
+        total[k] = (len(f), sum(f) * sf * 1024, sum(w) * sw * 1024 if w else 0.0)
+        lines.append("| `%s` | %d | %.0f | %.0f | %.3f | %.3f |" % (k, len(f), avg(f), avg(w), avg(f) * sf * 1024 / 1e9,
+                                                                   avg(w) * sw * 1024 / 1e9))
+    return lines, total, (cf, cw, sf, sw)
+
+
+def class_bytes(total):
+    """Bytes per layer call (per launch for the repack) of every kernel class present."""
+    def count(sub):
+        return sum(v[0] for k, v in total.items() if sub in k)
+
+    def size(subs):
+        return sum(v[1] + v[2] for k, v in total.items() if any(s in k for s in subs))
+    n_prefill = count("attn_prefill_lds_kernel") + count("attn_prefill_mfma_kernel")
+    n_decode = count("attn_decode_mfma_kernel")
+    out = {}
+    for cls, subs in CLASSES:
+        b = size(subs)
+        if not b:
+            continue
+        if cls == "kv_repack":          # the export of a whole batch is what bench.py times: the largest gather launches
+            per = [(v[1] + v[2]) / v[0] for k, v in total.items() if "kv_repack_kernel<unsigned short, true>" in k]
+            out[cls] = max(per) if per else b
+        else:
+            calls = n_prefill if cls.startswith("prefill") else n_decode
+            if calls:
+                out[cls] = b / calls
+    return out, n_prefill, n_decode
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--config", type=int, required=True, choices=[2, 3, 4, 5])
+    ap.add_argument("--dir", required=True, help="directory that holds trace_cN, sq_cN, tcc_cN, fetch_cN, write_cN")
+    ap.add_argument("--profiles", default="profiles")
+    ap.add_argument("--traffic", default="bench_traffic.json")
+    a = ap.parse_args()
+    n, wl = a.config, WORKLOAD[a.config]
+    d = lambda kind: os.path.join(a.dir, "%s_c%d" % (kind, n))
+    flags = "--config %d --only --no-cpu-baseline" % n
+    short_flags = flags + " --steps 2 --warmup 1 --class-reps 2"
+    os.makedirs(a.profiles, exist_ok=True)
+
+    trace_lines, durations = kernel_trace_tables(d("trace"))
+    if trace_lines:
+        with open(os.path.join(a.profiles, "bench_%s_kernel_trace.md" % wl), "w") as f:
+            f.write("# Kernel trace of `bench.py %s` (%s)\n\nCommand (from the repository root on the MI355X box, after "
+                    "`cd /tmp && export TMPDIR=/tmp`):\n\n    rocprofv3 --kernel-trace --stats -d OUT/trace_c%d -o t --output-format csv "
+                    "-- python3 bench.py %s\n\nAll passes of the run together (the timed steps, then the per-class timing passes); "
+                    "summarised by `python -m paper_2503_06433_amd.profile_summary`.\n\n" % (flags, wl, n, flags))
+            f.write("\n".join(trace_lines) + "\n")
+    sq, tcc = read_counters(d("sq")), read_counters(d("tcc"))
+    if sq or tcc:
+        with open(os.path.join(a.profiles, "bench_%s_counters.md" % wl), "w") as f:
+            f.write("# Hardware counters of the kernels of `bench.py %s` (%s)\n\nTwo runs (rocprofv3 does not split counters over "
+                    "passes):\n\n    rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 SQ_LDS_BANK_CONFLICT "
+                    "SQ_ACTIVE_INST_LDS SQ_WAVE_CYCLES SQ_WAIT_INST_ANY SQ_WAIT_INST_LDS -d OUT/sq_c%d -o t --output-format csv -- python3 "
+                    "bench.py %s\n    rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum GRBM_GUI_ACTIVE -d OUT/tcc_c%d -o t --output-format "
+                    "csv -- python3 bench.py %s\n\nAverages per launch.  GPU cycles = GRBM_GUI_ACTIVE / 8 (the counter sums the 8 XCDs); clock = "
+                    "those cycles / the kernel's median duration in the kernel trace; MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / 1024 (256 CUs x 4 "
+                    "SIMDs) / GPU cycles.\n\n" % (flags, wl, n, short_flags, n, short_flags))
+            f.write("\n".join(counter_table(sq, tcc, durations)) + "\n")
+    fetch, write = read_counters(d("fetch")), read_counters(d("write"))
+    if fetch:
+        lines, total, (cf, cw, sf, sw) = traffic(fetch, write)
+        per_class, n_pf, n_dec = class_bytes(total)
+        with open(os.path.join(a.profiles, "bench_%s_hbm_traffic.md" % wl), "w") as f:
+            f.write("# HBM-side traffic of the kernels of `bench.py %s` (%s)\n\nTwo runs, one counter each:\n\n    rocprofv3 --pmc FETCH_SIZE -d "
+                    "OUT/fetch_c%d -o t --output-format csv -- python3 bench.py %s --calibrate-copy\n    rocprofv3 --pmc WRITE_SIZE -d OUT/write_c%d "
+                    "-o t --output-format csv -- python3 bench.py %s --calibrate-copy\n\nCalibration: `--calibrate-copy` runs a plain 1 GiB "
+                    "device-to-device copy (1 048 576 KiB read, 1 048 576 KiB written); the counters read %s (FETCH_SIZE) and %s (WRITE_SIZE) for "
+                    "it, so FETCH_SIZE is scaled by %.3f and WRITE_SIZE by %.3f.\n\n" % (
+                        flags, wl, n, short_flags, n, short_flags, "%.0f" % cf if cf else "nothing", "%.0f" % cw if cw else "nothing", sf, sw))
+            f.write("\n".join(lines) + "\n\nPer layer call (sums over the launches of a class divided by the %d prefill / %d decode calls "
+                    "of the run; per launch for the repack), as written to `bench_traffic.json`:\n\n| class | HBM-side GB |\n|---|---|\n"
+                    % (n_pf, n_dec))
+            for cls, b in per_class.items():
+                f.write("| %s | %.3f |\n" % (cls, b / 1e9))
+        tj = {}
+        if os.path.exists(a.traffic):
+            with open(a.traffic) as f:
+                tj = json.load(f)
+        tj = {k: v for k, v in tj.items() if "." in k or k == "_note"}       # drop entries of the older, unprefixed form
+        for cls, b in per_class.items():
+            tj["c%d.%s" % (n, cls)] = b
+        tj["_note"] = ("HBM-side bytes per layer call (per launch for the repack) from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, scaled "
+                       "by the factors a 1 GiB device copy gives; written by python -m paper_2503_06433_amd.profile_summary, see profiles/")
+        with open(a.traffic, "w") as f:
+            json.dump(tj, f, indent=1)
+        print(json.dumps({k: v for k, v in tj.items() if k.startswith("c%d." % n)}, indent=1))
+
+
+if __name__ == "__main__":
+    main()
