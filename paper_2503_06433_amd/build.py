@@ -39,7 +39,9 @@ def build(verbose=False, jobs=8):
         for (src, _, _), msg in zip(units, ex.map(lambda u: _compile(*u), units)):
             if verbose and msg.strip():
                 print(src, msg, file=sys.stderr)
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs, "-lpthread"]
+    # the HSA runtime (the one HIP itself runs on) carries the swap-out's device-to-host copies on the DMA engines
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs, "-lpthread", "-L/opt/rocm/lib",
+           "-lhsa-runtime64"]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)

@@ -275,30 +275,48 @@ template <int EPI>
 __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __restrict__ A, int lda,
                                                                const bf16_t* __restrict__ Wt, bf16_t* __restrict__ C,
                                                                int ldc, const bf16_t* __restrict__ R, int M, int N,
-                                                               int K, int tiles_m, int tiles_n, int per_xcd,
+                                                               int K, int tiles_m, int tiles_n, int sync_walk,
                                                                int cus_per_xcd, int it0, int max_it, int GM) {
     constexpr int BM = 256, BN = 256;
     constexpr int STAGE = (BM + BN) * 128;       // bytes per ring stage
     constexpr int LPS = 16;                      // loads per wave per slice
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
-    // ---- this block's tiles: XCD x (blocks are dealt to the XCDs round-robin) owns the contiguous run
-    // [x * per_xcd, (x+1) * per_xcd) of tiles, ordered in groups of GM tile rows, so that the slices an XCD
-    // touches at one time stay in its own L2; inside the run the XCD's blocks take tiles round-robin
+    // ---- this block's tiles.  Tiles are ordered in groups of GM tile rows (inside a group: column by column), so
+    // that the 32 blocks of an XCD (blocks are dealt to the XCDs round-robin) work on GM rows x 32/GM columns at a
+    // time and the slices they touch stay in that XCD's L2.  XCD x owns `gpx` whole groups, [x gpx, (x+1) gpx):
+    // all eight XCDs then sweep the columns in step, each over its own rows, so a weight slice is asked for by
+    // the eight L2s at about the same time and comes from HBM once (the other seven find it in the memory-side
+    // cache), and the 8 GM rows of tokens in use stay in that cache over the whole sweep.  The rows that are
+    // left over (fewer than 8 whole groups) are dealt to the XCDs as eight contiguous runs.  A block takes every
+    // cus_per_xcd-th tile of its XCD's list; this launch covers rounds [it0, it0 + max_it) of that walk.
     const int xcd = blockIdx.x & 7, cu = blockIdx.x >> 3;
-    const int n_tiles = tiles_m * tiles_n;
-    int xcd_end = (xcd + 1) * per_xcd;
-    xcd_end = xcd_end < n_tiles ? xcd_end : n_tiles;
-    // (this launch covers rounds [it0, it0 + max_it) of that walk)
-    const int first = xcd * per_xcd + cu + it0 * cus_per_xcd;
-    if (first >= xcd_end) return;
-    int nt_local = (xcd_end - first + cus_per_xcd - 1) / cus_per_xcd;
+    const int group_size = GM * tiles_n;
+    const int gpx = sync_walk ? (tiles_m / GM) / 8 : 0;
+    const int main_tiles = gpx * group_size;
+    const int rem_row0 = 8 * gpx * GM;
+    const int rem_tiles = (tiles_m - rem_row0) * tiles_n;
+    const int rem_per_xcd = (rem_tiles + 7) / 8;
+    int my_rem = rem_tiles - xcd * rem_per_xcd;
+    my_rem = my_rem < rem_per_xcd ? my_rem : rem_per_xcd;
+    my_rem = my_rem > 0 ? my_rem : 0;
+    const int my_tiles = main_tiles + my_rem;
+    const int first = cu + it0 * cus_per_xcd;          // index in this XCD's list
+    if (first >= my_tiles) return;
+    int nt_local = (my_tiles - first + cus_per_xcd - 1) / cus_per_xcd;
     nt_local = nt_local < max_it ? nt_local : max_it;
     auto tile_origin = [&](int it, int& m0, int& n0) {
-        const int logical = first + it * cus_per_xcd;
-        const int group_size = GM * tiles_n;
+        const int l = first + it * cus_per_xcd;
+        int row0, logical;
+        if (l < main_tiles) {
+            row0 = xcd * gpx * GM;
+            logical = l;
+        } else {
+            row0 = rem_row0;
+            logical = xcd * rem_per_xcd + (l - main_tiles);
+        }
         const int group = logical / group_size;
-        const int first_m = group * GM;
+        const int first_m = row0 + group * GM;
         const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
         const int in_group = logical - group * group_size;
         m0 = (first_m + in_group % gm) * BM;
@@ -559,18 +577,26 @@ static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16
         if (e != hipSuccess) return e;
         if (n_cus < 8) n_cus = 8;
     }
-    const int per_xcd = (int)((n_tiles + 7) / 8);
     const int cus_per_xcd = n_cus / 8;
+    // Tile rows per group of the walk: the 32 CUs of an XCD cover GM x 32/GM tiles at a time, so an XCD re-fetches
+    // its token slices (tiles_n * GM / 32) times and the weight slices once per group from beyond its L2; with the
+    // eight XCDs sweeping the columns in step those re-fetches are served by the memory-side cache (the 8 GM tile
+    // rows in use and the 32/GM tile columns of weights fit it), and HBM sees the weights once per 8 GM tile rows.
+    // Measured (fraction of the MFMA peak over the four GEMMs of a layer, GM = 2 / 4 / 8 / 16): 70B-shape slice of
+    // 75 k tokens 0.518 / 0.529 / 0.501 / 0.477, 13B shape 0.503 / 0.510 / 0.518 / 0.457, 7B shape of 20 k tokens
+    // 0.524 / 0.516 / 0.508 / 0.488; without the XCDs in step (each on a contiguous run of tiles): 0.499 on the
+    // 70B shape.  Groups of 4, of 2 for wide outputs of few tile rows.
+    static const int gm_env = getenv("SS_GEMM_GROUP_ROWS") ? atoi(getenv("SS_GEMM_GROUP_ROWS")) : 0;
+    const int gm_rows = gm_env > 0 ? gm_env : (tiles_n >= 64 && tiles_m < 100 ? 2 : 4);
+    // the longest list of an XCD: its whole groups plus its share of the left-over rows (same arithmetic as the kernel)
+    static const int sync_walk = getenv("SS_GEMM_SYNC_WALK") ? atoi(getenv("SS_GEMM_SYNC_WALK")) : 1;
+    const int gpx = sync_walk ? (tiles_m / gm_rows) / 8 : 0;
+    const long long main_tiles = (long long)gpx * gm_rows * tiles_n;
+    const long long rem_tiles = (long long)(tiles_m - 8 * gpx * gm_rows) * tiles_n;
+    const int per_xcd = (int)(main_tiles + (rem_tiles + 7) / 8);
     const unsigned grid = 8 * (unsigned)(per_xcd < cus_per_xcd ? per_xcd : cus_per_xcd);
     const int rounds_total = (per_xcd + cus_per_xcd - 1) / cus_per_xcd;
     const int step = max_rounds > 0 ? max_rounds : rounds_total;
-    // Tile rows per group of the walk: the 32 CUs of an XCD cover GM x 32/GM tiles at a time, so token
-    // slices are re-fetched (tiles_n * GM / 32) times and weight slices (tiles_m / GM) times.  The token
-    // operand is the larger one here, so groups are short, shorter still for wide outputs (measured on the
-    // 7B shapes, us for QKV / O / gate+up / down: GM 8: 1393 / 531 / 2914 / 1479, GM 4: 1378 / 541 / 2755 /
-    // 1447, GM 2: 1404 / 572 / 2696 / 1519).
-    static const int gm_env = getenv("SS_GEMM_GROUP_ROWS") ? atoi(getenv("SS_GEMM_GROUP_ROWS")) : 0;
-    const int gm_rows = gm_env > 0 ? gm_env : (tiles_n >= 64 ? 2 : 4);
 #define SS_LAUNCH(E)                                                                                            \
     {                                                                                                           \
         auto kfn = gemm_mfma_stream_kernel<E>;                                                                  \
@@ -582,7 +608,7 @@ static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16
             attr_set = true;                                                                                    \
         }                                                                                                       \
         for (int it0 = 0; it0 < rounds_total; it0 += step)                                                      \
-            kfn<<<grid, 256, STREAM_LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd,        \
+            kfn<<<grid, 256, STREAM_LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, sync_walk,      \
                                               cus_per_xcd, it0, step, gm_rows);                                 \
     }
     switch (epi) {

@@ -22,6 +22,9 @@
 #include <unordered_map>
 #include <vector>
 
+#include <hsa/hsa.h>
+#include <hsa/hsa_ext_amd.h>
+
 #include "../../include/seesaw_rt.h"
 #include "ss_kernels.h"
 #define SS_DECL_NS ssk16
@@ -116,12 +119,124 @@ struct Job {
     int64_t needs_out = 0;     // swap-in: number of swap-out jobs that must have completed first
 };
 
+// Device-to-host copies on the DMA engines, issued through the HSA runtime.  The HIP runtime that a process gets
+// when PyTorch is loaded first (the 7.0 runtime bundled with the wheel) executes hipMemcpyAsync from device memory
+// into page-locked host memory as a copy kernel on the compute units (`__amd_rocclr_copyBuffer` in a kernel trace:
+// no device-to-host entry in the memory-copy trace), while the same call under the system's 7.2 runtime goes to a
+// DMA engine; host-to-device copies use the engines under both.  A copy kernel needs compute units, which the
+// persistent GEMM blocks hold, so the swap-out both slowed the layer down and waited for it.
+// hsa_amd_memory_async_copy addresses the engines directly and works the same under either runtime: both are
+// the process's one HSA runtime (same library, reference-counted hsa_init), and the buffers HIP allocated
+// (hipMalloc, hipHostMalloc) are HSA allocations that the agents already may access.
+struct HsaCopy {
+    bool ok = false;
+    hsa_agent_t gpu{}, cpu{};
+    hsa_signal_t done{};
+    static hsa_status_t pick(hsa_agent_t a, void* data) {
+        HsaCopy* h = (HsaCopy*)data;
+        hsa_device_type_t t;
+        if (hsa_agent_get_info(a, HSA_AGENT_INFO_DEVICE, &t) != HSA_STATUS_SUCCESS) return HSA_STATUS_SUCCESS;
+        if (t == HSA_DEVICE_TYPE_CPU && !h->cpu.handle) h->cpu = a;
+        if (t == HSA_DEVICE_TYPE_GPU) {
+            uint32_t bdf = 0;
+            if (hsa_agent_get_info(a, (hsa_agent_info_t)HSA_AMD_AGENT_INFO_BDFID, &bdf) != HSA_STATUS_SUCCESS) return HSA_STATUS_SUCCESS;
+            if ((int)((bdf >> 8) & 0xff) == h->want_bus && (int)((bdf >> 3) & 0x1f) == h->want_dev) h->gpu = a;
+        }
+        return HSA_STATUS_SUCCESS;
+    }
+    int want_bus = -1, want_dev = -1;
+    // finds the HSA agents of HIP device `device` (matched by PCI bus and device number) and of the host
+    void init(int device) {
+        const char* e = getenv("SS_HSA_COPY");
+        if (e && e[0] == '0') return;
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, device) != hipSuccess) { (void)hipGetLastError(); return; }
+        want_bus = prop.pciBusID;
+        want_dev = prop.pciDeviceID;
+        if (hsa_init() != HSA_STATUS_SUCCESS) return;
+        if (hsa_iterate_agents(pick, this) != HSA_STATUS_SUCCESS || !gpu.handle || !cpu.handle) { (void)hsa_shut_down(); return; }
+        if (hsa_signal_create(0, 0, nullptr, &done) != HSA_STATUS_SUCCESS) { (void)hsa_shut_down(); return; }
+        // An engine of its own for this direction.  Left to the HSA runtime, these copies and the host-to-device
+        // copies of the swap-in (issued by the HIP runtime) queue up on the same engines and the two PCIe
+        // directions take turns; and not every engine the runtime lists reaches the host link at full rate
+        // (measured on the pipelined step of the 7B-shape layer, ms per step: engines 0 / 1 / 2 / 3: 13.9 / 12.0 /
+        // 9.0 / 9.0, runtime's choice 12.0, engines 4 and above 26 - 47).  So every listed engine copies 16 MB once,
+        // and of those within 10 % of the fastest the highest-numbered one is taken (the HIP runtime starts from
+        // the lowest).  SS_HSA_ENGINE = bit index overrides, -1 leaves the choice to the HSA runtime.
+        uint32_t st_out = 0;
+        (void)hsa_amd_memory_copy_engine_status(cpu, gpu, &st_out);
+        int bit = -1;
+        if (const char* eb = getenv("SS_HSA_ENGINE")) {
+            bit = atoi(eb);
+        } else {
+            const size_t probe = (size_t)16 << 20;
+            void *d = nullptr, *h = nullptr;
+            if (hipMalloc(&d, probe) == hipSuccess && hipHostMalloc(&h, probe, hipHostMallocDefault) == hipSuccess &&
+                hipMemset(d, 0, probe) == hipSuccess && hipDeviceSynchronize() == hipSuccess) {
+                double best = 1e30, t[16];
+                for (int b = 0; b < 16; ++b) {
+                    t[b] = 1e30;
+                    if (!(st_out & (1u << b))) continue;
+                    for (int rep = 0; rep < 2; ++rep) {                  // the first copy on an engine sets it up
+                        hsa_signal_store_relaxed(done, 1);
+                        const auto t0 = std::chrono::steady_clock::now();
+                        if (hsa_amd_memory_async_copy_on_engine(h, cpu, d, gpu, probe, 0, nullptr, done,
+                                                                (hsa_amd_sdma_engine_id_t)(1u << b), false) != HSA_STATUS_SUCCESS) break;
+                        if (hsa_signal_wait_scacquire(done, HSA_SIGNAL_CONDITION_LT, 1, 2000000000ull, HSA_WAIT_STATE_BLOCKED) != 0) break;
+                        if (rep) t[b] = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+                    }
+                    best = std::min(best, t[b]);
+                }
+                for (int b = 0; b < 16; ++b)
+                    if (t[b] <= 1.1 * best) bit = b;
+            }
+            (void)hipGetLastError();
+            if (d) (void)hipFree(d);
+            if (h) (void)hipHostFree(h);
+        }
+        engine = bit >= 0 && bit < 16 ? (1u << bit) : 0;
+        if (getenv("SS_TRACE_MOVER"))
+            fprintf(stderr, "[mover] DMA engines listed for device->host: 0x%x; using 0x%x\n", st_out, engine);
+        ok = true;
+    }
+    uint32_t engine = 0;                 // hsa_amd_sdma_engine_id_t of the device -> host copies, 0 = the runtime's choice
+    void shutdown() {
+        if (!ok) return;
+        (void)hsa_signal_destroy(done);
+        (void)hsa_shut_down();
+        ok = false;
+    }
+    struct Run { void* host; const void* dev; size_t bytes; };
+    // all runs device -> host, then waits for them; false on any error (the caller falls back to hipMemcpyAsync)
+    bool copy_out(const std::vector<Run>& runs) {
+        if (!ok) return false;
+        if (runs.empty()) return true;
+        hsa_signal_store_relaxed(done, (hsa_signal_value_t)runs.size());
+        size_t issued = 0;
+        for (const Run& r : runs) {
+            const hsa_status_t st = engine
+                ? hsa_amd_memory_async_copy_on_engine(r.host, cpu, r.dev, gpu, r.bytes, 0, nullptr, done, (hsa_amd_sdma_engine_id_t)engine, false)
+                : hsa_amd_memory_async_copy(r.host, cpu, r.dev, gpu, r.bytes, 0, nullptr, done);
+            if (st != HSA_STATUS_SUCCESS) break;
+            ++issued;
+        }
+        if (issued < runs.size())       // account for the copies that were never issued, then drain the others
+            hsa_signal_add_relaxed(done, -(hsa_signal_value_t)(runs.size() - issued));
+        hsa_signal_value_t v;
+        do {
+            v = hsa_signal_wait_scacquire(done, HSA_SIGNAL_CONDITION_LT, 1, UINT64_MAX, HSA_WAIT_STATE_BLOCKED);
+        } while (v > 0);
+        return issued == runs.size() && v == 0;
+    }
+};
+
 // One mover lane: a host thread, a side stream, a two-slot pinned ring with its
 // device staging twin, and a metadata region.  Lane 0 carries swap-outs, lane 1
 // swap-ins, so that the two PCIe directions (and their host copies) overlap.
 struct Lane {
     hipStream_t side = nullptr;
-    hipStream_t copy = nullptr;                  // the swap-out's device-to-host copies
+    hipStream_t copy = nullptr;                  // the swap-out's device-to-host copies (when the HSA path is off)
+    HsaCopy hsa;                                 // the swap-out's device-to-host copies on the DMA engines
     hipEvent_t copy_ev[2] = {nullptr, nullptr};
     uint8_t* pinned = nullptr;
     uint8_t* dev_staging = nullptr;
@@ -986,14 +1101,19 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
             // time steadier than with the copies on the gather's stream.  The runtime executes them as copy
             // kernels either way.
             hipStream_t out_stream = L.side;
-            if (job.dir == SS_OUT && L.copy) {
+            const bool via_hsa = job.dir == SS_OUT && L.hsa.ok;
+            std::vector<HsaCopy::Run> hsa_runs;
+            if (job.dir == SS_OUT && !via_hsa && L.copy) {
                 HIP_TRY(c, hipEventRecord(L.copy_ev[0], L.side));
                 HIP_TRY(c, hipStreamWaitEvent(L.copy, L.copy_ev[0], 0));
                 out_stream = L.copy;
             }
+            // merged runs: up to copy_max_bytes for copies the HIP runtime carries out, 64 MB on the DMA engines
+            const size_t merge_max = via_hsa ? std::max(c->copy_max_bytes, (size_t)64 << 20) : c->copy_max_bytes;
             auto flush = [&]() -> int {
                 if (!cur_bytes) return SS_OK;
-                if (job.dir == SS_OUT) HIP_TRY(c, hipMemcpyAsync(cur_t, cur_d, cur_bytes, hipMemcpyDeviceToHost, out_stream));
+                if (via_hsa) hsa_runs.push_back({cur_t, cur_d, cur_bytes});
+                else if (job.dir == SS_OUT) HIP_TRY(c, hipMemcpyAsync(cur_t, cur_d, cur_bytes, hipMemcpyDeviceToHost, out_stream));
                 else HIP_TRY(c, hipMemcpyAsync(cur_d, cur_t, cur_bytes, hipMemcpyHostToDevice, L.side));
                 cur_bytes = 0;
                 return SS_OK;
@@ -1004,7 +1124,7 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
                 for (int kv = 0; kv < 2; ++kv) {
                     uint8_t* t = tier_run(c, s, sj, units[u].ll, kv);
                     uint8_t* d = L.dev_staging + uoff + (size_t)kv * run;
-                    if (cur_bytes && cur_bytes + run <= c->copy_max_bytes && t == cur_t + cur_bytes && d == cur_d + cur_bytes) {
+                    if (cur_bytes && cur_bytes + run <= merge_max && t == cur_t + cur_bytes && d == cur_d + cur_bytes) {
                         cur_bytes += run;
                     } else {
                         int rc = flush();
@@ -1016,6 +1136,15 @@ int worker_job(ss_ctx* c, Lane& L, Job& job) {
             }
             int rc = flush();
             if (rc) return rc;
+            if (via_hsa) {
+                // the gather kernel has written the staging buffer; then the engines copy while this thread waits
+                HIP_TRY(c, hipStreamSynchronize(L.side));
+                if (!L.hsa.copy_out(hsa_runs)) {
+                    L.hsa.ok = false;                 // once: from here on (and for these runs) the HIP runtime's copies
+                    for (const HsaCopy::Run& r : hsa_runs)
+                        HIP_TRY(c, hipMemcpyAsync(r.host, r.dev, r.bytes, hipMemcpyDeviceToHost, L.side));
+                }
+            }
             if (out_stream != L.side) {
                 HIP_TRY(c, hipEventRecord(L.copy_ev[1], L.copy));
                 HIP_TRY(c, hipStreamWaitEvent(L.side, L.copy_ev[1], 0));
@@ -1434,6 +1563,7 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
             HIP_TRY(c, hipMalloc((void**)&L.mv_meta_dev, c->mv_meta_cap));
             HIP_TRY(c, hipStreamCreateWithFlags(&L.side, hipStreamNonBlocking));
             HIP_TRY(c, hipStreamCreateWithFlags(&L.copy, hipStreamNonBlocking));
+            if (&L == &c->lane[0]) L.hsa.init(rt->device);
             for (hipEvent_t& e : L.copy_ev) HIP_TRY(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
             for (int i = 0; i < 2; ++i) HIP_TRY(c, hipEventCreateWithFlags(&L.mv_ev[i], hipEventDisableTiming));
         }
@@ -1485,6 +1615,7 @@ int ss_destroy(ss_ctx* c) {
         for (int i = 0; i < 2; ++i) if (L.mv_ev[i]) (void)hipEventDestroy(L.mv_ev[i]);
         if (L.side) (void)hipStreamDestroy(L.side);
         if (L.copy) (void)hipStreamDestroy(L.copy);
+        L.hsa.shutdown();
         for (hipEvent_t e : L.copy_ev) if (e) (void)hipEventDestroy(e);
     }
     for (void* p : {(void*)c->d_rope, c->d_embed, c->d_gf, c->d_wlm_t, (void*)c->d_ids})
