@@ -93,20 +93,19 @@ def kernel_trace_tables(directory):
 
 
 def counter_table(sq, tcc, durations):
-    lines = ["| kernel | launches | GPU cycles | clock GHz | MFMA busy | MFMA ops (bf16) | LDS conflict cycles / active LDS cycle | "
-             "waiting / wave cycles | L2 hit rate |", "|---|---|---|---|---|---|---|---|---|"]
+    lines = ["| kernel | launches | GPU cycles | MFMA busy | MFMA ops (bf16) | LDS conflict cycles / active LDS cycle | "
+             "waiting / wave cycles | L2 hit rate |", "|---|---|---|---|---|---|---|---|"]
     rows = []
     for k in sorted(set(sq) | set(tcc)):
         gui = avg(tcc[k]["GRBM_GUI_ACTIVE"]) / 8 if k in tcc else 0.0            # summed over the 8 XCDs
         if gui < 20000:
             continue
         mf = avg(sq[k]["SQ_VALU_MFMA_BUSY_CYCLES"]) / 1024                        # summed over 256 CUs x 4 SIMDs
-        us = statistics.median(durations[k]) if durations.get(k) else 0.0
         req, hit = avg(tcc[k]["TCC_REQ_sum"]), avg(tcc[k]["TCC_HIT_sum"])
         act = avg(sq[k]["SQ_ACTIVE_INST_LDS"])
         wc = avg(sq[k]["SQ_WAVE_CYCLES"])
-        rows.append((gui, "| `%s` | %d | %.0f | %s | %.1f %% | %.3g | %.2f | %.2f | %s |" % (
-            k, len(tcc[k]["GRBM_GUI_ACTIVE"]), gui, ("%.2f" % (gui / us / 1e3)) if us else "-", 100 * mf / gui if gui else 0,
+        rows.append((gui, "| `%s` | %d | %.0f | %.1f %% | %.3g | %.2f | %.2f | %s |" % (
+            k, len(tcc[k]["GRBM_GUI_ACTIVE"]), gui, 100 * mf / gui if gui else 0,
             avg(sq[k]["SQ_INSTS_VALU_MFMA_MOPS_BF16"]), avg(sq[k]["SQ_LDS_BANK_CONFLICT"]) / act if act else 0,
             avg(sq[k]["SQ_WAIT_INST_ANY"]) / wc if wc else 0, ("%.1f %%" % (100 * hit / req)) if req else "-")))
     return lines + [r[1] for r in sorted(rows, key=lambda r: -r[0])]
@@ -134,7 +133,7 @@ def traffic(fetch, write):
     return lines, total, (cf, cw, sf, sw)
 
 
-def class_bytes(total):
+def class_bytes(total, config):
     """Bytes per layer call (per launch for the repack) of every kernel class present."""
     def count(sub):
         return sum(v[0] for k, v in total.items() if sub in k)
@@ -148,6 +147,8 @@ def class_bytes(total):
         b = size(subs)
         if not b:
             continue
+        if cls == "kv_repack" and config not in (2, 5):
+            continue                    # only these two configurations time the repack (the others scatter their synthetic caches once)
         if cls == "kv_repack":          # the export of a whole batch is what bench.py times: the largest gather launches
             per = [(v[1] + v[2]) / v[0] for k, v in total.items() if "kv_repack_kernel<unsigned short, true>" in k]
             out[cls] = max(per) if per else b
@@ -186,23 +187,25 @@ def main():
                     "passes):\n\n    rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES SQ_INSTS_VALU_MFMA_MOPS_BF16 SQ_LDS_BANK_CONFLICT "
                     "SQ_ACTIVE_INST_LDS SQ_WAVE_CYCLES SQ_WAIT_INST_ANY SQ_WAIT_INST_LDS -d OUT/sq_c%d -o t --output-format csv -- python3 "
                     "bench.py %s\n    rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum GRBM_GUI_ACTIVE -d OUT/tcc_c%d -o t --output-format "
-                    "csv -- python3 bench.py %s\n\nAverages per launch.  GPU cycles = GRBM_GUI_ACTIVE / 8 (the counter sums the 8 XCDs); clock = "
-                    "those cycles / the kernel's median duration in the kernel trace; MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / 1024 (256 CUs x 4 "
-                    "SIMDs) / GPU cycles.\n\n" % (flags, wl, n, short_flags, n, short_flags))
+                    "csv -- python3 bench.py %s\n\nAverages per launch (while KV mover jobs are pending the runtime cuts the prefill GEMMs into launches "
+                    "of 8 tiles per block, so their rows average whole and partial launches).  GPU cycles = GRBM_GUI_ACTIVE / 8 (the counter sums "
+                    "the 8 XCDs); MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / 1024 (256 CUs x 4 SIMDs) / GPU cycles.\n\n" % (flags, wl, n, short_flags, n, short_flags))
             f.write("\n".join(counter_table(sq, tcc, durations)) + "\n")
     fetch, write = read_counters(d("fetch")), read_counters(d("write"))
     if fetch:
         lines, total, (cf, cw, sf, sw) = traffic(fetch, write)
-        per_class, n_pf, n_dec = class_bytes(total)
+        per_class, n_pf, n_dec = class_bytes(total, n)
         with open(os.path.join(a.profiles, "bench_%s_hbm_traffic.md" % wl), "w") as f:
-            f.write("# HBM-side traffic of the kernels of `bench.py %s` (%s)\n\nTwo runs, one counter each:\n\n    rocprofv3 --pmc FETCH_SIZE -d "
+            f.write("# Traffic between L2 and the memory fabric of the kernels of `bench.py %s` (%s)\n\nFETCH_SIZE / WRITE_SIZE count what "
+                    "leaves the eight L2s towards memory: reads that the memory-side cache (256 MB, in front of HBM) serves are included, "
+                    "so this is an upper bound of the HBM traffic.  Two runs, one counter each:\n\n    rocprofv3 --pmc FETCH_SIZE -d "
                     "OUT/fetch_c%d -o t --output-format csv -- python3 bench.py %s --calibrate-copy\n    rocprofv3 --pmc WRITE_SIZE -d OUT/write_c%d "
                     "-o t --output-format csv -- python3 bench.py %s --calibrate-copy\n\nCalibration: `--calibrate-copy` runs a plain 1 GiB "
                     "device-to-device copy (1 048 576 KiB read, 1 048 576 KiB written); the counters read %s (FETCH_SIZE) and %s (WRITE_SIZE) for "
                     "it, so FETCH_SIZE is scaled by %.3f and WRITE_SIZE by %.3f.\n\n" % (
                         flags, wl, n, short_flags, n, short_flags, "%.0f" % cf if cf else "nothing", "%.0f" % cw if cw else "nothing", sf, sw))
             f.write("\n".join(lines) + "\n\nPer layer call (sums over the launches of a class divided by the %d prefill / %d decode calls "
-                    "of the run; per launch for the repack), as written to `bench_traffic.json`:\n\n| class | HBM-side GB |\n|---|---|\n"
+                    "of the run; per launch for the repack), as written to `bench_traffic.json`:\n\n| class | GB beyond L2 |\n|---|---|\n"
                     % (n_pf, n_dec))
             for cls, b in per_class.items():
                 f.write("| %s | %.3f |\n" % (cls, b / 1e9))
@@ -213,8 +216,9 @@ def main():
         tj = {k: v for k, v in tj.items() if "." in k or k == "_note"}       # drop entries of the older, unprefixed form
         for cls, b in per_class.items():
             tj["c%d.%s" % (n, cls)] = b
-        tj["_note"] = ("HBM-side bytes per layer call (per launch for the repack) from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, scaled "
-                       "by the factors a 1 GiB device copy gives; written by python -m paper_2503_06433_amd.profile_summary, see profiles/")
+        tj["_note"] = ("bytes between L2 and the memory fabric (memory-side cache hits included: an upper bound of the HBM bytes) per layer "
+                       "call (per launch for the repack) from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, scaled by the factors a 1 GiB "
+                       "device copy gives; written by python -m paper_2503_06433_amd.profile_summary, see profiles/")
         with open(a.traffic, "w") as f:
             json.dump(tj, f, indent=1)
         print(json.dumps({k: v for k, v in tj.items() if k.startswith("c%d." % n)}, indent=1))
