@@ -276,7 +276,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
                                                                const bf16_t* __restrict__ Wt, bf16_t* __restrict__ C,
                                                                int ldc, const bf16_t* __restrict__ R, int M, int N,
                                                                int K, int tiles_m, int tiles_n, int sync_walk,
-                                                               int cus_per_xcd, int it0, int max_it, int GM) {
+                                                               int cus_per_xcd, int it0, int max_it, int GM,
+                                                               int pf_dist) {
     constexpr int BM = 256, BN = 256;
     constexpr int STAGE = (BM + BN) * 128;       // bytes per ring stage
     constexpr int LPS = 16;                      // loads per wave per slice
@@ -305,6 +306,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
     if (first >= my_tiles) return;
     int nt_local = (my_tiles - first + cus_per_xcd - 1) / cus_per_xcd;
     nt_local = nt_local < max_it ? nt_local : max_it;
+    // (r, c) = the tile's row inside its group and its column: the CUs of an XCD that work on one group row
+    // at a time differ in c, those on one column in r
+    int tile_r = 0, tile_c = 0, tile_gm = 1;
     auto tile_origin = [&](int it, int& m0, int& n0) {
         const int l = first + it * cus_per_xcd;
         int row0, logical;
@@ -319,8 +323,11 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
         const int first_m = row0 + group * GM;
         const int gm = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
         const int in_group = logical - group * group_size;
-        m0 = (first_m + in_group % gm) * BM;
-        n0 = (in_group / gm) * BN;
+        tile_r = in_group % gm;
+        tile_c = in_group / gm;
+        tile_gm = gm;
+        m0 = (first_m + tile_r) * BM;
+        n0 = tile_c * BN;
     };
 
     const int tid = threadIdx.x;
@@ -340,11 +347,20 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
     const int row_lim = isA ? M : N;
     uint32_t roff[LPS];
     const uint8_t* tbase = gbase;
+    // L2 prefetch (see `prefetch` below): this wave asks for the lines of a later slice in every pf_period-th
+    // slice, starting at slice 1 + pf_phase of a tile
+    int pf_row0 = 0, pf_period = 1 << 30, pf_phase = 0, pf_next = -1;
     auto set_roff = [&](int it) {
         int m0, n0;
         tile_origin(it < nt_local ? it : nt_local - 1, m0, n0);
         const int row0 = isA ? m0 : n0;
         tbase = gbase + (size_t)row0 * (size_t)ld * 2;
+        pf_row0 = row0;
+        if (pf_dist > 0) {
+            const int sharers = cus_per_xcd / GM > 0 ? cus_per_xcd / GM : 1;      // CUs of the XCD on one group row
+            pf_period = isA ? sharers : tile_gm;
+            pf_phase = isA ? tile_c % sharers : tile_r;
+        }
 #pragma unroll
         for (int i = 0; i < LPS; ++i) {
             const int row = row_base + i * 8 + (lane >> 3);
@@ -361,6 +377,28 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
         const uint8_t* sb = tbase + (size_t)ksl * 128;
         const uint32_t d = dst0 + (uint32_t)stage * STAGE + i * 1024;
         asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(roff[i]), "s"(sb), "s"(d) : "memory");
+    };
+
+    // L2 prefetch.  Of the 32 CUs of an XCD, cus_per_xcd / GM read the same token rows and GM the same weight rows
+    // at about the same time; whichever asks first waits for the line to come from beyond L2, the others wait with
+    // it, and with a two-stage ring a request has at most one slice time to land: too little for a miss.  So the
+    // CUs take turns (by their column for token rows, by their row in the group for weight rows): in its slice a
+    // wave touches one dword of each of the 128 lines of its loading share of slice `ksl`, pf_dist slices ahead of
+    // the slice being multiplied, which brings the lines into L2 for all sharers.  The dwords land in the wave's
+    // epilogue staging tile (unused inside the K loop) and are never read.  Loads of a wave return in order, so
+    // the requests of the next slice queue behind these two; the mid-slice wait of the slice that issued them
+    // leaves them outstanding (vmcnt 2), every other wait takes them in.
+    const uint32_t pf_dst = lds_base + 2 * STAGE + wave * 8192;
+    auto prefetch = [&](int ksl) {
+        const uint8_t* sb = tbase + (size_t)ksl * 128;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int row = row_base + h * 64 + lane;
+            int gr = pf_row0 + row;
+            gr = gr < row_lim ? gr : row_lim - 1;
+            const uint32_t off = (uint32_t)(gr - pf_row0) * (uint32_t)ld * 2u;
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(sb), "s"(pf_dst) : "memory");
+        }
     };
 
     f32x4_t acc[8][8];       // [n tile][m tile] of 16 x 16
@@ -523,11 +561,24 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
             int k2 = s + 2;
             if (k2 >= nsl) k2 -= nsl;
             if (g + 2 > g_last) k2 = nsl - 1;
+            // no prefetch in slice 0 (stores of the previous tile's epilogue may still be outstanding, and those
+            // do not return in order with the loads) nor where the target lies beyond this tile's K range
+            if (s == 0) pf_next = pf_dist > 0 ? 1 + pf_phase : -1;
+            bool prefetched = false;
+            if (s == pf_next) {
+                pf_next += pf_period;
+                if (s + pf_dist < nsl - 1) {
+                    prefetch(s + pf_dist);
+                    prefetched = true;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
             mfma_step(0, st, 1, false, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             if (s == nsl - 2) set_roff(it + 1);
             __builtin_amdgcn_s_waitcnt(0xC07F);
-            __builtin_amdgcn_s_waitcnt(0x0F70);
+            if (prefetched) __builtin_amdgcn_s_waitcnt(VmcntImm<2>::value);
+            else __builtin_amdgcn_s_waitcnt(0x0F70);
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             mfma_step(1, stn, 0, true, g & 1, k2);
@@ -590,6 +641,13 @@ static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16
     const int gm_rows = gm_env > 0 ? gm_env : (tiles_n >= 64 && tiles_m < 100 ? 2 : 4);
     // the longest list of an XCD: its whole groups plus its share of the left-over rows (same arithmetic as the kernel)
     static const int sync_walk = getenv("SS_GEMM_SYNC_WALK") ? atoi(getenv("SS_GEMM_SYNC_WALK")) : 1;
+    // L2 prefetch distance in slices (0 = off; the kernel needs at least 2).  Measured on the 70B-shape slice
+    // (fraction of the MFMA peak over a layer's four GEMMs, one box): off 0.488-0.494, 2: 0.541-0.555, 3: 0.539-0.551,
+    // 4: 0.515, 6: 0.509; weight lines only 0.541-0.544, token lines only 0.489.  A larger distance gains nothing:
+    // the requests behind a prefetch in the same wave wait for it (loads return in order), and at distance 2
+    // those are requests for the very lines it asked for.
+    static const int pf_env = getenv("SS_GEMM_PREFETCH") ? atoi(getenv("SS_GEMM_PREFETCH")) : 2;
+    const int pf_dist = pf_env >= 2 && pf_env < 64 ? pf_env : 0;
     const int gpx = sync_walk ? (tiles_m / gm_rows) / 8 : 0;
     const long long main_tiles = (long long)gpx * gm_rows * tiles_n;
     const long long rem_tiles = (long long)(tiles_m - 8 * gpx * gm_rows) * tiles_n;
@@ -609,7 +667,7 @@ static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16
         }                                                                                                       \
         for (int it0 = 0; it0 < rounds_total; it0 += step)                                                      \
             kfn<<<grid, 256, STREAM_LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, sync_walk,      \
-                                              cus_per_xcd, it0, step, gm_rows);                                 \
+                                              cus_per_xcd, it0, step, gm_rows, pf_dist);                        \
     }
     switch (epi) {
         case EPI_STORE: SS_LAUNCH(EPI_STORE) break;
