@@ -624,6 +624,10 @@ def main():
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--dtype", choices=["bf16", "f16"], default="bf16",
                     help="16-bit storage type of configuration 2 (bf16: what BASELINE.json names; f16: the paper's own)")
+    ap.add_argument("--zero-data", action="store_true",
+                    help="power probe, not a benchmark: weights, gains and inputs are all zero, so the same instruction streams run "
+                         "without toggling the data paths (the clock the chip then holds shows how far the package power limit, "
+                         "not the kernels' issue rate, sets the speed on real data)")
     ap.add_argument("--offline-loop", action="store_true",
                     help="instead of the layer step: the whole offline engine loop (scheduler, swaps, weight re-shards) on a "
                          "two-layer model of the configuration-2 layer shape, for three sizes of the CPU store")
@@ -645,6 +649,11 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+    if args.zero_data:
+        draw_normal, draw_weights = wl.device_normal, wl.device_layer_weights
+        wl.device_normal = lambda *a, **k: draw_normal(*a, **k).zero_()
+        wl.device_layer_weights = lambda *a, **k: {name: t.zero_() for name, t in draw_weights(*a, **k).items()}
+        args.no_cpu_baseline = True
     if args.calibrate_copy:
         src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda")      # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
@@ -673,7 +682,8 @@ def main():
         "metric": "prefill+decode tokens/s per GPU shard", "value": head["tokens_per_step"] * args.steps / elapsed,
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": elapsed * 1e3 / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if args.config == 1 else (args.dtype if args.config == 2 else "bf16"), "data": "synthetic",
+        "dtype": "f32" if args.config == 1 else (args.dtype if args.config == 2 else "bf16"),
+        "data": "zeros (power probe, not a benchmark result)" if args.zero_data else "synthetic",
         "config": head["config"], "roofline": roof, "rooflines": b.rooflines,
         "phase_ms": dict({"c%d" % args.config: head.get("phase")}, **others),
     }

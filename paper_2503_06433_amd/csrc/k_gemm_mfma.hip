@@ -401,6 +401,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
         }
     };
 
+    // The residual rows of the tile being finished, brought into L2 the same way three slices before the epilogue
+    // reads them: this wave's 128 x 128 piece is 128 rows of 256 bytes = 256 lines, one per lane and request.
+    auto prefetch_residual = [&](int it) {
+        if (EPI != EPI_RESIDUAL) return;
+        int m0, n0;
+        tile_origin(it, m0, n0);
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            const int l = h * 64 + lane;                     // line l: row l / 2, half l % 2 of the wave's piece
+            int gr = m0 + wm * 128 + (l >> 1);
+            gr = gr < M ? gr : M - 1;
+            int gc = n0 + wn * 128 + (l & 1) * 64;
+            gc = gc < N ? gc : 0;
+            const uint32_t off = (uint32_t)(gr - m0) * (uint32_t)ldc * 2u + (uint32_t)gc * 2u;
+            const uint8_t* sb = reinterpret_cast<const uint8_t*>(R) + (size_t)m0 * (size_t)ldc * 2;
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(sb), "s"(pf_dst) : "memory");
+        }
+    };
+
     f32x4_t acc[8][8];       // [n tile][m tile] of 16 x 16
 #pragma unroll
     for (int i = 0; i < 8; ++i)
@@ -572,12 +591,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
                     prefetched = true;
                 }
             }
+            const bool res_prefetched = EPI == EPI_RESIDUAL && pf_dist > 0 && !prefetched && s == nsl - 3 && s > 0;
+            if (res_prefetched) prefetch_residual(it);
             __builtin_amdgcn_sched_barrier(0);
             mfma_step(0, st, 1, false, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             if (s == nsl - 2) set_roff(it + 1);
             __builtin_amdgcn_s_waitcnt(0xC07F);
             if (prefetched) __builtin_amdgcn_s_waitcnt(VmcntImm<2>::value);
+            else if (res_prefetched) __builtin_amdgcn_s_waitcnt(VmcntImm<4>::value);
             else __builtin_amdgcn_s_waitcnt(0x0F70);
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);

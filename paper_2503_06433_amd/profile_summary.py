@@ -16,6 +16,15 @@ and then
 
     python -m paper_2503_06433_amd.profile_summary --config N --dir OUT --profiles profiles --traffic bench_traffic.json
 
+Clock table (how far the package power limit, not the kernels, sets the GEMM rate): two runs that collect the cycle
+counter together with the kernel trace, one on the bench's random data and one with `--zero-data` (same instruction
+streams, data paths not toggling),
+
+    rocprofv3 --kernel-trace --pmc GRBM_GUI_ACTIVE SQ_VALU_MFMA_BUSY_CYCLES -d OUT/clk_random_cN -o t --output-format csv -- python3 bench.py --config N --only --no-cpu-baseline --no-reshard --steps 2 --warmup 1
+    rocprofv3 --kernel-trace --pmc GRBM_GUI_ACTIVE SQ_VALU_MFMA_BUSY_CYCLES -d OUT/clk_zero_cN -o t --output-format csv -- python3 bench.py (same flags) --zero-data
+
+are condensed by the same command into profiles/bench_<workload>_gemm_clock.md when those two directories exist.
+
 `--calibrate-copy` makes bench.py run a plain 1 GiB device-to-device copy first; FETCH_SIZE and WRITE_SIZE (KiB per
 dispatch) are scaled by what they read for that copy of known size.
 """
@@ -111,6 +120,35 @@ def counter_table(sq, tcc, durations):
     return lines + [r[1] for r in sorted(rows, key=lambda r: -r[0])]
 
 
+def clock_rows(directory):
+    """Per kernel of a run that has both a kernel trace and GRBM_GUI_ACTIVE / SQ_VALU_MFMA_BUSY_CYCLES per dispatch:
+    [(kernel, launches, median us, median GHz, median MFMA busy %)] for launches of a millisecond and more."""
+    tr_path, cc_path = find(directory, "kernel_trace.csv"), find(directory, "counter_collection.csv")
+    if not tr_path or not cc_path:
+        return []
+    us = {}
+    with open(tr_path) as f:
+        for r in csv.DictReader(f):
+            us[r["Dispatch_Id"]] = (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3
+    per = collections.defaultdict(dict)
+    with open(cc_path) as f:
+        for r in csv.DictReader(f):
+            per[r["Dispatch_Id"]][r["Counter_Name"]] = float(r["Counter_Value"])
+            per[r["Dispatch_Id"]]["kernel"] = short(r["Kernel_Name"])
+    by_kernel = collections.defaultdict(list)
+    for did, c in per.items():
+        t = us.get(did, 0.0)
+        if t < 1000 or "GRBM_GUI_ACTIVE" not in c:
+            continue
+        cycles = c["GRBM_GUI_ACTIVE"] / 8
+        by_kernel[c["kernel"]].append((t, cycles / t / 1e3, 100 * c.get("SQ_VALU_MFMA_BUSY_CYCLES", 0.0) / 1024 / cycles))
+    rows = []
+    for k, v in sorted(by_kernel.items(), key=lambda kv: -sum(x[0] for x in kv[1])):
+        rows.append((k, len(v), statistics.median(x[0] for x in v), statistics.median(x[1] for x in v),
+                     statistics.median(x[2] for x in v)))
+    return rows
+
+
 def traffic(fetch, write):
     """HBM-side GB per class and the per-kernel table; counters scaled by the 1 GiB calibration copy."""
     def calib(per, ctr):
@@ -191,6 +229,25 @@ def main():
                     "of 8 tiles per block, so their rows average whole and partial launches).  GPU cycles = GRBM_GUI_ACTIVE / 8 (the counter sums "
                     "the 8 XCDs); MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / 1024 (256 CUs x 4 SIMDs) / GPU cycles.\n\n" % (flags, wl, n, short_flags, n, short_flags))
             f.write("\n".join(counter_table(sq, tcc, durations)) + "\n")
+    clk_random, clk_zero = clock_rows(d("clk_random")), clock_rows(d("clk_zero"))
+    if clk_random and clk_zero:
+        zero = {r[0]: r for r in clk_zero}
+        cflags = flags + " --no-reshard --steps 2 --warmup 1"
+        with open(os.path.join(a.profiles, "bench_%s_gemm_clock.md" % wl), "w") as f:
+            f.write("# Clock and matrix-pipe occupancy of the long kernels of `bench.py %s`, on the bench's data and on zeros (%s)\n\n"
+                    "Two runs; each collects the cycle counter and the kernel trace together, so cycles / duration is the clock the "
+                    "chip held during that launch:\n\n    rocprofv3 --kernel-trace --pmc GRBM_GUI_ACTIVE SQ_VALU_MFMA_BUSY_CYCLES -d OUT/clk_random_c%d "
+                    "-o t --output-format csv -- python3 bench.py %s\n    rocprofv3 --kernel-trace --pmc GRBM_GUI_ACTIVE SQ_VALU_MFMA_BUSY_CYCLES "
+                    "-d OUT/clk_zero_c%d -o t --output-format csv -- python3 bench.py %s --zero-data\n\n`--zero-data` runs the same instruction "
+                    "streams on all-zero weights and inputs.  Medians over launches of 1 ms and more; clock = GRBM_GUI_ACTIVE / 8 / "
+                    "duration; MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / 1024 / (GRBM_GUI_ACTIVE / 8).  The nominal matrix peak (2.5 PFLOP/s) "
+                    "assumes 2.4 GHz; at the clock the chip holds on random data the pipes could deliver clock / 2.4 of it.\n\n"
+                    "| kernel | launches | median us (random) | clock GHz (random) | MFMA busy (random) | median us (zeros) | clock GHz (zeros) | "
+                    "MFMA busy (zeros) | zeros / random speed |\n|---|---|---|---|---|---|---|---|---|\n" % (cflags, wl, n, cflags, n, cflags))
+            for k, cnt, t, ghz, busy in clk_random:
+                if k in zero:
+                    z = zero[k]
+                    f.write("| `%s` | %d | %.0f | %.2f | %.1f %% | %.0f | %.2f | %.1f %% | %.2f |\n" % (k, cnt, t, ghz, busy, z[2], z[3], z[4], t / z[2]))
     fetch, write = read_counters(d("fetch")), read_counters(d("write"))
     if fetch:
         lines, total, (cf, cw, sf, sw) = traffic(fetch, write)
