@@ -103,7 +103,8 @@ int ss_destroy(ss_ctx* ctx);
 const char* ss_last_error(ss_ctx* ctx);   /* valid until the next failing call */
 
 /* Slices the shard's part out of the full layer and keeps a device copy
- * (the pointers may be released on return). */
+ * (the pointers may be released on return).  The gains are folded into the
+ * matrices that follow the norms (see ss_weights_read). */
 int ss_load_layer(ss_ctx*, const ss_shard_desc*, int layer, const ss_layer_weights* full);
 
 /* ---- weight re-sharding (paper section 4.1 "Dynamic Model Re-sharding",
@@ -136,6 +137,12 @@ int ss_load_layer(ss_ctx*, const ss_shard_desc*, int layer, const ss_layer_weigh
  * ss_weights_read: inspection (slow): slice `which` (SS_W_*) that the shard
  *   holds for `layer`, in [in_features, out_features] orientation as in
  *   ss_layer_weights but with the shard's columns / rows only, into host_out.
+ *   The matrices are returned as the library keeps them: RMSNorm is fused
+ *   into the products that follow it (norm(x) W = r (x (g W)) with r the
+ *   per-token factor rsqrt(mean(x^2) + eps), applied in the epilogue), so the
+ *   rows of wq, wk, wv carry the gains g1 and the rows of wg, wu the gains g2:
+ *   element [h, j] is w[h, j] * g[h], formed in fp32 and rounded once to the
+ *   model dtype.  g1, g2, wo and wd are kept as given.
  */
 enum { SS_W_G1 = 0, SS_W_Q = 1, SS_W_K = 2, SS_W_V = 3, SS_W_O = 4, SS_W_G2 = 5, SS_W_G = 6, SS_W_U = 7, SS_W_D = 8 };
 int ss_host_weights_put(ss_ctx*, int layer, const ss_layer_weights* full);

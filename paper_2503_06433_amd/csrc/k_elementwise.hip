@@ -62,6 +62,44 @@ hipError_t rmsnorm(int dt, const void* x, const void* g, void* out, int T, int H
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- RMSNorm statistics
+// r[t] = 1 / sqrt(mean(x[t,:]^2) + eps): the per-row factor of RMSNorm.  The gains are folded into the rows
+// of the weight matrix that follows and the factor is applied in that product's epilogue
+// (norm(x) W = r * (x (g W))), so the normalised activations are never written.  One read of x, T floats out.
+// One wave per row, four rows per block.
+template <typename T>
+__global__ __launch_bounds__(256) void row_scale_kernel(const T* __restrict__ x, float* __restrict__ r, int n_rows, int H,
+                                                        float eps) {
+    constexpr int V = VecOf<T>::N;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= n_rows) return;
+    const int lane = threadIdx.x & 63;
+    const T* row = x + (size_t)t * H;
+    float ss = 0.f;
+    if ((H % V) == 0) {
+        for (int i = lane * V; i < H; i += 64 * V) {
+            vec16 v = *reinterpret_cast<const vec16*>(row + i);
+            float f[V];
+            unpack16<T>(v, f);
+#pragma unroll
+            for (int j = 0; j < V; ++j) ss += f[j] * f[j];
+        }
+    } else {
+        for (int i = lane; i < H; i += 64) { float f = ldf(row + i); ss += f * f; }
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) r[t] = 1.0f / sqrtf(ss / (float)H + eps);
+}
+
+hipError_t row_scale(int dt, const void* x, float* r, int T, int H, float eps, hipStream_t s) {
+    if (T <= 0) return hipSuccess;
+    if (H <= 0) return hipErrorInvalidValue;
+    const unsigned grid = (unsigned)((T + 3) / 4);
+    if (dt == F32) row_scale_kernel<float><<<grid, 256, 0, s>>>((const float*)x, r, T, H, eps);
+    else row_scale_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t*)x, r, T, H, eps);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- SwiGLU (unfused)
 template <typename T>
 __global__ __launch_bounds__(256) void swiglu_kernel(const T* __restrict__ gu, T* __restrict__ out, int F) {
@@ -261,17 +299,27 @@ hipError_t rope_kvwrite(int dt, void* qkv, int n_q, int n_kv, const float* rope_
 }
 
 // ---------------------------------------------------------------- weight slicing
-// 32x32 tile transpose through LDS: src[K, ld] columns c0.. -> dst rows.
+// 32x32 tile transpose through LDS: src[K, ld] columns c0.. -> dst rows.  With `gain`, source row k is
+// multiplied by gain[k] on the way (the product of two stored values is formed in fp32 and rounded once to
+// the storage type): the RMSNorm gains folded into the matrix that consumes the normalised activations.
 template <typename T>
 __global__ __launch_bounds__(256) void slice_transpose_kernel(const T* __restrict__ src, int64_t ld, int K, int c0,
                                                               int n, T* __restrict__ dst, int blk, int blk_stride,
-                                                              int row_off) {
+                                                              int row_off, const T* __restrict__ gain) {
     __shared__ T tile[32][33];
     const int k0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
     for (int r = ty; r < 32; r += 8) {
         const int k = k0 + r, j = j0 + tx;
-        if (k < K && j < n) tile[r][tx] = src[(size_t)k * ld + c0 + j];
+        if (k < K && j < n) {
+            T v = src[(size_t)k * ld + c0 + j];
+            if (gain) {
+                T w;
+                stf(&w, ldf(&v) * ldf(gain + k));
+                v = w;
+            }
+            tile[r][tx] = v;
+        }
     }
     __syncthreads();
     for (int r = ty; r < 32; r += 8) {
@@ -284,17 +332,17 @@ __global__ __launch_bounds__(256) void slice_transpose_kernel(const T* __restric
 }
 
 hipError_t slice_transpose(int dt, const void* src, int64_t ld_src, int K, int c0, int n, void* dst, int blk,
-                           int blk_stride, int row_off, hipStream_t s) {
+                           int blk_stride, int row_off, hipStream_t s, const void* gain) {
     if (K <= 0 || n <= 0) return hipSuccess;
     if (blk <= 0) return hipErrorInvalidValue;
     dim3 grid((K + 31) / 32, (n + 31) / 32);
     if (grid.y > 65535) return hipErrorInvalidValue;
     if (dt == F32)
         slice_transpose_kernel<float><<<grid, 256, 0, s>>>((const float*)src, ld_src, K, c0, n, (float*)dst, blk,
-                                                           blk_stride, row_off);
+                                                           blk_stride, row_off, (const float*)gain);
     else
         slice_transpose_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t*)src, ld_src, K, c0, n, (bf16_t*)dst, blk,
-                                                            blk_stride, row_off);
+                                                            blk_stride, row_off, (const bf16_t*)gain);
     return hipGetLastError();
 }
 

@@ -11,7 +11,8 @@ using namespace ssk;
 template <typename T, int EPI>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__ A, int lda,
                                                            const T* __restrict__ Wt, void* __restrict__ Cv,
-                                                           int ldc, const T* __restrict__ R, int M, int N, int K) {
+                                                           int ldc, const T* __restrict__ R, int M, int N, int K,
+                                                           const float* __restrict__ RS) {
     constexpr int BM = 64, BN = 64, BK = 16;
     __shared__ float As[BK][BM + 4];
     __shared__ float Bs[BK][BN + 4];
@@ -50,6 +51,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__
             const int n = n0 + tx * 4 + j;
             if (n >= N) continue;
             float v = acc[i][j];
+            if (RS) v *= RS[m];
             if (EPI == EPI_RESIDUAL) v += ldf(R + (size_t)m * ldc + n);
             if (EPI == EPI_STORE_F32)
                 reinterpret_cast<float*>(Cv)[(size_t)m * ldc + n] = v;
@@ -61,37 +63,38 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__
 
 template <typename T>
 static hipError_t launch_generic(const void* A, int lda, const void* Wt, void* C, int ldc, const void* R, int M,
-                                 int N, int K, int epi, hipStream_t s) {
+                                 int N, int K, int epi, hipStream_t s, const float* rs) {
     dim3 grid((N + 63) / 64, (M + 63) / 64);
     if (grid.y > 65535) return hipErrorInvalidValue;
     const T* a = (const T*)A;
     const T* w = (const T*)Wt;
     const T* r = (const T*)R;
     switch (epi) {
-        case EPI_STORE: gemm_generic_kernel<T, EPI_STORE><<<grid, 256, 0, s>>>(a, lda, w, C, ldc, r, M, N, K); break;
+        case EPI_STORE: gemm_generic_kernel<T, EPI_STORE><<<grid, 256, 0, s>>>(a, lda, w, C, ldc, r, M, N, K, rs); break;
         case EPI_RESIDUAL:
             if (!R) return hipErrorInvalidValue;
-            gemm_generic_kernel<T, EPI_RESIDUAL><<<grid, 256, 0, s>>>(a, lda, w, C, ldc, r, M, N, K);
+            gemm_generic_kernel<T, EPI_RESIDUAL><<<grid, 256, 0, s>>>(a, lda, w, C, ldc, r, M, N, K, rs);
             break;
-        case EPI_STORE_F32: gemm_generic_kernel<T, EPI_STORE_F32><<<grid, 256, 0, s>>>(a, lda, w, C, ldc, r, M, N, K); break;
+        case EPI_STORE_F32: gemm_generic_kernel<T, EPI_STORE_F32><<<grid, 256, 0, s>>>(a, lda, w, C, ldc, r, M, N, K, rs); break;
         default: return hipErrorInvalidValue;   // the fused SwiGLU layout exists only for the MFMA kernel
     }
     return hipGetLastError();
 }
 
 hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int ldc, const void* R, int M, int N,
-                          int K, int epi, hipStream_t s, float* ws, size_t ws_bytes, int max_rounds);
+                          int K, int epi, hipStream_t s, float* ws, size_t ws_bytes, int max_rounds, const float* rs);
 bool gemm_mfma_supported(int M, int N, int K, int lda, int ldc, int epi);
 
 hipError_t gemm_nt(int dt, const void* A, int lda, const void* Wt, void* C, int ldc, const void* R, int M, int N,
-                   int K, int epi, bool force_generic, hipStream_t s, float* ws, size_t ws_bytes, int max_rounds) {
+                   int K, int epi, bool force_generic, hipStream_t s, float* ws, size_t ws_bytes, int max_rounds,
+                   const float* row_scale) {
     if (M <= 0 || N <= 0) return hipSuccess;
     if (K <= 0 || lda < K || !A || !Wt || !C) return hipErrorInvalidValue;
     if (dt == BF16 && !force_generic && gemm_mfma_supported(M, N, K, lda, ldc, epi))
-        return gemm_mfma_bf16(A, lda, Wt, C, ldc, R, M, N, K, epi, s, ws, ws_bytes, max_rounds);
+        return gemm_mfma_bf16(A, lda, Wt, C, ldc, R, M, N, K, epi, s, ws, ws_bytes, max_rounds, row_scale);
     if (epi == EPI_SWIGLU) return hipErrorInvalidValue;
-    if (dt == F32) return launch_generic<float>(A, lda, Wt, C, ldc, R, M, N, K, epi, s);
-    return launch_generic<bf16_t>(A, lda, Wt, C, ldc, R, M, N, K, epi, s);
+    if (dt == F32) return launch_generic<float>(A, lda, Wt, C, ldc, R, M, N, K, epi, s, row_scale);
+    return launch_generic<bf16_t>(A, lda, Wt, C, ldc, R, M, N, K, epi, s, row_scale);
 }
 
 }  // namespace SS_NS

@@ -48,7 +48,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
                                                                  const bf16_t* __restrict__ Wt,
                                                                  bf16_t* __restrict__ C, int ldc,
                                                                  const bf16_t* __restrict__ R, int M, int N, int K,
-                                                                 int tiles_m, int tiles_n, int per_xcd, int ksplit) {
+                                                                 int tiles_m, int tiles_n, int per_xcd, int ksplit,
+                                                                 const float* __restrict__ RS) {
     constexpr int NT = 64 * WM * WN;
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;   // 16-byte chunks per thread per slice
@@ -198,7 +199,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
                 for (int v = 0; v < 16; ++v) {
                     const int r = rbase + 8 * (v >> 2) + (v & 3);
                     if (r >= M) continue;
-                    const float g = acc[i][j][v], u = acc[i][j + 1][v];
+                    const float rs = RS ? RS[r] : 1.0f;
+                    const float g = acc[i][j][v] * rs, u = acc[i][j + 1][v] * rs;
                     C[(size_t)r * ldc + oc] = f2bf(swiglu_act(g, u));
                 }
             }
@@ -212,6 +214,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
                     const int r = rbase + 8 * (v >> 2) + (v & 3);
                     if (r >= M) continue;
                     float o = acc[i][j][v];
+                    if (RS) o *= RS[r];
                     if (EPI == EPI_RESIDUAL) o += bf2f(R[(size_t)r * ldc + c]);
                     C[(size_t)r * ldc + c] = f2bf(o);
                 }
@@ -277,7 +280,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
                                                                int ldc, const bf16_t* __restrict__ R, int M, int N,
                                                                int K, int tiles_m, int tiles_n, int sync_walk,
                                                                int cus_per_xcd, int it0, int max_it, int GM,
-                                                               int pf_dist) {
+                                                               int pf_dist, const float* __restrict__ RS) {
     constexpr int BM = 256, BN = 256;
     constexpr int STAGE = (BM + BN) * 128;       // bytes per ring stage
     constexpr int LPS = 16;                      // loads per wave per slice
@@ -474,6 +477,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
         constexpr int NP = 4 * NH;
         const int n_out = (EPI == EPI_SWIGLU) ? (N >> 1) : N;
         const int row_l = lane >> 3, g8 = lane & 7;
+        // RMSNorm factor of the token rows this lane holds products of (row 16 mt + lane % 16 of the wave's 128):
+        // norm(x) W = r * (x (g W)), the gains are in the weight rows already
+        float rsv[8];
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) {
+            int gr = m0 + wm * 128 + mt * 16 + l16;
+            gr = gr < M ? gr : M - 1;
+            rsv[mt] = (EPI != EPI_RESIDUAL && RS) ? RS[gr] : 1.0f;
+        }
         auto write_pass = [&](int p) {
             const int q = p / NH, h = p % NH;
 #pragma unroll
@@ -485,12 +497,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
                         const int gt = (c4 >> 1) * 4 + (c4 & 1);
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            const float g = acc[gt][2 * q + mt][e], u = acc[gt + 2][2 * q + mt][e];
+                            const float g = acc[gt][2 * q + mt][e] * rsv[2 * q + mt], u = acc[gt + 2][2 * q + mt][e] * rsv[2 * q + mt];
                             o[e] = swiglu_act(g, u);
                         }
                     } else {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = acc[4 * h + c4][2 * q + mt][e];
+                        for (int e = 0; e < 4; ++e) {
+                            o[e] = acc[4 * h + c4][2 * q + mt][e];
+                            if (EPI != EPI_RESIDUAL) o[e] *= rsv[2 * q + mt];
+                        }
                     }
                     const int row = mt * 16 + l16;
                     const int c = c4 * 4 + lk;
@@ -637,7 +652,8 @@ bool gemm_mfma_stream_supported(const void* C, const void* R, int ldc, int M, in
 // of another stream can only start at a launch boundary.  `max_rounds` > 0 cuts the walk into launches
 // of at most that many tiles per block, for callers that have latency-bound work on other streams.
 static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
-                                int N, int K, int epi, hipStream_t s, int max_rounds) {
+                                int N, int K, int epi, hipStream_t s, int max_rounds, const float* rs) {
+    if (rs && epi == EPI_RESIDUAL) return hipErrorInvalidValue;      // no caller scales a product that adds a residual
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     const long long n_tiles = (long long)tiles_m * tiles_n;
     if (n_tiles > (1ll << 30)) return hipErrorInvalidValue;
@@ -689,7 +705,7 @@ static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16
         }                                                                                                       \
         for (int it0 = 0; it0 < rounds_total; it0 += step)                                                      \
             kfn<<<grid, 256, STREAM_LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, sync_walk,      \
-                                              cus_per_xcd, it0, step, gm_rows, pf_dist);                        \
+                                              cus_per_xcd, it0, step, gm_rows, pf_dist, rs);                    \
     }
     switch (epi) {
         case EPI_STORE: SS_LAUNCH(EPI_STORE) break;
@@ -714,20 +730,23 @@ bool gemm_mfma_supported(int M, int N, int K, int lda, int ldc, int epi) {
 // Sums the split-K partials [S][M][N] and applies the epilogue.
 template <int EPI>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ P, int S, bf16_t* __restrict__ C,
-                                                            int ldc, const bf16_t* __restrict__ R, int M, int N) {
+                                                            int ldc, const bf16_t* __restrict__ R, int M, int N,
+                                                            const float* __restrict__ RS) {
     const int n_out = (EPI == EPI_SWIGLU) ? N / 2 : N;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (size_t)M * n_out) return;
     const int m = (int)(idx / n_out), j = (int)(idx % n_out);
     const size_t plane = (size_t)M * N;
+    const float rs = RS ? RS[m] : 1.0f;
     if (EPI == EPI_SWIGLU) {
         const int ng = (j >> 5) * 64 + (j & 31);
         float g = 0.f, u = 0.f;
         for (int s = 0; s < S; ++s) { g += P[s * plane + (size_t)m * N + ng]; u += P[s * plane + (size_t)m * N + ng + 32]; }
-        C[(size_t)m * ldc + j] = f2bf(swiglu_act(g, u));
+        C[(size_t)m * ldc + j] = f2bf(swiglu_act(g * rs, u * rs));
     } else {
         float o = 0.f;
         for (int s = 0; s < S; ++s) o += P[s * plane + (size_t)m * N + j];
+        o *= rs;
         if (EPI == EPI_RESIDUAL) o += bf2f(R[(size_t)m * ldc + j]);
         if (EPI == EPI_STORE_F32) reinterpret_cast<float*>(C)[(size_t)m * ldc + j] = o;
         else C[(size_t)m * ldc + j] = f2bf(o);
@@ -736,7 +755,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 
 template <int BM, int BN, int WM, int WN>
 static hipError_t launch_cfg(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
-                             int N, int K, int epi, hipStream_t s, int ksplit = 1, float* ws = nullptr) {
+                             int N, int K, int epi, hipStream_t s, int ksplit = 1, float* ws = nullptr,
+                             const float* rs = nullptr) {
     constexpr int NT = 64 * WM * WN;
     constexpr size_t LDS = (size_t)2 * (BM + BN) * 128;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
@@ -754,26 +774,28 @@ static hipError_t launch_cfg(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t*
             if (e != hipSuccess) return e;                                                                      \
             attr_set = true;                                                                                    \
         }                                                                                                       \
-        kfn<<<grid, NT, LDS, s>>>(A, lda, Wt, OUT, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd, ksplit);         \
+        kfn<<<grid, NT, LDS, s>>>(A, lda, Wt, OUT, ldc, R, M, N, K, tiles_m, tiles_n, per_xcd, ksplit, rs);     \
     }
     if (ksplit > 1) {
         SS_LAUNCH(EPI_PARTIAL, reinterpret_cast<bf16_t*>(ws))
         const size_t n_out = (size_t)M * (epi == EPI_SWIGLU ? N / 2 : N);
         const unsigned rgrid = (unsigned)((n_out + 255) / 256);
         switch (epi) {
-            case EPI_STORE: splitk_reduce_kernel<EPI_STORE><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N); break;
+            case EPI_STORE: splitk_reduce_kernel<EPI_STORE><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N, rs); break;
             case EPI_RESIDUAL:
                 if (!R) return hipErrorInvalidValue;
-                splitk_reduce_kernel<EPI_RESIDUAL><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N);
+                splitk_reduce_kernel<EPI_RESIDUAL><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N, rs);
                 break;
-            case EPI_SWIGLU: splitk_reduce_kernel<EPI_SWIGLU><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N); break;
-            case EPI_STORE_F32: splitk_reduce_kernel<EPI_STORE_F32><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N); break;
+            case EPI_SWIGLU: splitk_reduce_kernel<EPI_SWIGLU><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N, rs); break;
+            case EPI_STORE_F32: splitk_reduce_kernel<EPI_STORE_F32><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N, rs); break;
             default: return hipErrorInvalidValue;
         }
         return hipGetLastError();
     }
     switch (epi) {
-        case EPI_STORE_F32: SS_LAUNCH(EPI_PARTIAL, C) break;      // one K range: plane 0 of the partials is the fp32 result
+        case EPI_STORE_F32:                                       // one K range: plane 0 of the partials is the fp32 result
+            if (rs) return hipErrorInvalidValue;
+            SS_LAUNCH(EPI_PARTIAL, C) break;
         case EPI_STORE: SS_LAUNCH(EPI_STORE, C) break;
         case EPI_RESIDUAL:
             if (!R) return hipErrorInvalidValue;
@@ -786,7 +808,7 @@ static hipError_t launch_cfg(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t*
 }
 
 hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int ldc, const void* R, int M, int N,
-                          int K, int epi, hipStream_t s, float* ws, size_t ws_bytes, int max_rounds) {
+                          int K, int epi, hipStream_t s, float* ws, size_t ws_bytes, int max_rounds, const float* rs) {
     const bf16_t* a = (const bf16_t*)A;
     const bf16_t* w = (const bf16_t*)Wt;
     bf16_t* c = (bf16_t*)C;
@@ -796,7 +818,7 @@ hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int l
     // (partials in fp32, summed by a small second kernel).
     const long long big = (long long)((M + 255) / 256) * ((N + 255) / 256);
     if (big >= 256 && epi != EPI_STORE_F32 && gemm_mfma_stream_supported(C, R, ldc, M, N, K, lda, epi))
-        return launch_stream(a, lda, w, c, ldc, r, M, N, K, epi, s, max_rounds);
+        return launch_stream(a, lda, w, c, ldc, r, M, N, K, epi, s, max_rounds, rs);
     const long long mid = (long long)((M + 127) / 128) * ((N + 127) / 128);
     // split K until every CU has a block, but only while the fp32 partials (8*S*M*N bytes written and
     // read back) stay below the weight bytes (2*N*K) they help to stream: S <= K / (4 M)
@@ -804,7 +826,7 @@ hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int l
     while (split < 8 && mid * split < 256 && (K / 64) % (split * 2) == 0 && (long long)(split * 2) * 4 * M <= K &&
            (size_t)(split * 2) * M * N * sizeof(float) <= ws_bytes && ws)
         split *= 2;
-    return launch_cfg<128, 128, 2, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s, split, ws);
+    return launch_cfg<128, 128, 2, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s, split, ws, rs);
 }
 
 }  // namespace SS_NS

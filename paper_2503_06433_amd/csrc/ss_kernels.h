@@ -115,13 +115,21 @@ using namespace ssk;
 // The large-output bf16 kernel runs as persistent blocks that own their CUs until the launch is done;
 // max_rounds > 0 cuts it into launches of at most that many output tiles per block, so that kernels of
 // other streams (the KV movers' repack kernels) get the chip at the boundaries; 0 = one launch.
+// row_scale (optional, M floats): row m of the product is multiplied by row_scale[m] before the epilogue's
+// activation or store: the RMSNorm factor of token m when A holds the raw activations and the gains are
+// folded into the weight rows.  Not combined with EPI_RESIDUAL or EPI_STORE_F32 by the large-output and
+// fp32-output kernels (refused there).
 hipError_t gemm_nt(int dt, const void* A, int lda, const void* Wt, void* C, int ldc,
                    const void* R, int M, int N, int K, int epi, bool force_generic,
-                   hipStream_t s, float* ws = nullptr, size_t ws_bytes = 0, int max_rounds = 0);
+                   hipStream_t s, float* ws = nullptr, size_t ws_bytes = 0, int max_rounds = 0,
+                   const float* row_scale = nullptr);
 
 // out[t,:] = x[t,:] * rsqrt(mean(x[t,:]^2) + eps) * g
 hipError_t rmsnorm(int dt, const void* x, const void* g, void* out, int T, int H, float eps,
                    hipStream_t s);
+
+// r[t] = rsqrt(mean(x[t,:]^2) + eps)
+hipError_t row_scale(int dt, const void* x, float* r, int T, int H, float eps, hipStream_t s);
 
 // out[t, j] = silu(gu[t, j]) * gu[t, F + j]   (unfused form used by the generic GEMM path)
 hipError_t swiglu(int dt, const void* gu, void* out, int T, int F, hipStream_t s);
@@ -156,9 +164,11 @@ hipError_t kv_scatter(int dt, void* const* k_pools, void* const* v_pools, int n_
 
 // Weight slicing at load time: column j (0 <= j < n) of src[K, ld_src], taken from
 // column c0 + j, becomes row  (j / blk) * blk_stride + (j % blk) + row_off  of
-// dst[*, K] (K contiguous).  blk = n, row_off = 0 gives the plain transpose.
+// dst[*, K] (K contiguous).  blk = n, row_off = 0 gives the plain transpose.  With `gain` (K values of the
+// model dtype) element [k, j] is multiplied by gain[k] and rounded once to the storage type.
 hipError_t slice_transpose(int dt, const void* src, int64_t ld_src, int K, int c0, int n,
-                           void* dst, int blk, int blk_stride, int row_off, hipStream_t s);
+                           void* dst, int blk, int blk_stride, int row_off, hipStream_t s,
+                           const void* gain = nullptr);
 
 // out[r] = argmax of logits[r, 0..V), lowest index on ties (greedy decoding).
 hipError_t argmax_rows(const float* logits, int n, int V, int32_t* out, hipStream_t s);

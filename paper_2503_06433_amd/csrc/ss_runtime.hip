@@ -288,7 +288,7 @@ struct ss_ctx {
     std::string err;
     std::map<DescKey, Shard*> shards;
     float* d_rope = nullptr;
-    DevBuf ws_h, ws_qkv, ws_attn, ws_gu, ws_act, ws_x1, ws_scratch, ws_splitk;
+    DevBuf ws_h, ws_qkv, ws_attn, ws_gu, ws_act, ws_x1, ws_scratch, ws_splitk, ws_rs;
     MetaSlot meta[4];
     int meta_next = 0;
     void *d_embed = nullptr, *d_gf = nullptr, *d_wlm_t = nullptr;
@@ -797,7 +797,7 @@ int run_attn_phase(ss_ctx* c, Shard* s, int ll, const ss_batch* b, bool decode, 
     if (rc) return rc;
     const int T = ms->bm.T, H = m.hidden, d = m.head_dim;
     const int nqkv = (s->nq_l + 2 * s->nkv_l) * d;
-    if ((rc = ensure_buf(c, c->ws_h, (size_t)T * H * c->es))) return rc;
+    if ((rc = ensure_buf(c, c->ws_rs, (size_t)T * sizeof(float)))) return rc;
     if ((rc = ensure_buf(c, c->ws_qkv, (size_t)T * nqkv * c->es))) return rc;
     if ((rc = ensure_buf(c, c->ws_attn, (size_t)T * s->nq_l * d * c->es))) return rc;
     if (decode) {
@@ -806,14 +806,18 @@ int run_attn_phase(ss_ctx* c, Shard* s, int ll, const ss_batch* b, bool decode, 
     }
     if (c->dt != SS_F32 && T <= 2048 && (rc = ensure_buf(c, c->ws_splitk, (size_t)128 << 20))) return rc;
     const ssk::KvLayer kv = kv_layer(c, s, ll);
+    // RMSNorm is not a pass of its own: the gains are folded into the rows of Wqkv at load time, the product
+    // runs on the raw activations and its epilogue multiplies every token row by rsqrt(mean(x^2) + eps), which
+    // a read-only pass over x provides (T floats)
     {
         ProfScope ps(c, 4, st);
-        K_TRY(c, SSK_CALL(c, rmsnorm, x_in, w.g1, c->ws_h.p, T, H, m.rms_eps, st));
+        K_TRY(c, SSK_CALL(c, row_scale, x_in, (float*)c->ws_rs.p, T, H, m.rms_eps, st));
     }
     {
         ProfScope ps(c, 0, st);
-        K_TRY(c, SSK_CALL(c, gemm_nt, c->ws_h.p, H, w.wqkv_t, c->ws_qkv.p, nqkv, nullptr, T, nqkv, H, ssk::EPI_STORE,
-                              c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
+        K_TRY(c, SSK_CALL(c, gemm_nt, x_in, H, w.wqkv_t, c->ws_qkv.p, nqkv, nullptr, T, nqkv, H, ssk::EPI_STORE,
+                              c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds,
+                              (const float*)c->ws_rs.p));
     }
     {
         ProfScope ps(c, 4, st);
@@ -841,23 +845,24 @@ int run_mlp_phase(ss_ctx* c, Shard* s, int ll, int T, const void* x1, void* out,
     const LayerW& w = s->w[ll];
     const int H = m.hidden, F = s->f_l;
     int rc;
-    if ((rc = ensure_buf(c, c->ws_h, (size_t)T * H * c->es))) return rc;
+    if ((rc = ensure_buf(c, c->ws_rs, (size_t)T * sizeof(float)))) return rc;
     if ((rc = ensure_buf(c, c->ws_act, (size_t)T * F * c->es))) return rc;
     if (c->dt != SS_F32 && T <= 2048 && (rc = ensure_buf(c, c->ws_splitk, (size_t)128 << 20))) return rc;
     {
         ProfScope ps(c, 4, st);
-        K_TRY(c, SSK_CALL(c, rmsnorm, x1, w.g2, c->ws_h.p, T, H, m.rms_eps, st));
+        K_TRY(c, SSK_CALL(c, row_scale, x1, (float*)c->ws_rs.p, T, H, m.rms_eps, st));      // as in the attention phase
     }
     if (w.gu_interleaved) {
         ProfScope ps(c, 0, st);
-        K_TRY(c, SSK_CALL(c, gemm_nt, c->ws_h.p, H, w.wgu_t, c->ws_act.p, F, nullptr, T, 2 * F, H, ssk::EPI_SWIGLU,
-                              false, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
+        K_TRY(c, SSK_CALL(c, gemm_nt, x1, H, w.wgu_t, c->ws_act.p, F, nullptr, T, 2 * F, H, ssk::EPI_SWIGLU,
+                              false, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds, (const float*)c->ws_rs.p));
     } else {
         if ((rc = ensure_buf(c, c->ws_gu, (size_t)T * 2 * F * c->es))) return rc;
         {
             ProfScope ps(c, 0, st);
-            K_TRY(c, SSK_CALL(c, gemm_nt, c->ws_h.p, H, w.wgu_t, c->ws_gu.p, 2 * F, nullptr, T, 2 * F, H,
-                                  ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds));
+            K_TRY(c, SSK_CALL(c, gemm_nt, x1, H, w.wgu_t, c->ws_gu.p, 2 * F, nullptr, T, 2 * F, H,
+                                  ssk::EPI_STORE, c->force_generic, st, (float*)c->ws_splitk.p, c->ws_splitk.cap, c->gemm_rounds,
+                                  (const float*)c->ws_rs.p));
         }
         ProfScope ps(c, 4, st);
         K_TRY(c, SSK_CALL(c, swiglu, c->ws_gu.p, c->ws_act.p, T, F, st));
@@ -1282,14 +1287,15 @@ int upload_matrix(ss_ctx* c, const void* src, int location, size_t bytes, void**
 }
 
 // dst rows <- columns [c0, c0+n) of src[K, ld] (one full matrix staged at a time)
+// (`gain`: device vector of K values folded into the rows, or null)
 int slice_into(ss_ctx* c, const void* src, int location, size_t src_rows, size_t ld, size_t row0, int K, int c0, int n,
-               void* dst, int blk, int blk_stride, int row_off) {
+               void* dst, int blk, int blk_stride, int row_off, const void* gain = nullptr) {
     void* tmp = nullptr;
     const void* dsrc = nullptr;
     int rc = upload_matrix(c, src, location, src_rows * ld * c->es, &tmp, &dsrc);
     if (rc) return rc;
     const uint8_t* base = (const uint8_t*)dsrc + row0 * ld * c->es;
-    hipError_t e = SSK_CALL(c, slice_transpose, base, (int64_t)ld, K, c0, n, dst, blk, blk_stride, row_off, 0);
+    hipError_t e = SSK_CALL(c, slice_transpose, base, (int64_t)ld, K, c0, n, dst, blk, blk_stride, row_off, 0, gain);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (tmp) (void)hipFree(tmp);
     if (e != hipSuccess) return fail(c, SS_EHIP, "weight slicing: %s", hipGetErrorString(e));
@@ -1439,12 +1445,13 @@ int reload_layer(ss_ctx* c, Shard* s, int ll) {
     HIP_TRY(c, hipMemcpyAsync(L.g1, hl.base + hl.off[SS_W_G1], (size_t)H * es, hipMemcpyHostToDevice, ws));
     HIP_TRY(c, hipMemcpyAsync(L.g2, hl.base + hl.off[SS_W_G2], (size_t)H * es, hipMemcpyHostToDevice, ws));
     // columns [c0, c0+n) of the host matrix [K, ld] -> dense staging [K, n] -> dst rows
-    auto cols = [&](int which, int K, size_t ld, size_t c0, int n, void* dst, int blk, int blk_stride, int row_off) -> int {
+    auto cols = [&](int which, int K, size_t ld, size_t c0, int n, void* dst, int blk, int blk_stride, int row_off,
+                    const void* gain) -> int {
         const uint8_t* src = hl.base + hl.off[which] + c0 * es;
         if ((size_t)n == ld) HIP_TRY(c, hipMemcpyAsync(c->w_staging.p, src, (size_t)K * n * es, hipMemcpyHostToDevice, ws));
         else HIP_TRY(c, hipMemcpy2DAsync(c->w_staging.p, (size_t)n * es, src, ld * es, (size_t)n * es, (size_t)K,
                                          hipMemcpyHostToDevice, ws));
-        K_TRY(c, SSK_CALL(c, slice_transpose, c->w_staging.p, (int64_t)n, K, 0, n, dst, blk, blk_stride, row_off, ws));
+        K_TRY(c, SSK_CALL(c, slice_transpose, c->w_staging.p, (int64_t)n, K, 0, n, dst, blk, blk_stride, row_off, ws, gain));
         return SS_OK;
     };
     // rows [r0, r0+K) of the host matrix [*, n] (contiguous) -> staging [K, n] -> dst = its transpose
@@ -1455,17 +1462,18 @@ int reload_layer(ss_ctx* c, Shard* s, int ll) {
         return SS_OK;
     };
     uint8_t* qkv = (uint8_t*)L.wqkv_t;
-    if ((rc = cols(SS_W_Q, H, qd, (size_t)s->q0 * dh, nq, qkv, nq, nq, 0))) return rc;
-    if ((rc = cols(SS_W_K, H, kd, (size_t)s->g0 * dh, nkv, qkv + (size_t)nq * H * es, nkv, nkv, 0))) return rc;
-    if ((rc = cols(SS_W_V, H, kd, (size_t)s->g0 * dh, nkv, qkv + (size_t)(nq + nkv) * H * es, nkv, nkv, 0))) return rc;
+    // gains folded as in ss_load_layer (they were copied on this stream just above)
+    if ((rc = cols(SS_W_Q, H, qd, (size_t)s->q0 * dh, nq, qkv, nq, nq, 0, L.g1))) return rc;
+    if ((rc = cols(SS_W_K, H, kd, (size_t)s->g0 * dh, nkv, qkv + (size_t)nq * H * es, nkv, nkv, 0, L.g1))) return rc;
+    if ((rc = cols(SS_W_V, H, kd, (size_t)s->g0 * dh, nkv, qkv + (size_t)(nq + nkv) * H * es, nkv, nkv, 0, L.g1))) return rc;
     if ((rc = rows(SS_W_O, (size_t)s->q0 * dh, nq, H, L.wo_t))) return rc;
     L.gu_interleaved = (c->dt != SS_F32) && !c->force_generic && (F % 32 == 0) && (H % 64 == 0);
     if (L.gu_interleaved) {
-        if ((rc = cols(SS_W_G, H, m.ffn, s->f0, F, L.wgu_t, 32, 64, 0))) return rc;
-        if ((rc = cols(SS_W_U, H, m.ffn, s->f0, F, L.wgu_t, 32, 64, 32))) return rc;
+        if ((rc = cols(SS_W_G, H, m.ffn, s->f0, F, L.wgu_t, 32, 64, 0, L.g2))) return rc;
+        if ((rc = cols(SS_W_U, H, m.ffn, s->f0, F, L.wgu_t, 32, 64, 32, L.g2))) return rc;
     } else {
-        if ((rc = cols(SS_W_G, H, m.ffn, s->f0, F, L.wgu_t, F, F, 0))) return rc;
-        if ((rc = cols(SS_W_U, H, m.ffn, s->f0, F, L.wgu_t, F, F, F))) return rc;
+        if ((rc = cols(SS_W_G, H, m.ffn, s->f0, F, L.wgu_t, F, F, 0, L.g2))) return rc;
+        if ((rc = cols(SS_W_U, H, m.ffn, s->f0, F, L.wgu_t, F, F, F, L.g2))) return rc;
     }
     if ((rc = rows(SS_W_D, (size_t)s->f0, F, H, L.wd_t))) return rc;
     L.loaded = true;
@@ -1600,7 +1608,7 @@ int ss_destroy(ss_ctx* c) {
         if (s->w_ready) (void)hipEventDestroy(s->w_ready);
         delete s;
     }
-    for (DevBuf* b : {&c->ws_h, &c->ws_qkv, &c->ws_attn, &c->ws_gu, &c->ws_act, &c->ws_x1, &c->ws_scratch, &c->ws_splitk})
+    for (DevBuf* b : {&c->ws_h, &c->ws_qkv, &c->ws_attn, &c->ws_gu, &c->ws_act, &c->ws_x1, &c->ws_scratch, &c->ws_splitk, &c->ws_rs})
         if (b->p) (void)hipFree(b->p);
     for (auto& ms : c->meta) {
         if (ms.host) (void)hipHostFree(ms.host);
@@ -1662,19 +1670,20 @@ int ss_load_layer(ss_ctx* c, const ss_shard_desc* d, int layer, const ss_layer_w
     if ((rc = copy_vec(c, w->g2, w->location, H, &L.g2))) return rc;
     uint8_t* qkv = (uint8_t*)L.wqkv_t;
     const size_t qd = (size_t)m.n_q_heads * dh, kd = (size_t)m.n_kv_heads * dh;
-    if ((rc = slice_into(c, w->wq, w->location, H, qd, 0, H, s->q0 * dh, nq, qkv, nq, nq, 0))) return rc;
-    if ((rc = slice_into(c, w->wk, w->location, H, kd, 0, H, s->g0 * dh, nkv, qkv + (size_t)nq * H * es, nkv, nkv, 0))) return rc;
-    if ((rc = slice_into(c, w->wv, w->location, H, kd, 0, H, s->g0 * dh, nkv, qkv + (size_t)(nq + nkv) * H * es, nkv, nkv, 0))) return rc;
+    // the RMSNorm gains are folded into the matrices that read the normalised activations (Q, K, V: g1; gate, up: g2)
+    if ((rc = slice_into(c, w->wq, w->location, H, qd, 0, H, s->q0 * dh, nq, qkv, nq, nq, 0, L.g1))) return rc;
+    if ((rc = slice_into(c, w->wk, w->location, H, kd, 0, H, s->g0 * dh, nkv, qkv + (size_t)nq * H * es, nkv, nkv, 0, L.g1))) return rc;
+    if ((rc = slice_into(c, w->wv, w->location, H, kd, 0, H, s->g0 * dh, nkv, qkv + (size_t)(nq + nkv) * H * es, nkv, nkv, 0, L.g1))) return rc;
     // Wo rows of this shard's heads -> Wo^T [H, nq]
     if ((rc = slice_into(c, w->wo, w->location, qd, H, (size_t)s->q0 * dh, nq, 0, H, L.wo_t, H, H, 0))) return rc;
     // gate / up: interleaved in blocks of 32 rows when the fused SwiGLU epilogue can run
     L.gu_interleaved = (c->dt != SS_F32) && !c->force_generic && (F % 32 == 0) && (H % 64 == 0);
     if (L.gu_interleaved) {
-        if ((rc = slice_into(c, w->wg, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, 32, 64, 0))) return rc;
-        if ((rc = slice_into(c, w->wu, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, 32, 64, 32))) return rc;
+        if ((rc = slice_into(c, w->wg, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, 32, 64, 0, L.g2))) return rc;
+        if ((rc = slice_into(c, w->wu, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, 32, 64, 32, L.g2))) return rc;
     } else {
-        if ((rc = slice_into(c, w->wg, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, F, F, 0))) return rc;
-        if ((rc = slice_into(c, w->wu, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, F, F, F))) return rc;
+        if ((rc = slice_into(c, w->wg, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, F, F, 0, L.g2))) return rc;
+        if ((rc = slice_into(c, w->wu, w->location, H, m.ffn, 0, H, s->f0, F, L.wgu_t, F, F, F, L.g2))) return rc;
     }
     if ((rc = slice_into(c, w->wd, w->location, m.ffn, H, (size_t)s->f0, F, 0, H, L.wd_t, H, H, 0))) return rc;
     L.loaded = true;

@@ -116,3 +116,32 @@ def staging_from_logical(content_by_seq, dtype):
     """content_by_seq: list of raw arrays [n_layers_local, 2, heads_local, s, d] ->
     one flat raw staging array in the export/import layout (sequences back to back)."""
     return np.concatenate([np.ascontiguousarray(c).reshape(-1) for c in content_by_seq])
+
+
+def stored_form(ref, dtype):
+    """What the library keeps (and ss_weights_read returns) for a shard whose raw slices are `ref` (name -> storage
+    array, matrices in [in, out] orientation): the RMSNorm gains are folded into the rows of the matrices that
+    read normalised activations (wq, wk, wv: g1; wg, wu: g2).  Element [h, j] * gain[h] is formed in float32
+    (exact for the 16-bit types: the factors have at most 11 significant bits each) and rounded once, to nearest
+    even, to the storage type; everything else is kept as it is."""
+    def f32(a):
+        if dtype == wl.F32:
+            return np.asarray(a, dtype=np.float32)
+        if dtype == wl.F16:
+            return np.ascontiguousarray(a, dtype=np.uint16).view(np.float16).astype(np.float32)
+        return wl.bf16_to_f32(a)
+
+    def store(a):
+        if dtype == wl.F32:
+            return a
+        if dtype == wl.F16:
+            return a.astype(np.float16).view(np.uint16)
+        return wl.bf16_bits(a)
+
+    out = dict(ref)
+    for names, gain in ((("wq", "wk", "wv"), "g1"), (("wg", "wu"), "g2")):
+        g = f32(ref[gain]).reshape(-1, 1)
+        for n in names:
+            w = f32(ref[n])
+            out[n] = store((w.reshape(g.shape[0], -1) * g).astype(np.float32)).reshape(np.shape(ref[n]))
+    return out

@@ -316,6 +316,7 @@ def test_config3_weight_reshard_pp_layer_to_tp4_shard_bit_exact():
     the CPU copy; every tensor the shard then holds is compared bit for bit with the oracle's slice."""
     from oracle import weight_shard as ows
     from paper_2503_06433_amd.binding import W_NAMES
+    from paper_2503_06433_amd.harness import stored_form
     cfg = wl.config3().cfg
     _, raws = wl.make_layer_weights(cfg, 3301)
     ctx = make_context(cfg, pages=8)
@@ -324,7 +325,7 @@ def test_config3_weight_reshard_pp_layer_to_tp4_shard_bit_exact():
     ctx.reshard_weights(None, stage)
     ctx.reshard_weights(stage, shard)
     assert ctx.weights_shard_bytes(shard) == ows.reload_elems(cfg, 4, 0, 1) * 2
-    ref = ows.shard_weights(cfg, raws, 4, 2)
+    ref = stored_form(ows.shard_weights(cfg, raws, 4, 2), cfg.dtype)      # gains folded into wq, wk, wv, wg, wu
     for which, name in enumerate(W_NAMES):
         got = ctx.weights_read(shard, 0, which, ref[name].size)
         assert np.array_equal(got, ref[name].reshape(-1)), name

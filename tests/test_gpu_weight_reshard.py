@@ -20,7 +20,7 @@ if torch.cuda.is_available():
     import paper_2503_06433_amd as ss
     from paper_2503_06433_amd.binding import W_NAMES
     from paper_2503_06433_amd.harness import (make_context, to_device, to_f64, to_raw, empty_like_acts, rel_err, tol,
-                                              pp_desc, tp_desc)
+                                              pp_desc, tp_desc, stored_form)
 
 SHAPES = {
     "mha_d128": dict(hidden=512, n_q_heads=4, n_kv_heads=4, head_dim=128, ffn=1024),      # gate/up interleaved layout
@@ -39,9 +39,10 @@ def _model(cfg, seed):
 
 
 def _check_shard(ctx, cfg, raws, desc, k, i):
-    """Every tensor the shard holds == the oracle's slice of the raw storage bits."""
+    """Every tensor the shard holds == the oracle's slice of the raw storage bits (the matrices behind a norm
+    with that norm's gains folded into their rows, see harness.stored_form)."""
     for l in range(desc.layer_begin, desc.layer_end):
-        ref = ows.shard_weights(cfg, raws[l], k, i)
+        ref = stored_form(ows.shard_weights(cfg, raws[l], k, i), cfg.dtype)
         for which, name in enumerate(W_NAMES):
             got = ctx.weights_read(desc, l, which, ref[name].size)
             assert np.array_equal(got, ref[name].reshape(-1)), (l, name)
