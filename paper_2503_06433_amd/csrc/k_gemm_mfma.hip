@@ -97,7 +97,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
         b_src[i] = Wt + (size_t)gr * K + kc * 8;
         b_dst[i] = lds_chunk_off(row, kc);
     }
-    u32x4_t a_reg[A_CH], b_reg[B_CH];
+    // two register sets: the loads of two slices are in flight while a third is multiplied.  At decode sizes the
+    // kernel does little but stream weights, and what bounds a block's share of the bandwidth is the bytes it has
+    // in flight (one slice = 16 KB of weights per block was half of what the loaded memory system needs)
+    u32x4_t a_reg[2][A_CH], b_reg[2][B_CH];
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -112,19 +115,19 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
     const int kt0 = blockIdx.y * nk;
     const int lrow = lane & 31, lgrp = lane >> 5;
 
-    auto fetch = [&](int kt) {
+    auto fetch = [&](int kt, u32x4_t* ar, u32x4_t* br) {
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const u32x4_t*>(a_src[i] + (size_t)(kt0 + kt) * 64);
+        for (int i = 0; i < A_CH; ++i) ar[i] = *reinterpret_cast<const u32x4_t*>(a_src[i] + (size_t)(kt0 + kt) * 64);
 #pragma unroll
-        for (int i = 0; i < B_CH; ++i) b_reg[i] = *reinterpret_cast<const u32x4_t*>(b_src[i] + (size_t)(kt0 + kt) * 64);
+        for (int i = 0; i < B_CH; ++i) br[i] = *reinterpret_cast<const u32x4_t*>(b_src[i] + (size_t)(kt0 + kt) * 64);
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int buf, const u32x4_t* ar, const u32x4_t* br) {
         uint8_t* An = As + buf * BM * 128;
         uint8_t* Bn = Bs + buf * BN * 128;
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4_t*>(An + a_dst[i]) = a_reg[i];
+        for (int i = 0; i < A_CH; ++i) *reinterpret_cast<u32x4_t*>(An + a_dst[i]) = ar[i];
 #pragma unroll
-        for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4_t*>(Bn + b_dst[i]) = b_reg[i];
+        for (int i = 0; i < B_CH; ++i) *reinterpret_cast<u32x4_t*>(Bn + b_dst[i]) = br[i];
     };
     // Fragments of k-step ks+1 are read from LDS while the MFMAs of k-step ks run
     // (two register sets); scheduling barriers keep the compiler from sinking the
@@ -154,16 +157,26 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
         }
     };
 
-    fetch(0);
-    stash(0);
+    // slice kt is multiplied out of LDS stage kt & 1 while slice kt + 1 (register set (kt + 1) & 1) and slice
+    // kt + 2 (set kt & 1, free since slice kt was stashed) are on their way; the loop is unrolled by two so that
+    // the sets are named at compile time
+    fetch(0, a_reg[0], b_reg[0]);
+    if (nk > 1) fetch(1, a_reg[1], b_reg[1]);
+    stash(0, a_reg[0], b_reg[0]);
     __syncthreads();
-    for (int kt = 0; kt + 1 < nk; ++kt) {
-        fetch(kt + 1);          // global loads of the next slice fly while this one is multiplied
+    auto step = [&](int kt, u32x4_t* a_same, u32x4_t* b_same, u32x4_t* a_next, u32x4_t* b_next) {
+        if (kt + 2 < nk) fetch(kt + 2, a_same, b_same);
         __builtin_amdgcn_sched_barrier(0);
         multiply(kt & 1);
-        stash((kt + 1) & 1);
+        stash((kt + 1) & 1, a_next, b_next);
         __syncthreads();
+    };
+    int kt = 0;
+    for (; kt + 2 < nk; kt += 2) {
+        step(kt, a_reg[0], b_reg[0], a_reg[1], b_reg[1]);
+        step(kt + 1, a_reg[1], b_reg[1], a_reg[0], b_reg[0]);
     }
+    if (kt + 1 < nk) step(kt, a_reg[0], b_reg[0], a_reg[1], b_reg[1]);
     multiply((nk - 1) & 1);
 
     // ---- epilogue
