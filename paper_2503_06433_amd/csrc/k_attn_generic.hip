@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
             const float pj = __expf(s[jj] - mx);
             l += pj;
 #pragma unroll
-            for (int e = 0; e < DS; ++e) acc[e] = fmaf(pj, Vs[sub * DS + e][vslot(jj)], acc[e]);
+            for (int e = 0; e < DS; ++e) acc[e] = fmaf(pj, Vs[sub * DS + e][vpos(jj, sub * DS + e)], acc[e]);
         }
         m = mx;
         __syncthreads();

@@ -148,9 +148,11 @@ __global__ __launch_bounds__(256) void attn_prefill_mfma_kernel(const bf16_t* __
             }
         }
         // ---- O^T += V^T P^T
-        // the page keeps each row as [0-3, 8-11, 4-7, 12-15]: lane group g2's eight tokens are 16 contiguous bytes
-        const bf16_t* vA = v_pool + (size_t)pA * page_elems + head_off + (size_t)lq * 16 + 8 * g2;
-        const bf16_t* vB = v_pool + (size_t)pB * page_elems + head_off + (size_t)lq * 16 + 8 * g2;
+        // the page keeps each row as [0-3, 8-11, 4-7, 12-15] (halves swapped in rows with bit 3 of the row index set,
+        // see vpos): lane group g2's eight tokens are 16 contiguous bytes
+        const int vhalf = g2 ^ ((lq >> 3) & 1);
+        const bf16_t* vA = v_pool + (size_t)pA * page_elems + head_off + (size_t)lq * 16 + 8 * vhalf;
+        const bf16_t* vB = v_pool + (size_t)pB * page_elems + head_off + (size_t)lq * 16 + 8 * vhalf;
 #pragma unroll
         for (int u = 0; u < DT; ++u) {
             Frag va, vb;
@@ -386,7 +388,7 @@ __global__ __launch_bounds__(512) void attn_prefill_lds_kernel(const bf16_t* __r
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) s0 = SS_MFMA_32x32x16(ka[ks].v, qf[ks].v, s0, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        const uint8_t* vp = st + KBYTES + lq * 32 + g2 * 16;
+        const uint8_t* vp = st + KBYTES + lq * 32 + (g2 ^ ((lq >> 3) & 1)) * 16;      // halves swapped in rows 8-15 of 16 (vpos)
         Frag va[DT], vb[DT];
 #pragma unroll
         for (int u = 0; u < DT; ++u) {
@@ -529,8 +531,9 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
     const int32_t* pt = bm.page_tables + (size_t)sq * bm.pt_stride + page0;
     const size_t page_elems = (size_t)n_kv * 16 * D;
     const size_t head_off = (size_t)g * 16 * D;
-    // tokens 4*g4 .. 4*g4+3 sit at piece ((g4 & 1) << 1 | g4 >> 1) of a V^T row (see vslot)
-    const int vpiece = ((g4 & 1) << 1) | (g4 >> 1);
+    // tokens 4*g4 .. 4*g4+3 sit at piece ((g4 & 1) << 1 | g4 >> 1) of a V^T row, in rows with bit 3 of the row
+    // index set in the other half of the row (see vpos)
+    const int vpiece = (((g4 & 1) << 1) | (g4 >> 1)) ^ (((lq >> 3) & 1) << 1);
     const size_t k_lane = head_off + (size_t)lq * D + g4 * 8, v_lane = head_off + (size_t)lq * 16 + 4 * vpiece;
     // The loop is software-pipelined over page pairs: the K fragments of the next pair (8 KB per wave) are
     // requested right after the score product of this pair has consumed its own, and the V^T fragments of

@@ -182,7 +182,7 @@ hipError_t argmax_rows(const float* logits, int n, int V, int32_t* out, hipStrea
 // with the q heads of those kv heads' groups, the k heads and the v heads (several heads per block at
 // prefill sizes: a thread loads the cos / sin values of its token and chunk once and reuses them over the
 // heads, and has several independent rows in flight).  q is rotated in place; the rotated
-// k rows land in the page as [slot][d] (one contiguous run); v lands transposed, [d][vslot(slot)].  A full
+// k rows land in the page as [slot][d] (one contiguous run); v lands transposed, [d][vpos(slot, d)].  A full
 // page of v goes through an LDS tile and is written as one contiguous 16-byte-per-lane run; partial pages
 // (the first and last page of a prompt, every decode step) write element by element.
 template <typename T, int HB>
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(T* __restrict__ qkv, 
         }
     }
 
-    // ---- v: element (token tl, e) of head g -> vpage[e][vslot(slot0 + tl)]
+    // ---- v: element (token tl, e) of head g -> vpage[e][vpos(slot0 + tl, e)]
     __shared__ T tile[HB][PS][128 + V];
     if (cnt == PS && d == 128) {                   // block-uniform: whole pages go through LDS
         constexpr int CPR = 128 / V;               // 16-byte chunks per row
@@ -255,13 +255,13 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(T* __restrict__ qkv, 
             *reinterpret_cast<vec16*>(&tile[gl][tl][cc * V]) = *reinterpret_cast<const vec16*>(vcol + cc * V);
         }
         __syncthreads();
-        // 16-byte piece `pc` of row e holds positions [V*pc, V*pc + V); position p is token vslot(p) (an involution)
+        // 16-byte piece `pc` of row e holds positions [V*pc, V*pc + V); position p of row e is token vtok(p, e)
         constexpr int PPR = PS / V;
         for (int w = threadIdx.x; w < nh * 128 * PPR; w += 256) {
             const int gl = w / (128 * PPR), e = (w / PPR) % 128, pc = w % PPR;
             union { vec16 v; T x[V]; } o;
 #pragma unroll
-            for (int j = 0; j < V; ++j) o.x[j] = tile[gl][vslot(pc * V + j)][e];
+            for (int j = 0; j < V; ++j) o.x[j] = tile[gl][vtok(pc * V + j, e)][e];
             T* vpage = v_pool + (size_t)page * page_elems + (size_t)(g0 + gl) * PS * d;
             *reinterpret_cast<vec16*>(vpage + (size_t)e * PS + pc * V) = o.v;
         }
@@ -270,7 +270,7 @@ __global__ __launch_bounds__(256) void rope_kvwrite_kernel(T* __restrict__ qkv, 
             const int gl = w / (cnt * d), tl = (w / d) % cnt, e = w % d;
             const T* vcol = qkv + (size_t)(tok0 + tl) * row_stride + (size_t)(n_q + n_kv + g0 + gl) * d;
             T* vpage = v_pool + (size_t)page * page_elems + (size_t)(g0 + gl) * PS * d;
-            vpage[(size_t)e * PS + vslot(slot0 + tl)] = vcol[e];
+            vpage[(size_t)e * PS + vpos(slot0 + tl, e)] = vcol[e];
         }
     }
 }

@@ -6,7 +6,7 @@
 // Pure data movement, HBM-bound: every byte is read once and written once with
 // 16-byte accesses.  One block per (page, unit, head).  K page chunks ([16][d] per
 // head) are already position-major and are copied straight through; V page
-// chunks are stored transposed in the page ([d][16], token order see vslot) and go through a small
+// chunks are stored transposed in the page ([d][16], token order see vpos) and go through a small
 // LDS tile to be turned back into [position][d] (and the reverse on scatter).
 #include "ss_device.h"
 #include "ss_kernels.h"
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void kv_repack_kernel(void* const* __restrict_
                 const int tok = o / vec_per_row, e0 = (o % vec_per_row) * EV;
                 union { vec16 v; E x[EV]; } w;
 #pragma unroll
-                for (int j = 0; j < EV; ++j) w.x[j] = tile[e0 + j][vslot(tok)];
+                for (int j = 0; j < EV; ++j) w.x[j] = tile[e0 + j][vpos(tok, e0 + j)];
                 st16_stream(stp + (size_t)tok * d + e0, w.v);
             }
         } else {
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void kv_repack_kernel(void* const* __restrict_
                 if (tok < nvalid) w.v = ld16_stream(stp + (size_t)tok * d + e0);
                 else w.v = vec16{{0u, 0u, 0u, 0u}};
 #pragma unroll
-                for (int j = 0; j < EV; ++j) tile[e0 + j][vslot(tok)] = w.x[j];
+                for (int j = 0; j < EV; ++j) tile[e0 + j][vpos(tok, e0 + j)] = w.x[j];
             }
             __syncthreads();
             for (int i = threadIdx.x; i < d * VPR; i += 256) {

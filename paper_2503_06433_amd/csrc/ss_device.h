@@ -115,6 +115,12 @@ template <> __device__ __forceinline__ vec16 pack16<bf16_t>(const float* f) {
 // [0-3, 8-11, 4-7, 12-15] (bits 2 and 3 of the slot swapped), so that the 8 tokens one MFMA lane
 // group contributes to the second attention product are one contiguous 16-byte piece.
 __device__ __forceinline__ int vslot(int s) { return (s & 3) | ((s & 4) << 1) | ((s & 8) >> 1); }
+// In the rows of a V page whose head-dimension index e has bit 3 set, the two halves of the row are swapped on
+// top of that: 16 lanes that read the same half of 16 consecutive rows (a fragment read of the second attention
+// product out of LDS, where the page is kept as it is) then fall on 16 different bank groups instead of 8.
+// vpos: position of token slot s in row e; vtok: token slot at position p of row e (its inverse).
+__device__ __forceinline__ int vpos(int s, int e) { return vslot(s) ^ (e & 8); }
+__device__ __forceinline__ int vtok(int p, int e) { return vslot(p ^ (e & 8)); }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -27,7 +27,7 @@ enum Epilogue {
 // Paged cache geometry of one shard and one layer.
 //   K page: [n_heads][page_size][d]   (token-major, d contiguous)
 //   V page: [n_heads][d][page_size]   (transposed inside the page: token contiguous, in the
-//           order 0-3, 8-11, 4-7, 12-15, see vslot() in ss_device.h)
+//           order 0-3, 8-11, 4-7, 12-15, the two halves swapped in rows d with bit 3 set, see vpos() in ss_device.h)
 // page p of the pool starts at element p * n_heads * page_size * d.
 struct KvLayer {
     void* k_pool;
