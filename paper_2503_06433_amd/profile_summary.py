@@ -25,6 +25,13 @@ streams, data paths not toggling),
 
 are condensed by the same command into profiles/bench_<workload>_gemm_clock.md when those two directories exist.
 
+The offline engine loop has a kernel trace of its own,
+
+    rocprofv3 --kernel-trace --stats -d OUT/trace_offline -o t --output-format csv -- python3 bench.py --offline-loop > OUT/trace_offline.json
+
+condensed by `python -m paper_2503_06433_amd.profile_summary --offline --dir OUT` into
+profiles/offline_loop_c2_shape_2_layers_kernel_trace.md.
+
 `--calibrate-copy` makes bench.py run a plain 1 GiB device-to-device copy first; FETCH_SIZE and WRITE_SIZE (KiB per
 dispatch) are scaled by what they read for that copy of known size.
 """
@@ -197,13 +204,46 @@ def class_bytes(total, config):
     return out, n_prefill, n_decode
 
 
+def offline_summary(directory, profiles):
+    lines, _ = kernel_trace_tables(os.path.join(directory, "trace_offline"))
+    if not lines:
+        raise SystemExit("no kernel trace under %s/trace_offline" % directory)
+    runs = {}
+    try:
+        with open(os.path.join(directory, "trace_offline.json")) as f:
+            runs = json.loads(f.read().strip().splitlines()[-1]).get("runs", {})
+    except (OSError, ValueError, IndexError):
+        pass
+    with open(os.path.join(profiles, "offline_loop_c2_shape_2_layers_kernel_trace.md"), "w") as f:
+        f.write("# Kernel trace of the offline engine loop (`bench.py --offline-loop`)\n\nCommand (from the repository root on the MI355X "
+                "box, after `cd /tmp && export TMPDIR=/tmp`):\n\n    rocprofv3 --kernel-trace --stats -d OUT/trace_offline -o t --output-format csv "
+                "-- python3 bench.py --offline-loop > OUT/trace_offline.json\n\nWorkload: 64 requests of 3000 prompt + 64 output tokens, two layers "
+                "of the configuration-2 shape, vocabulary 2048, bf16, greedy decoding, weights reloaded at every switch; four runs (CPU store for all "
+                "64 requests, the same with swap-ins in groups of 4, for 16 requests, for 4 requests), each executed twice (the first execution "
+                "allocates).  All runs together; summarised by `python -m paper_2503_06433_amd.profile_summary --offline`.\n\n")
+        f.write("\n".join(lines) + "\n")
+        if runs:
+            f.write("\nThe same command printed (under the profiler; prompt+output tokens/s, stage changes, seconds in prefill / decode / "
+                    "switch issue):\n\n")
+            for name, r in runs.items():
+                f.write("* `%s`: %.0f tokens/s, %s switches, %.3f / %.3f / %.3f s\n" % (
+                    name, r.get("tokens_per_s", 0.0), r.get("switches", "?"), r.get("prefill_s", 0.0), r.get("decode_s", 0.0), r.get("switch_s", 0.0)))
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--config", type=int, required=True, choices=[2, 3, 4, 5])
+    ap.add_argument("--offline", action="store_true", help="summarise OUT/trace_offline (the offline engine loop) instead of a configuration")
+    ap.add_argument("--config", type=int, choices=[2, 3, 4, 5])
     ap.add_argument("--dir", required=True, help="directory that holds trace_cN, sq_cN, tcc_cN, fetch_cN, write_cN")
     ap.add_argument("--profiles", default="profiles")
     ap.add_argument("--traffic", default="bench_traffic.json")
     a = ap.parse_args()
+    os.makedirs(a.profiles, exist_ok=True)
+    if a.offline:
+        offline_summary(a.dir, a.profiles)
+        return
+    if a.config is None:
+        ap.error("--config N or --offline")
     n, wl = a.config, WORKLOAD[a.config]
     d = lambda kind: os.path.join(a.dir, "%s_c%d" % (kind, n))
     flags = "--config %d --only --no-cpu-baseline" % n
