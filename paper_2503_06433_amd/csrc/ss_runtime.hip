@@ -280,6 +280,11 @@ struct ss_ctx {
     size_t es = 2;
     bool force_generic = false;
     int gemm_rounds_busy = 8;                    // GEMM launch granularity while mover jobs are pending
+    int gemm_rounds_idle = 8;                    // ... and while none are: the blocks of a long persistent launch drift
+                                                 // apart and lose the sharing of operand slices in L2; a launch
+                                                 // boundary every few tiles brings them back in step (70B-shape
+                                                 // GEMMs: 0.52 of the MFMA peak in one launch, 0.547 in launches of 8,
+                                                 // 16 or 32 tiles per block; shorter GEMMs are not affected)
     int gemm_rounds = 0;                         // ... of the layer call in progress (0 = one launch)
     int copy_threads = 4;
     int n_cus = 256;                             // compute units of the device (blocks of the persistent kernels)
@@ -905,7 +910,7 @@ int layer_call(ss_ctx* c, const ss_shard_desc* d, int layer, int phase, const ss
     for (int i = 0; i < b->n_seqs; ++i) T += b->q_lens[i];
     {   // the movers' repack kernels need launch boundaries to get onto the chip between persistent GEMM blocks
         std::lock_guard<std::mutex> lk(c->mu);
-        c->gemm_rounds = c->jobs_done < c->jobs_issued ? c->gemm_rounds_busy : 0;
+        c->gemm_rounds = c->jobs_done < c->jobs_issued ? c->gemm_rounds_busy : c->gemm_rounds_idle;
     }
     if (ph == SS_ATTN) return run_attn_phase(c, s, ll, b, decode, x_in, out, residual, st);
     if (ph == SS_MLP) {
@@ -1518,6 +1523,7 @@ int ss_create(const ss_model_cfg* model, const ss_runtime_cfg* rt, ss_ctx** out)
     c->force_generic = fg && fg[0] == '1';
     c->trace_mover = getenv("SS_TRACE_MOVER") != nullptr;
     if (const char* gr = getenv("SS_GEMM_ROUNDS")) c->gemm_rounds_busy = std::max(0, atoi(gr));
+    if (const char* gr = getenv("SS_GEMM_ROUNDS_IDLE")) c->gemm_rounds_idle = std::max(0, atoi(gr));
     if (const char* cm = getenv("SS_COPY_MAX_MB")) c->copy_max_bytes = (size_t)std::max(1, atoi(cm)) << 20;
     if (const char* ct = getenv("SS_COPY_THREADS")) c->copy_threads = std::max(1, std::min(16, atoi(ct)));
     {
