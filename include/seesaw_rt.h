@@ -173,6 +173,17 @@ int ss_layer_prefill(ss_ctx*, const ss_shard_desc*, int layer, int phase, const 
 int ss_layer_decode(ss_ctx*, const ss_shard_desc*, int layer, int phase, const ss_batch*,
                     const void* x_in, void* out, void* stream);
 
+/* All layers of the descriptor's range, both phases each, chained on the device
+ * in one call (what a worker does with its stage of the model, paper section
+ * 2.2; for decode this is one step of the stage): layer l reads what layer
+ * l - 1 wrote (two library-owned buffers of T x hidden in between), the first
+ * layer reads x_in, the last writes out.  k == 1 only (SS_EINVAL otherwise:
+ * with k > 1 the partial sums of every layer have to be reduced over the shards
+ * between the phases, which one shard cannot do on its own).  The result is the
+ * one the same layers give when called one by one with SS_BOTH. */
+int ss_layers_prefill(ss_ctx*, const ss_shard_desc*, const ss_batch*, const void* x_in, void* out, void* stream);
+int ss_layers_decode(ss_ctx*, const ss_shard_desc*, const ss_batch*, const void* x_in, void* out, void* stream);
+
 /* ---- KV movement (paper section 4.2 "tiered KV cache buffering" and the
  * re-sharding paragraph; section 5.2 two-stage swap-out, asynchronous swap-in,
  * heads-major host layout) ---------------------------------------------------

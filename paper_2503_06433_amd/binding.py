@@ -93,6 +93,8 @@ def load_library():
         "ss_weights_read": (I, [V, D, I, I, V]),
         "ss_layer_prefill": (I, [V, D, I, I, P(_Batch), V, V, V]),
         "ss_layer_decode": (I, [V, D, I, I, P(_Batch), V, V, V]),
+        "ss_layers_prefill": (I, [V, D, P(_Batch), V, V, V]),
+        "ss_layers_decode": (I, [V, D, P(_Batch), V, V, V]),
         "ss_kv_swap": (I, [V, D, I, P(L), I, V]),
         "ss_kv_reshard": (I, [V, D, D, P(L), I, V]),
         "ss_sync": (I, [V]),
@@ -128,7 +130,7 @@ def load_library():
 
 
 EXPORTED = ("ss_create ss_destroy ss_last_error ss_load_layer ss_host_weights_put ss_reshard_weights ss_weights_wait "
-            "ss_weights_shard_bytes ss_weights_read ss_layer_prefill ss_layer_decode ss_kv_swap "
+            "ss_weights_shard_bytes ss_weights_read ss_layer_prefill ss_layer_decode ss_layers_prefill ss_layers_decode ss_kv_swap "
             "ss_kv_reshard ss_sync ss_kv_jobs_issued ss_kv_wait ss_kv_free ss_host_tier_release ss_kv_export_dev ss_kv_import_dev "
             "ss_kv_page_table ss_kv_seq_len ss_kv_read ss_host_tier_read ss_host_tier_used_bytes "
             "ss_kv_free_pages ss_load_head ss_embed ss_lm_head ss_lm_head_noalloc ss_get_config ss_offline_run ss_prof_enable ss_prof_read ss_prof_reset").split()
@@ -258,6 +260,14 @@ class Context:
     def layer_decode(self, desc, layer, phase, seq_ids, kv_before, x_in, out, stream=0):
         bt, keep = self._batch(seq_ids, np.ones(len(seq_ids), dtype=np.int32), kv_before)
         self._ck(self.lib.ss_layer_decode(self.h, C.byref(desc), layer, phase, C.byref(bt), _ptr(x_in), _ptr(out), stream))
+
+    def layers_prefill(self, desc, seq_ids, q_lens, kv_before, x_in, out, stream=0):
+        bt, keep = self._batch(seq_ids, q_lens, kv_before)
+        self._ck(self.lib.ss_layers_prefill(self.h, C.byref(desc), C.byref(bt), _ptr(x_in), _ptr(out), stream))
+
+    def layers_decode(self, desc, seq_ids, kv_before, x_in, out, stream=0):
+        bt, keep = self._batch(seq_ids, np.ones(len(seq_ids), dtype=np.int32), kv_before)
+        self._ck(self.lib.ss_layers_decode(self.h, C.byref(desc), C.byref(bt), _ptr(x_in), _ptr(out), stream))
 
     # ---- KV movement
     def kv_swap(self, desc, direction, seq_ids, stream=0):

@@ -293,7 +293,7 @@ struct ss_ctx {
     std::string err;
     std::map<DescKey, Shard*> shards;
     float* d_rope = nullptr;
-    DevBuf ws_h, ws_qkv, ws_attn, ws_gu, ws_act, ws_x1, ws_scratch, ws_splitk, ws_rs;
+    DevBuf ws_h, ws_qkv, ws_attn, ws_gu, ws_act, ws_x1, ws_scratch, ws_splitk, ws_rs, ws_chain[2];
     MetaSlot meta[4];
     int meta_next = 0;
     void *d_embed = nullptr, *d_gf = nullptr, *d_wlm_t = nullptr;
@@ -920,6 +920,28 @@ int layer_call(ss_ctx* c, const ss_shard_desc* d, int layer, int phase, const ss
     if ((rc = ensure_buf(c, c->ws_x1, (size_t)T * c->m.hidden * c->es))) return rc;
     if ((rc = run_attn_phase(c, s, ll, b, decode, x_in, c->ws_x1.p, true, st))) return rc;
     return run_mlp_phase(c, s, ll, (int)T, c->ws_x1.p, out, true, st);
+}
+
+// The layers of the shard's range one after the other, the output of one the input of the next.
+int layers_call(ss_ctx* c, const ss_shard_desc* d, const ss_batch* b, const void* x_in, void* out, void* stream, bool decode) {
+    if (!c) return SS_EINVAL;
+    if (!d || !b || !x_in || !out || b->n_seqs <= 0 || !b->q_lens) return fail(c, SS_EINVAL, "null or empty batch / buffers");
+    if (d->k != 1) return fail(c, SS_EINVAL, "layers can only be chained on the device for k == 1");
+    if (d->layer_end <= d->layer_begin) return fail(c, SS_EINVAL, "empty layer range");
+    int64_t T = 0;
+    for (int i = 0; i < b->n_seqs; ++i) T += b->q_lens[i];
+    if (T <= 0 || T > (1 << 30)) return fail(c, SS_EINVAL, "bad token count");
+    const int n = d->layer_end - d->layer_begin;
+    int rc;
+    for (int j = 0; j < (n > 2 ? 2 : n - 1); ++j)
+        if ((rc = ensure_buf(c, c->ws_chain[j], (size_t)T * c->m.hidden * c->es))) return rc;
+    const void* in = x_in;
+    for (int j = 0; j < n; ++j) {
+        void* o = j == n - 1 ? out : c->ws_chain[j & 1].p;
+        if ((rc = layer_call(c, d, d->layer_begin + j, SS_BOTH, b, in, o, stream, decode))) return rc;
+        in = o;
+    }
+    return SS_OK;
 }
 
 // ------------------------------------------------------------------ mover
@@ -1614,7 +1636,8 @@ int ss_destroy(ss_ctx* c) {
         if (s->w_ready) (void)hipEventDestroy(s->w_ready);
         delete s;
     }
-    for (DevBuf* b : {&c->ws_h, &c->ws_qkv, &c->ws_attn, &c->ws_gu, &c->ws_act, &c->ws_x1, &c->ws_scratch, &c->ws_splitk, &c->ws_rs})
+    for (DevBuf* b : {&c->ws_h, &c->ws_qkv, &c->ws_attn, &c->ws_gu, &c->ws_act, &c->ws_x1, &c->ws_scratch, &c->ws_splitk, &c->ws_rs,
+                      &c->ws_chain[0], &c->ws_chain[1]})
         if (b->p) (void)hipFree(b->p);
     for (auto& ms : c->meta) {
         if (ms.host) (void)hipHostFree(ms.host);
@@ -1865,6 +1888,14 @@ int ss_layer_prefill(ss_ctx* c, const ss_shard_desc* d, int layer, int phase, co
 int ss_layer_decode(ss_ctx* c, const ss_shard_desc* d, int layer, int phase, const ss_batch* b, const void* x_in,
                     void* out, void* stream) {
     return layer_call(c, d, layer, phase, b, x_in, out, stream, true);
+}
+
+int ss_layers_prefill(ss_ctx* c, const ss_shard_desc* d, const ss_batch* b, const void* x_in, void* out, void* stream) {
+    return layers_call(c, d, b, x_in, out, stream, false);
+}
+
+int ss_layers_decode(ss_ctx* c, const ss_shard_desc* d, const ss_batch* b, const void* x_in, void* out, void* stream) {
+    return layers_call(c, d, b, x_in, out, stream, true);
 }
 
 int ss_kv_swap(ss_ctx* c, const ss_shard_desc* d, int dir, const int64_t* seq_ids, int n, void* stream) {

@@ -230,6 +230,83 @@ def test_mixed_batch_of_prompt_chunks_and_decode_tokens(name, dtype):
     twin.destroy()
 
 
+@pytest.mark.parametrize("name,dtype", [("gqa4_d128", wl.BF16), ("mha_d64_generic", wl.F32)])
+def test_layers_chained_in_one_call_equal_layer_by_layer_calls_and_the_oracle(name, dtype):
+    """ss_layers_prefill / ss_layers_decode over a three-layer stage: the same bits as the layers called one by
+    one on a twin context (outputs and every layer's cache), the oracle's result within the tolerance, the
+    descriptor's own range (layers 1 and 2 of 3) respected, and k > 1 refused."""
+    cfg = wl.ModelCfg(n_layers=3, dtype=dtype, **SMALL[name])
+    vals, raws = _weights(cfg, 900)
+    lens = [5, 70, 33]
+    ids = [3, 4, 9]
+    T = sum(lens)
+    xv, xr = wl.make_activations((T, cfg.hidden), 31, dtype)
+    x = to_device(xr, dtype)
+    zeros = [0] * len(lens)
+    stage = pp_desc(cfg)
+    one, twin = make_context(cfg, pages=64), make_context(cfg, pages=64)
+    for ctx in (one, twin):
+        _load(ctx, stage, cfg, raws)
+    # ---- prefill
+    y = empty_like_acts(T, cfg.hidden, dtype)
+    one.layers_prefill(stage, ids, lens, zeros, x, y)
+    cur = x
+    for l in range(cfg.n_layers):
+        nxt = empty_like_acts(T, cfg.hidden, dtype)
+        twin.layer_prefill(stage, l, ss.SS_BOTH, ids, lens, zeros, cur, nxt)
+        cur = nxt
+    torch.cuda.synchronize()
+    assert torch.equal(y, cur)
+    cache = lm.KVCache(cfg)
+    batch = [(sid, n, 0) for sid, n in zip(ids, lens)]
+    ref = lm.run_layers(cfg, vals, xv, batch, cache, 0, cfg.n_layers, round_kv=_round_kv(cfg))
+    starts = np.concatenate([[0], np.cumsum(lens)])
+    spans = [(int(starts[i]), int(starts[i + 1])) for i in range(len(lens))]
+    parity(to_f64(y, dtype), ref, dtype, "three chained layers, prefill output", spans)
+    for l in range(cfg.n_layers):
+        for sid in ids:
+            assert np.array_equal(one.kv_read(stage, sid, l, cfg.n_kv_heads), twin.kv_read(stage, sid, l, cfg.n_kv_heads))
+    # ---- two decode steps
+    now = list(lens)
+    for step in range(2):
+        dv, dr = wl.make_activations((len(ids), cfg.hidden), 60 + step, dtype)
+        dx = to_device(dr, dtype)
+        y = empty_like_acts(len(ids), cfg.hidden, dtype)
+        one.layers_decode(stage, ids, now, dx, y)
+        cur = dx
+        for l in range(cfg.n_layers):
+            nxt = empty_like_acts(len(ids), cfg.hidden, dtype)
+            twin.layer_decode(stage, l, ss.SS_BOTH, ids, now, cur, nxt)
+            cur = nxt
+        torch.cuda.synchronize()
+        assert torch.equal(y, cur)
+        dbatch = [(sid, 1, n) for sid, n in zip(ids, now)]
+        ref = lm.run_layers(cfg, vals, dv, dbatch, cache, 0, cfg.n_layers, round_kv=_round_kv(cfg))
+        parity(to_f64(y, dtype), ref, dtype, "three chained layers, decode step %d" % step,
+               [(j, j + 1) for j in range(len(ids))])
+        now = [n + 1 for n in now]
+    # ---- a stage of layers 1 and 2 only, and the refusal for k > 1
+    part = pp_desc(cfg, 1, 3)
+    _load(one, part, cfg, raws)
+    y = empty_like_acts(T, cfg.hidden, dtype)
+    one.layers_prefill(part, [100, 101, 102], lens, zeros, x, y)
+    mid = empty_like_acts(T, cfg.hidden, dtype)
+    last = empty_like_acts(T, cfg.hidden, dtype)
+    _load(twin, part, cfg, raws)
+    twin.layer_prefill(part, 1, ss.SS_BOTH, [100, 101, 102], lens, zeros, x, mid)
+    twin.layer_prefill(part, 2, ss.SS_BOTH, [100, 101, 102], lens, zeros, mid, last)
+    torch.cuda.synchronize()
+    assert torch.equal(y, last)
+    if cfg.n_kv_heads % 2 == 0:
+        shard = tp_desc(cfg, 2, 0)
+        _load(one, shard, cfg, raws)
+        with pytest.raises(ss.SeesawError) as e:
+            one.layers_prefill(shard, [200], [4], [0], x[:4], y[:4])
+        assert e.value.code == ss.SS_EINVAL
+    one.destroy()
+    twin.destroy()
+
+
 def test_generic_kernels_forced_for_bf16():
     os.environ["SS_FORCE_GENERIC"] = "1"
     try:
