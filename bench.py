@@ -619,7 +619,7 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--dtype", choices=["bf16", "f16"], default="bf16",
-                    help="16-bit storage type of configuration 2 (bf16: what BASELINE.json names; f16: the paper's own)")
+                    help="16-bit storage type of configuration 2 (bf16: the type the benchmark is defined on; f16: the paper's own)")
     ap.add_argument("--zero-data", action="store_true",
                     help="power probe, not a benchmark: weights, gains and inputs are all zero, so the same instruction streams run "
                          "without toggling the data paths (the clock the chip then holds shows how far the package power limit, "
