@@ -508,7 +508,9 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
     const int item = wk.item_order[blockIdx.x / n_kv], g = blockIdx.x % n_kv;     // the heads of an item side by side
     const int G = n_q / n_kv;
     const int sq = wk.item_seq[item];
-    const int page0 = wk.item_page0[item], npg = wk.item_npages[item];
+    // an item is pages page0, page0 + stride, ... (npg of them) of its sequence: the items of a sequence interleave
+    const int page0 = wk.item_page0[item], npg = wk.item_npages[item] & 0xffff;
+    const int stride = (wk.item_npages[item] >> 16) > 0 ? (wk.item_npages[item] >> 16) : 1;
     const int kv_len = bm.kv_before[sq] + 1;
     const int lane = threadIdx.x;
     const int lq = lane & 15, g4 = lane >> 4;
@@ -543,8 +545,8 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
     // would make the load counter's bookkeeping conservative.
     auto pair_pages = [&](int pi, int& pgA, int& pgB) {
         const int ia = pi < npg ? pi : npg - 1, ib = pi + 1 < npg ? pi + 1 : npg - 1;
-        pgA = pt[ia];
-        pgB = pt[ib];
+        pgA = pt[ia * stride];
+        pgB = pt[ib * stride];
     };
     auto load_k = [&](int pgA, int pgB, Frag* fa, Frag* fb) {
 #pragma unroll
@@ -574,12 +576,12 @@ __global__ __launch_bounds__(64) void attn_decode_mfma_kernel(const bf16_t* __re
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (decltype(prefetch)::value) load_k(nA, nB, na, nb);
         __builtin_amdgcn_sched_barrier(0);
-        const int posA = (page0 + pi) * 16 + 4 * g4;
+        const int posA = (page0 + pi * stride) * 16 + 4 * g4, posB = posA + 16 * stride;
         float mx = m;
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             sA[v] = (posA + v < kv_len) ? sA[v] * scale_log2e : -INFINITY;
-            sB[v] = (hasB && posA + 16 + v < kv_len) ? sB[v] * scale_log2e : -INFINITY;
+            sB[v] = (hasB && posB + v < kv_len) ? sB[v] * scale_log2e : -INFINITY;
             mx = fmaxf(mx, fmaxf(sA[v], sB[v]));
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));

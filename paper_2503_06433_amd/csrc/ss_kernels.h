@@ -72,7 +72,8 @@ struct BatchMeta {
 struct DecodeWork {
     const int32_t* item_seq;    // [n_items]
     const int32_t* item_page0;  // [n_items] first page index within the sequence
-    const int32_t* item_npages; // [n_items]
+    const int32_t* item_npages; // [n_items] low 16 bits: number of pages; high 16 bits: stride between them in pages
+                                //           (0 = 1): pages page0, page0 + stride, ...
     const int32_t* seq_item0;   // [n_seqs+1] first item of each sequence
     const int32_t* item_order;  // [n_items] launch order (block x works on item item_order[x])
     int n_items;

@@ -594,6 +594,17 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
             // and a short remainder
             const int cnt = (used + ipp - 1) / ipp;
             const int per = (((used + cnt - 1) / cnt) + 1) & ~1;
+            // The items of a sequence interleave (item j takes pages j, j + cnt, ...): the waves that work on one
+            // sequence then read neighbouring pages at about the same time (7B shape: 0.715 -> 0.73 of the HBM rate;
+            // the one-kv-head shard is unchanged).  SS_DECODE_STRIDED=0 gives contiguous runs of pages instead.
+            static const int strided = getenv("SS_DECODE_STRIDED") ? atoi(getenv("SS_DECODE_STRIDED")) : 1;
+            if (strided && cnt > 1 && cnt < 65536) {
+                for (int j = 0; j < cnt && j < used; ++j) {
+                    item_seq.push_back(i);
+                    item_page0.push_back(j);
+                    item_np.push_back(((used - j + cnt - 1) / cnt) | (cnt << 16));
+                }
+            } else
             for (int p0 = 0; p0 < used; p0 += per) {
                 item_seq.push_back(i);
                 item_page0.push_back(p0);
@@ -688,7 +699,7 @@ int prepare_batch(ss_ctx* c, Shard* s, const ss_batch* b, bool decode, hipStream
     // launch order: longest items first, so that the last waves of the grid are the short ones
     std::vector<int32_t> item_order(n_items);
     for (size_t i = 0; i < n_items; ++i) item_order[i] = (int32_t)i;
-    std::stable_sort(item_order.begin(), item_order.end(), [&](int32_t a, int32_t b2) { return item_np[a] > item_np[b2]; });
+    std::stable_sort(item_order.begin(), item_order.end(), [&](int32_t a, int32_t b2) { return (item_np[a] & 0xffff) > (item_np[b2] & 0xffff); });
     auto al = [](size_t x) { return (x + 63) & ~(size_t)63; };
     size_t off_tok_seq = 0;
     size_t off_tok_pos = off_tok_seq + al(4 * (size_t)T);
