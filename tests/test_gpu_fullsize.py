@@ -330,3 +330,29 @@ def test_config3_weight_reshard_pp_layer_to_tp4_shard_bit_exact():
         got = ctx.weights_read(shard, 0, which, ref[name].size)
         assert np.array_equal(got, ref[name].reshape(-1)), name
     ctx.destroy()
+
+
+def test_many_tokens_on_a_narrow_layer_short_contractions_on_the_large_output_kernel():
+    """70 000 tokens through a layer of hidden size 256: every projection has enough output tiles for the
+    persistent large-output GEMM but contractions of only 4 or 5 slices (K = 256, 320) and ragged output widths
+    (gate/up: 640 columns), the corner where that kernel's prefetches, waits and tile boundaries lie closest
+    together.  700 prompts of 100 tokens; eight of them recomputed by the oracle."""
+    cfg = wl.ModelCfg(n_layers=1, dtype=wl.BF16, hidden=256, n_q_heads=2, n_kv_heads=2, head_dim=128, ffn=320)
+    vals, raws = wl.make_layer_weights(cfg, 7301)
+    lens = [100] * 700
+    T = sum(lens)
+    xv, xr = wl.make_activations((T, cfg.hidden), 7302, cfg.dtype)
+    ctx = make_context(cfg, pages=_pages_for(lens), max_seq_len=256)
+    desc = pp_desc(cfg)
+    ctx.load_layer(desc, 0, raws)
+    ids = list(range(len(lens)))
+    out = empty_like_acts(T, cfg.hidden, cfg.dtype)
+    ctx.layer_prefill(desc, 0, ss.SS_BOTH, ids, lens, [0] * len(lens), to_device(xr, cfg.dtype), out)
+    torch.cuda.synchronize()
+    got = to_f64(out, cfg.dtype)
+    assert np.isfinite(got).all()
+    for i in (0, 1, 255, 256, 349, 511, 698, 699):             # around tile boundaries of 256 tokens, first and last
+        a, b = 100 * i, 100 * (i + 1)
+        _, ref = lm.layer_forward(cfg, vals, xv[a:b], [(i, 100, 0)], lm.KVCache(cfg), 0)
+        parity(got[a:b], ref, cfg.dtype, "narrow layer, sequence %d" % i)
+    ctx.destroy()
