@@ -293,7 +293,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
                                                                int ldc, const bf16_t* __restrict__ R, int M, int N,
                                                                int K, int tiles_m, int tiles_n, int sync_walk,
                                                                int cus_per_xcd, int it0, int max_it, int GM,
-                                                               int pf_dist, const float* __restrict__ RS) {
+                                                               int pf_dist, const float* __restrict__ RS, int ksplit) {
     constexpr int BM = 256, BN = 256;
     constexpr int STAGE = (BM + BN) * 128;       // bytes per ring stage
     constexpr int LPS = 16;                      // loads per wave per slice
@@ -318,15 +318,24 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
     my_rem = my_rem < rem_per_xcd ? my_rem : rem_per_xcd;
     my_rem = my_rem > 0 ? my_rem : 0;
     const int my_tiles = main_tiles + my_rem;
+    // Split K (outputs of too few tiles to occupy the chip): the list of the XCD is walked ksplit times, once per
+    // K range; entry l is K range l / my_tiles of tile l % my_tiles, and the product of a range goes to plane
+    // `range` of the fp32 partial sums [ksplit][M][N] (EPI_PARTIAL, C is that buffer), which a second kernel sums.
+    const int my_entries = my_tiles * ksplit;
     const int first = cu + it0 * cus_per_xcd;          // index in this XCD's list
-    if (first >= my_tiles) return;
-    int nt_local = (my_tiles - first + cus_per_xcd - 1) / cus_per_xcd;
+    if (first >= my_entries) return;
+    int nt_local = (my_entries - first + cus_per_xcd - 1) / cus_per_xcd;
     nt_local = nt_local < max_it ? nt_local : max_it;
     // (r, c) = the tile's row inside its group and its column: the CUs of an XCD that work on one group row
     // at a time differ in c, those on one column in r
-    int tile_r = 0, tile_c = 0, tile_gm = 1;
+    int tile_r = 0, tile_c = 0, tile_gm = 1, tile_range = 0;
     auto tile_origin = [&](int it, int& m0, int& n0) {
-        const int l = first + it * cus_per_xcd;
+        int l = first + it * cus_per_xcd;
+        tile_range = 0;
+        if (ksplit > 1) {
+            tile_range = l / my_tiles;
+            l -= tile_range * my_tiles;
+        }
         int row0, logical;
         if (l < main_tiles) {
             row0 = xcd * gpx * GM;
@@ -370,7 +379,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
         int m0, n0;
         tile_origin(it < nt_local ? it : nt_local - 1, m0, n0);
         const int row0 = isA ? m0 : n0;
-        tbase = gbase + (size_t)row0 * (size_t)ld * 2;
+        tbase = gbase + (size_t)row0 * (size_t)ld * 2 + (size_t)tile_range * (size_t)(K / 64 / ksplit) * 128;
         pf_row0 = row0;
         if (pf_dist > 0) {
             const int sharers = cus_per_xcd / GM > 0 ? cus_per_xcd / GM : 1;      // CUs of the XCD on one group row
@@ -387,7 +396,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
         }
     };
     const uint32_t dst0 = lds_base + (isA ? 0 : BM * 128) + row_base * 128;
-    const int nsl = K / 64;
+    const int nsl = K / 64 / ksplit;             // slices of one K range
     const int g_last = nt_local * nsl - 1;       // last slice of this block's stream
     auto issue1 = [&](int stage, int ksl, int i) {
         const uint8_t* sb = tbase + (size_t)ksl * 128;
@@ -486,6 +495,20 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
     auto epilogue = [&](int it) {
         int m0, n0;
         tile_origin(it, m0, n0);
+        if (EPI == EPI_PARTIAL) {                // fp32 sums of this K range, straight from the accumulators
+            float* P = reinterpret_cast<float*>(C) + (size_t)tile_range * (size_t)M * (size_t)N;
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) {
+                const int gr = m0 + wm * 128 + mt * 16 + l16;
+                if (gr >= M) continue;
+#pragma unroll
+                for (int nt = 0; nt < 8; ++nt) {
+                    const int gc = n0 + wn * 128 + nt * 16 + 4 * lk;
+                    if (gc < N) *reinterpret_cast<f32x4_t*>(P + (size_t)gr * N + gc) = acc[nt][mt];
+                }
+            }
+            return;
+        }
         constexpr int NH = (EPI == EPI_SWIGLU) ? 1 : 2;
         constexpr int NP = 4 * NH;
         const int n_out = (EPI == EPI_SWIGLU) ? (N >> 1) : N;
@@ -664,9 +687,18 @@ bool gemm_mfma_stream_supported(const void* C, const void* R, int ldc, int M, in
 // Blocks of the persistent kernel own their CU (all registers, all LDS) until they are done, so a kernel
 // of another stream can only start at a launch boundary.  `max_rounds` > 0 cuts the walk into launches
 // of at most that many tiles per block, for callers that have latency-bound work on other streams.
+// With ksplit > 1 the kernel writes fp32 partial sums [ksplit][M][N] into `partial` (EPI_PARTIAL) and the caller
+// sums them.
 static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
-                                int N, int K, int epi, hipStream_t s, int max_rounds, const float* rs) {
+                                int N, int K, int epi, hipStream_t s, int max_rounds, const float* rs, int ksplit = 1,
+                                float* partial = nullptr) {
     if (rs && epi == EPI_RESIDUAL) return hipErrorInvalidValue;      // no caller scales a product that adds a residual
+    if (ksplit < 1 || (K / 64) % ksplit != 0 || K / 64 / ksplit < 2 || (ksplit > 1 && !partial)) return hipErrorInvalidValue;
+    if (ksplit > 1) {
+        epi = EPI_PARTIAL;
+        C = reinterpret_cast<bf16_t*>(partial);
+        rs = nullptr;
+    }
     const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
     const long long n_tiles = (long long)tiles_m * tiles_n;
     if (n_tiles > (1ll << 30)) return hipErrorInvalidValue;
@@ -702,7 +734,7 @@ static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16
     const int gpx = sync_walk ? (tiles_m / gm_rows) / 8 : 0;
     const long long main_tiles = (long long)gpx * gm_rows * tiles_n;
     const long long rem_tiles = (long long)(tiles_m - 8 * gpx * gm_rows) * tiles_n;
-    const int per_xcd = (int)(main_tiles + (rem_tiles + 7) / 8);
+    const int per_xcd = (int)(main_tiles + (rem_tiles + 7) / 8) * ksplit;       // entries of the longest list
     const unsigned grid = 8 * (unsigned)(per_xcd < cus_per_xcd ? per_xcd : cus_per_xcd);
     const int rounds_total = (per_xcd + cus_per_xcd - 1) / cus_per_xcd;
     const int step = max_rounds > 0 ? max_rounds : rounds_total;
@@ -718,7 +750,7 @@ static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16
         }                                                                                                       \
         for (int it0 = 0; it0 < rounds_total; it0 += step)                                                      \
             kfn<<<grid, 256, STREAM_LDS, s>>>(A, lda, Wt, C, ldc, R, M, N, K, tiles_m, tiles_n, sync_walk,      \
-                                              cus_per_xcd, it0, step, gm_rows, pf_dist, rs);                    \
+                                              cus_per_xcd, it0, step, gm_rows, pf_dist, rs, ksplit);            \
     }
     switch (epi) {
         case EPI_STORE: SS_LAUNCH(EPI_STORE) break;
@@ -726,6 +758,7 @@ static hipError_t launch_stream(const bf16_t* A, int lda, const bf16_t* Wt, bf16
             if (!R) return hipErrorInvalidValue;
             SS_LAUNCH(EPI_RESIDUAL) break;
         case EPI_SWIGLU: SS_LAUNCH(EPI_SWIGLU) break;
+        case EPI_PARTIAL: SS_LAUNCH(EPI_PARTIAL) break;
         default: return hipErrorInvalidValue;
     }
 #undef SS_LAUNCH
@@ -766,6 +799,23 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     }
 }
 
+static hipError_t reduce_partials(const float* ws, int ksplit, bf16_t* C, int ldc, const bf16_t* R, int M, int N, int epi,
+                                  const float* rs, hipStream_t s) {
+    const size_t n_out = (size_t)M * (epi == EPI_SWIGLU ? N / 2 : N);
+    const unsigned rgrid = (unsigned)((n_out + 255) / 256);
+    switch (epi) {
+        case EPI_STORE: splitk_reduce_kernel<EPI_STORE><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N, rs); break;
+        case EPI_RESIDUAL:
+            if (!R) return hipErrorInvalidValue;
+            splitk_reduce_kernel<EPI_RESIDUAL><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N, rs);
+            break;
+        case EPI_SWIGLU: splitk_reduce_kernel<EPI_SWIGLU><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N, rs); break;
+        case EPI_STORE_F32: splitk_reduce_kernel<EPI_STORE_F32><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N, rs); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 template <int BM, int BN, int WM, int WN>
 static hipError_t launch_cfg(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t* C, int ldc, const bf16_t* R, int M,
                              int N, int K, int epi, hipStream_t s, int ksplit = 1, float* ws = nullptr,
@@ -791,19 +841,7 @@ static hipError_t launch_cfg(const bf16_t* A, int lda, const bf16_t* Wt, bf16_t*
     }
     if (ksplit > 1) {
         SS_LAUNCH(EPI_PARTIAL, reinterpret_cast<bf16_t*>(ws))
-        const size_t n_out = (size_t)M * (epi == EPI_SWIGLU ? N / 2 : N);
-        const unsigned rgrid = (unsigned)((n_out + 255) / 256);
-        switch (epi) {
-            case EPI_STORE: splitk_reduce_kernel<EPI_STORE><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N, rs); break;
-            case EPI_RESIDUAL:
-                if (!R) return hipErrorInvalidValue;
-                splitk_reduce_kernel<EPI_RESIDUAL><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N, rs);
-                break;
-            case EPI_SWIGLU: splitk_reduce_kernel<EPI_SWIGLU><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N, rs); break;
-            case EPI_STORE_F32: splitk_reduce_kernel<EPI_STORE_F32><<<rgrid, 256, 0, s>>>(ws, ksplit, C, ldc, R, M, N, rs); break;
-            default: return hipErrorInvalidValue;
-        }
-        return hipGetLastError();
+        return reduce_partials(ws, ksplit, C, ldc, R, M, N, epi, rs, s);
     }
     switch (epi) {
         case EPI_STORE_F32:                                       // one K range: plane 0 of the partials is the fp32 result
@@ -830,8 +868,29 @@ hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int l
     // Smaller outputs (decode batches) are bound by streaming the weights: 128 x 128 tiles with split-K
     // (partials in fp32, summed by a small second kernel).
     const long long big = (long long)((M + 255) / 256) * ((N + 255) / 256);
-    if (big >= 256 && epi != EPI_STORE_F32 && gemm_mfma_stream_supported(C, R, ldc, M, N, K, lda, epi))
+    static const long long stream_min = getenv("SS_GEMM_STREAM_MIN_TILES") ? atoll(getenv("SS_GEMM_STREAM_MIN_TILES")) : 256;
+    if (big >= stream_min && epi != EPI_STORE_F32 && gemm_mfma_stream_supported(C, R, ldc, M, N, K, lda, epi))
         return launch_stream(a, lda, w, c, ldc, r, M, N, K, epi, s, max_rounds, rs);
+    // In between (a thousand tokens or so, as in the decode step of a tensor-parallel shard): too few 256 x 256
+    // tiles for the chip, but long contractions.  The persistent kernel with K cut into ranges, so that tiles x
+    // ranges fill the CUs, with fp32 partial sums and the reduce kernel of the small-tile path; only while the
+    // partial sums stay below the weight bytes (as below) and at least half the CUs get a block.  Measured with
+    // 1024 tokens on the shapes of the k = 8 shard of the 70B layer: gate/up (7168 x 8192) 150 -> 113 us; the
+    // down projection (K = 3584) would lose (73 -> 83 us: its partial sums outweigh its weights) and is excluded
+    // by the rule, as are outputs too narrow to fill the chip even when split (QKV of the shard: 20 tiles).
+    static const int stream_split = getenv("SS_GEMM_STREAM_SPLIT") ? atoi(getenv("SS_GEMM_STREAM_SPLIT")) : 1;
+    if (stream_split && M >= 512 && big >= 8 && big < 256 && epi != EPI_STORE_F32 && ws &&
+        gemm_mfma_stream_supported(C, R, ldc, M, N, K, lda, epi) && ((uintptr_t)ws & 15) == 0) {
+        int ks = 1;
+        while (ks < 8 && big * (ks * 2) <= 288 && (K / 64) % (ks * 2) == 0 && K / 64 / (ks * 2) >= 16 &&
+               (long long)(ks * 2) * 4 * M <= K && (size_t)(ks * 2) * M * N * sizeof(float) <= ws_bytes)
+            ks *= 2;
+        if (ks > 1 && big * ks >= 128) {
+            hipError_t e = launch_stream(a, lda, w, c, ldc, r, M, N, K, epi, s, max_rounds, rs, ks, ws);
+            if (e != hipSuccess) return e;
+            return reduce_partials(ws, ks, c, ldc, r, M, N, epi, rs, s);
+        }
+    }
     const long long mid = (long long)((M + 127) / 128) * ((N + 127) / 128);
     // split K until every CU has a block, but only while the fp32 partials (8*S*M*N bytes written and
     // read back) stay below the weight bytes (2*N*K) they help to stream: S <= K / (4 M)
