@@ -98,8 +98,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t* _
         b_dst[i] = lds_chunk_off(row, kc);
     }
     // two register sets: the loads of two slices are in flight while a third is multiplied.  At decode sizes the
-    // kernel does little but stream weights, and what bounds a block's share of the bandwidth is the bytes it has
-    // in flight (one slice = 16 KB of weights per block was half of what the loaded memory system needs)
+    // kernel does little but stream weights; twice the bytes in flight per block gained 3-4 % on the shapes of
+    // tensor-parallel shards and nothing on the 7B shape (the chain of steps of one iteration bounds it)
     u32x4_t a_reg[2][A_CH], b_reg[2][B_CH];
 
     f32x16_t acc[TM][TN];
