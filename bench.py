@@ -485,9 +485,41 @@ class Bench:
         run_slice(ids, lens, x)
         stg = torch.empty(Ta * kv_tok_bytes * L // 2, device="cuda", dtype=torch.bfloat16)
         rp = self.timed(ctx, lambda: ctx.kv_export_dev(pp, ids, stg, stream), 3)
-        ctx.kv_free(pp, ids)
         self.rooflines["c5.kv_repack"] = self.hbm(2.0 * Ta * kv_tok_bytes * L, rp[CLS_REPACK][0], rp[CLS_REPACK][1], "c5.kv_repack")
         del stg
+        if headline:
+            # the PCIe legs of the re-shard alone, nothing else running: the batch's caches out of the pipeline layout
+            # into the host tier, then the tensor-parallel shard's heads of them in; next to what a plain copy between
+            # the device and page-locked memory reaches on this machine (the link differs a lot from box to box)
+            torch.cuda.synchronize()
+            ctx.sync()
+            t0 = time.perf_counter()
+            ctx.kv_swap(pp, ss.SS_OUT, ids, stream)
+            ctx.kv_wait(ctx.kv_jobs_issued())
+            t_out = time.perf_counter() - t0
+            t0 = time.perf_counter()
+            ctx.kv_swap(tp, ss.SS_IN, ids, stream)
+            ctx.kv_wait(ctx.kv_jobs_issued())
+            t_in = time.perf_counter() - t0
+            ctx.kv_free(tp, ids)
+            ctx.host_tier_release(ids)
+            b_out, b_in = Ta * kv_tok_bytes * L, Ta * kv_tok_bytes * L // work.k
+            n = 512 << 20
+            dev = torch.empty(n, dtype=torch.uint8, device="cuda")
+            pin = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+            rates = {}
+            for label, dst, src in (("d2h", pin, dev), ("h2d", dev, pin)):
+                dst.copy_(src, non_blocking=True)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                dst.copy_(src, non_blocking=True)
+                torch.cuda.synchronize()
+                rates[label + "_GB/s"] = n / (time.perf_counter() - t0) / 1e9
+            del dev, pin
+            out["kv_movement"] = {"swap_out": {"bytes": b_out, "ms": t_out * 1e3, "GB/s": b_out / t_out / 1e9},
+                                  "swap_in": {"bytes": b_in, "ms": t_in * 1e3, "GB/s": b_in / t_in / 1e9},
+                                  "plain_pinned_copy_512MB": rates}
+        ctx.kv_free(pp, ids)
         if headline and w0 is not None:
             out["cpu_baseline"] = cpu_baseline_layer(work, w0, wl, 2.0e13, 0, L, 5101)
         ctx.destroy()
@@ -683,7 +715,7 @@ def main():
         "config": head["config"], "roofline": roof, "rooflines": b.rooflines,
         "phase_ms": dict({"c%d" % args.config: head.get("phase")}, **others),
     }
-    for key in ("weight_reshard", "cpu_baseline"):
+    for key in ("weight_reshard", "kv_movement", "cpu_baseline"):
         if key in head:
             out[key] = head[key]
     print(json.dumps(out))
