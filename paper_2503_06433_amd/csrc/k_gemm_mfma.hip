@@ -877,9 +877,11 @@ hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int l
     // partial sums stay below the weight bytes (as below) and at least half the CUs get a block.  Measured with
     // 1024 tokens on the shapes of the k = 8 shard of the 70B layer: gate/up (7168 x 8192) 150 -> 113 us; the
     // down projection (K = 3584) would lose (73 -> 83 us: its partial sums outweigh its weights) and is excluded
-    // by the rule, as are outputs too narrow to fill the chip even when split (QKV of the shard: 20 tiles).
+    // by the rule, as are outputs too narrow to fill the chip even when split (QKV of the shard: 20 tiles).  At 256
+    // tokens (one tile row) the four GEMMs of the 7B layer together go from 232 to 217 us.
     static const int stream_split = getenv("SS_GEMM_STREAM_SPLIT") ? atoi(getenv("SS_GEMM_STREAM_SPLIT")) : 1;
-    if (stream_split && M >= 512 && big >= 8 && big < 256 && epi != EPI_STORE_F32 && ws &&
+    static const int stream_split_min_m = getenv("SS_GEMM_STREAM_SPLIT_MIN_M") ? atoi(getenv("SS_GEMM_STREAM_SPLIT_MIN_M")) : 256;
+    if (stream_split && M >= stream_split_min_m && big >= 8 && big < 256 && epi != EPI_STORE_F32 && ws &&
         gemm_mfma_stream_supported(C, R, ldc, M, N, K, lda, epi) && ((uintptr_t)ws & 15) == 0) {
         int ks = 1;
         while (ks < 8 && big * (ks * 2) <= 288 && (K / 64) % (ks * 2) == 0 && K / 64 / (ks * 2) >= 16 &&
