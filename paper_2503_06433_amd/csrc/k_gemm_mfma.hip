@@ -884,10 +884,11 @@ hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int l
     if (stream_split && M >= stream_split_min_m && big >= 8 && big < 256 && epi != EPI_STORE_F32 && ws &&
         gemm_mfma_stream_supported(C, R, ldc, M, N, K, lda, epi) && ((uintptr_t)ws & 15) == 0) {
         int ks = 1;
-        while (ks < 8 && big * (ks * 2) <= 288 && (K / 64) % (ks * 2) == 0 && K / 64 / (ks * 2) >= 16 &&
+        constexpr int min_slices = 16, min_blocks = 128;      // (64 blocks: the 7B-shape decode GEMMs 217 -> 260 us)
+        while (ks < 8 && big * (ks * 2) <= 288 && (K / 64) % (ks * 2) == 0 && K / 64 / (ks * 2) >= min_slices &&
                (long long)(ks * 2) * 4 * M <= K && (size_t)(ks * 2) * M * N * sizeof(float) <= ws_bytes)
             ks *= 2;
-        if (ks > 1 && big * ks >= 128) {
+        if (ks > 1 && big * ks >= min_blocks) {
             hipError_t e = launch_stream(a, lda, w, c, ldc, r, M, N, K, epi, s, max_rounds, rs, ks, ws);
             if (e != hipSuccess) return e;
             return reduce_partials(ws, ks, c, ldc, r, M, N, epi, rs, s);
