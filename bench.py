@@ -419,6 +419,13 @@ class Bench:
         out = {}
 
         def run_slice(ids, lens, x):
+            if os.environ.get("SS_X_PER_LAYER"):
+                cur, T = x, sum(lens)
+                for l in range(L):
+                    nxt = buf[l & 1][:T]
+                    ctx.layer_prefill(pp, l, ss.SS_BOTH, ids, lens, [0] * len(ids), cur, nxt, stream)
+                    cur = nxt
+                return
             # the slice's ten layers chained on the device in one call
             ctx.layers_prefill(pp, ids, lens, [0] * len(ids), x, buf[0][:sum(lens)], stream)
 

@@ -374,13 +374,15 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
     const uint8_t* tbase = gbase;
     // L2 prefetch (see `prefetch` below): this wave asks for the lines of a later slice in every pf_period-th
     // slice, starting at slice 1 + pf_phase of a tile
-    int pf_row0 = 0, pf_period = 1 << 30, pf_phase = 0, pf_next = -1;
+    // (only for tiles whose 256 operand rows all exist: the touch then needs no per-lane arithmetic)
+    int pf_period = 1 << 30, pf_phase = 0, pf_next = -1;
+    bool pf_full = false;
     auto set_roff = [&](int it) {
         int m0, n0;
         tile_origin(it < nt_local ? it : nt_local - 1, m0, n0);
         const int row0 = isA ? m0 : n0;
         tbase = gbase + (size_t)row0 * (size_t)ld * 2 + (size_t)tile_range * (size_t)(K / 64 / ksplit) * 128;
-        pf_row0 = row0;
+        pf_full = row0 + 256 <= row_lim;
         if (pf_dist > 0) {
             const int sharers = cus_per_xcd / GM > 0 ? cus_per_xcd / GM : 1;      // CUs of the XCD on one group row
             pf_period = isA ? sharers : tile_gm;
@@ -413,36 +415,43 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
     // epilogue staging tile (unused inside the K loop) and are never read.  Loads of a wave return in order, so
     // the requests of the next slice queue behind these two; the mid-slice wait of the slice that issued them
     // leaves them outstanding (vmcnt 2), every other wait takes them in.
+    // The touch is two instructions with a scalar base and one per-lane offset (row `lane` of a run of 64 rows)
+    // that is formed on the spot from the lane number, inside the assembly: a value kept in a register over the
+    // whole kernel for this rare use is what the register allocator spills first, the reload is a vector memory
+    // operation, and the wait the compiler puts in front of the first use counts the loads of this loop, which it
+    // does not know of, as well (seen: a vmcnt(0) in front of every touch, 2.7 % of the GEMM time).
     const uint32_t pf_dst = lds_base + 2 * STAGE + wave * 8192;
+    const uint32_t ld_bytes = (uint32_t)ld * 2u;
     auto prefetch = [&](int ksl) {
-        const uint8_t* sb = tbase + (size_t)ksl * 128;
+        uint32_t off;
+        asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0\n\tv_mul_lo_u32 %0, %0, %1" : "=v"(off) : "s"(ld_bytes));
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const int row = row_base + h * 64 + lane;
-            int gr = pf_row0 + row;
-            gr = gr < row_lim ? gr : row_lim - 1;
-            const uint32_t off = (uint32_t)(gr - pf_row0) * (uint32_t)ld * 2u;
+            const uint8_t* sb = tbase + (size_t)ksl * 128 + (size_t)(row_base + h * 64) * (size_t)ld * 2;
             asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(sb), "s"(pf_dst) : "memory");
         }
     };
 
     // The residual rows of the tile being finished, brought into L2 the same way three slices before the epilogue
     // reads them: this wave's 128 x 128 piece is 128 rows of 256 bytes = 256 lines, one per lane and request.
-    auto prefetch_residual = [&](int it) {
-        if (EPI != EPI_RESIDUAL) return;
+    // (tiles that lie wholly inside the output; scalar base + a per-lane offset formed on the spot as above: lane l
+    // is row l / 2, half l % 2 of a run of 32 rows)
+    auto prefetch_residual = [&](int it) -> bool {
+        if (EPI != EPI_RESIDUAL) return false;
         int m0, n0;
         tile_origin(it, m0, n0);
+        if (m0 + 256 > M || n0 + 256 > N) return false;
+        const uint32_t ldc_bytes = (uint32_t)ldc * 2u;
+        uint32_t lane_res_off, half;
+        asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0\n\tv_and_b32 %1, 1, %0\n\tv_lshrrev_b32 %0, 1, %0\n\t"
+                     "v_mul_lo_u32 %0, %0, %2\n\tv_lshl_add_u32 %0, %1, 7, %0" : "=&v"(lane_res_off), "=&v"(half) : "s"(ldc_bytes));
 #pragma unroll
         for (int h = 0; h < 4; ++h) {
-            const int l = h * 64 + lane;                     // line l: row l / 2, half l % 2 of the wave's piece
-            int gr = m0 + wm * 128 + (l >> 1);
-            gr = gr < M ? gr : M - 1;
-            int gc = n0 + wn * 128 + (l & 1) * 64;
-            gc = gc < N ? gc : 0;
-            const uint32_t off = (uint32_t)(gr - m0) * (uint32_t)ldc * 2u + (uint32_t)gc * 2u;
-            const uint8_t* sb = reinterpret_cast<const uint8_t*>(R) + (size_t)m0 * (size_t)ldc * 2;
-            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(off), "s"(sb), "s"(pf_dst) : "memory");
+            const uint8_t* sb = reinterpret_cast<const uint8_t*>(R) + (size_t)(m0 + wm * 128 + h * 32) * (size_t)ldc * 2 +
+                                (size_t)(n0 + wn * 128) * 2;
+            asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(lane_res_off), "s"(sb), "s"(pf_dst) : "memory");
         }
+        return true;
     };
 
     f32x4_t acc[8][8];       // [n tile][m tile] of 16 x 16
@@ -637,13 +646,13 @@ __global__ __launch_bounds__(256) void gemm_mfma_stream_kernel(const bf16_t* __r
             bool prefetched = false;
             if (s == pf_next) {
                 pf_next += pf_period;
-                if (s + pf_dist < nsl - 1) {
+                if (s + pf_dist < nsl - 1 && pf_full) {
                     prefetch(s + pf_dist);
                     prefetched = true;
                 }
             }
-            const bool res_prefetched = EPI == EPI_RESIDUAL && pf_dist > 0 && !prefetched && s == nsl - 3 && s > 0;
-            if (res_prefetched) prefetch_residual(it);
+            bool res_prefetched = false;
+            if (EPI == EPI_RESIDUAL && pf_dist > 0 && !prefetched && s == nsl - 3 && s > 0) res_prefetched = prefetch_residual(it);
             __builtin_amdgcn_sched_barrier(0);
             mfma_step(0, st, 1, false, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
