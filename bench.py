@@ -413,19 +413,12 @@ class Bench:
         sets = [(list(range(len(lens_a))), lens_a, wl.device_normal((Ta, cfg.hidden), 5002, cfg.dtype)),
                 (list(range(1000, 1000 + len(lens_b))), lens_b, wl.device_normal((Tb, cfg.hidden), 5003, cfg.dtype))]
         tmax = max(Ta, Tb)
-        buf = [torch.empty((tmax, cfg.hidden), device="cuda", dtype=torch.bfloat16) for _ in range(2)]
+        buf = [torch.empty((tmax, cfg.hidden), device="cuda", dtype=torch.bfloat16)]
         tickets = [None, None]
         stream = self.stream
         out = {}
 
         def run_slice(ids, lens, x):
-            if os.environ.get("SS_X_PER_LAYER"):
-                cur, T = x, sum(lens)
-                for l in range(L):
-                    nxt = buf[l & 1][:T]
-                    ctx.layer_prefill(pp, l, ss.SS_BOTH, ids, lens, [0] * len(ids), cur, nxt, stream)
-                    cur = nxt
-                return
             # the slice's ten layers chained on the device in one call
             ctx.layers_prefill(pp, ids, lens, [0] * len(ids), x, buf[0][:sum(lens)], stream)
 
