@@ -356,3 +356,28 @@ def test_many_tokens_on_a_narrow_layer_short_contractions_on_the_large_output_ke
         _, ref = lm.layer_forward(cfg, vals, xv[a:b], [(i, 100, 0)], lm.KVCache(cfg), 0)
         parity(got[a:b], ref, cfg.dtype, "narrow layer, sequence %d" % i)
     ctx.destroy()
+
+
+@pytest.mark.parametrize("hidden,n_q,n_kv,ffn,T", [(8192, 16, 8, 2048, 777), (4096, 8, 8, 8192, 777), (8192, 16, 8, 2048, 1000)])
+def test_ragged_token_count_on_the_projections_cut_along_the_contraction(hidden, n_q, n_kv, ffn, T):
+    """Between a decode batch and a prefill batch (some hundreds of tokens, a count that is no multiple of any tile)
+    wide layers send their projections to the large-output GEMM with the contraction cut into ranges and fp32
+    partial sums: with hidden 8192 the QKV product (plain store) and the gate/up product (SwiGLU), with
+    hidden 4096 and an inner width of 8192 the down projection (residual).  Single-token sequences, so the
+    attention is the identity on V and the oracle can afford every row."""
+    cfg = wl.ModelCfg(n_layers=1, dtype=wl.BF16, hidden=hidden, n_q_heads=n_q, n_kv_heads=n_kv, head_dim=128, ffn=ffn)
+    vals, raws = wl.make_layer_weights(cfg, 7401)
+    lens = [1] * T
+    xv, xr = wl.make_activations((T, cfg.hidden), 7402, cfg.dtype)
+    ctx = make_context(cfg, pages=T + 8, max_seq_len=64)
+    desc = pp_desc(cfg)
+    ctx.load_layer(desc, 0, raws)
+    ids = list(range(T))
+    out = empty_like_acts(T, cfg.hidden, cfg.dtype)
+    ctx.layer_prefill(desc, 0, ss.SS_BOTH, ids, lens, [0] * T, to_device(xr, cfg.dtype), out)
+    torch.cuda.synchronize()
+    got = to_f64(out, cfg.dtype)
+    assert np.isfinite(got).all()
+    _, ref = lm.layer_forward(cfg, vals, xv, [(i, 1, 0) for i in range(T)], lm.KVCache(cfg), 0)
+    parity(got, ref, cfg.dtype, "ragged %d tokens, hidden %d" % (T, hidden))
+    ctx.destroy()
