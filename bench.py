@@ -633,6 +633,53 @@ def offline_loop_bench(torch, wl, ss, hz):
                       "value": runs["store_all"]["tokens_per_s"], "runs": runs}))
 
 
+def library_gemm_yardstick(torch, wl, config):
+    """The vendor library's GEMM on the shapes of the configuration's prefill projections (tokens = the mean of the two
+    alternating batches where there are two): the same contractions as this library's prefill GEMMs without the
+    fused epilogues.  One JSON line; fractions are of the 2.5 PFLOP/s bf16 peak."""
+    w = {2: wl.config2, 3: wl.config3, 5: wl.config5}.get(config)
+    if w is None:
+        print("bench.py: --library-gemm needs a configuration with a prefill batch (2, 3 or 5)", file=sys.stderr)
+        sys.exit(2)
+    w = w()
+    cfg = w.cfg
+    T = int(sum(w.prefill_lens))
+    if w.notes and "next_batch_lens" in w.notes:
+        T = (T + int(sum(w.notes["next_batch_lens"]))) // 2
+    d = cfg.head_dim
+    shapes = [("qkv", (cfg.n_q_heads + 2 * cfg.n_kv_heads) * d, cfg.hidden), ("o", cfg.hidden, cfg.n_q_heads * d),
+              ("gate_up", 2 * cfg.ffn, cfg.hidden), ("down", cfg.hidden, cfg.ffn)]
+    out = {"library_gemm": {"workload": w.name, "tokens": T, "peak_tflops": 2500.0, "reps": 5}}
+    for data in ("random", "zeros"):
+        rows, total_ms, total_fl = {}, 0.0, 0.0
+        for name, N, K in shapes:
+            if data == "zeros":
+                a = torch.zeros((T, K), device="cuda", dtype=torch.bfloat16)
+                wt = torch.zeros((N, K), device="cuda", dtype=torch.bfloat16)
+            else:
+                a = wl.device_normal((T, K), 9101, wl.BF16)
+                wt = wl.device_normal((N, K), 9102, wl.BF16, std=0.02)
+            c = torch.empty((T, N), device="cuda", dtype=torch.bfloat16)
+            for _ in range(2):
+                torch.matmul(a, wt.t(), out=c)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                torch.matmul(a, wt.t(), out=c)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 5
+            fl = 2.0 * T * N * K
+            rows[name] = {"N": N, "K": K, "ms": ms, "frac": fl / ms / 1e9 / 2500.0}
+            total_ms += ms
+            total_fl += fl
+            del a, wt, c
+        rows["all"] = {"ms": total_ms, "frac": total_fl / total_ms / 1e9 / 2500.0}
+        out["library_gemm"][data] = rows
+    print(json.dumps(out))
+
+
 DEFAULT_STEPS = {1: (20, 3), 2: (20, 6), 3: (10, 3), 4: (50, 5), 5: (8, 2)}
 
 
@@ -659,6 +706,9 @@ def main():
     ap.add_argument("--offline-loop", action="store_true",
                     help="instead of the layer step: the whole offline engine loop (scheduler, swaps, weight re-shards) on a "
                          "two-layer model of the configuration-2 layer shape, for three sizes of the CPU store")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="yardstick, not a benchmark of this library: the vendor library's plain GEMM (torch.matmul, no fused "
+                         "epilogue) on the four projection shapes of the configuration's prefill batch, on random data and on zeros")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives); --gpus %d is not supported" % args.gpus,
@@ -691,6 +741,9 @@ def main():
         del src, dst
     if args.offline_loop:
         offline_loop_bench(torch, wl, ss, hz)
+        return
+    if args.library_gemm:
+        library_gemm_yardstick(torch, wl, args.config)
         return
     b = Bench(args, torch, wl, ss, hz)
     runs = {1: b.config1, 2: b.config2, 3: b.config3, 4: b.config4, 5: b.config5}

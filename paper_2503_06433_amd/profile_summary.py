@@ -24,6 +24,11 @@ streams, data paths not toggling),
     rocprofv3 --kernel-trace --pmc GRBM_GUI_ACTIVE SQ_VALU_MFMA_BUSY_CYCLES -d OUT/clk_zero_cN -o t --output-format csv -- python3 bench.py (same flags) --zero-data
 
 are condensed by the same command into profiles/bench_<workload>_gemm_clock.md when those two directories exist.
+A yardstick next to it: the vendor library's GEMM on the same projection shapes under the same counters,
+
+    rocprofv3 --kernel-trace --pmc GRBM_GUI_ACTIVE SQ_VALU_MFMA_BUSY_CYCLES -d OUT/clk_library_cN -o t --output-format csv -- python3 bench.py --config N --library-gemm
+
+goes to profiles/library_gemm_<workload>_clock.md when that directory exists.
 
 The offline engine loop has a kernel trace of its own,
 
@@ -153,6 +158,37 @@ def clock_rows(directory):
     for k, v in sorted(by_kernel.items(), key=lambda kv: -sum(x[0] for x in kv[1])):
         rows.append((k, len(v), statistics.median(x[0] for x in v), statistics.median(x[1] for x in v),
                      statistics.median(x[2] for x in v)))
+    return rows
+
+
+def library_rows(directory):
+    """The run of `bench.py --library-gemm` under the clock counters: its long launches in dispatch order come in
+    groups of 7 (2 warm-up + 5 timed) per data kind (random, zeros) and shape (qkv, o, gate_up, down).
+    [(data, shape, median us, median GHz, median MFMA busy %)] over the timed launches of each group."""
+    tr_path, cc_path = find(directory, "kernel_trace.csv"), find(directory, "counter_collection.csv")
+    if not tr_path or not cc_path:
+        return []
+    us = {}
+    with open(tr_path) as f:
+        for r in csv.DictReader(f):
+            us[r["Dispatch_Id"]] = (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3
+    per = collections.defaultdict(dict)
+    with open(cc_path) as f:
+        for r in csv.DictReader(f):
+            per[r["Dispatch_Id"]][r["Counter_Name"]] = float(r["Counter_Value"])
+    long = []
+    for did in sorted(per, key=int):
+        c, t = per[did], us.get(did, 0.0)
+        if t >= 1000 and "GRBM_GUI_ACTIVE" in c:
+            cycles = c["GRBM_GUI_ACTIVE"] / 8
+            long.append((t, cycles / t / 1e3, 100 * c.get("SQ_VALU_MFMA_BUSY_CYCLES", 0.0) / 1024 / cycles))
+    if len(long) != 56:
+        return []
+    rows = []
+    for i, (data, shape) in enumerate((dk, sh) for dk in ("random", "zeros") for sh in ("qkv", "o", "gate_up", "down")):
+        g = long[7 * i + 2:7 * i + 7]
+        rows.append((data, shape, statistics.median(x[0] for x in g), statistics.median(x[1] for x in g),
+                     statistics.median(x[2] for x in g)))
     return rows
 
 
@@ -288,6 +324,19 @@ def main():
                 if k in zero:
                     z = zero[k]
                     f.write("| `%s` | %d | %.0f | %.2f | %.1f %% | %.0f | %.2f | %.1f %% | %.2f |\n" % (k, cnt, t, ghz, busy, z[2], z[3], z[4], t / z[2]))
+    lib = library_rows(d("clk_library"))
+    if lib:
+        with open(os.path.join(a.profiles, "library_gemm_%s_clock.md" % wl), "w") as f:
+            f.write("# Yardstick: the vendor library's GEMM (`torch.matmul`) on the prefill projection shapes of %s\n\n"
+                    "Not a kernel of this library: the same four contractions without the fused epilogues, timed by "
+                    "`bench.py --config %d --library-gemm` (2 warm-up + 5 timed launches per shape, on random data and on zeros) "
+                    "under the clock counters:\n\n    rocprofv3 --kernel-trace --pmc GRBM_GUI_ACTIVE SQ_VALU_MFMA_BUSY_CYCLES -d OUT/clk_library_c%d "
+                    "-o t --output-format csv -- python3 bench.py --config %d --library-gemm\n\nMedians over the timed launches; clock = "
+                    "GRBM_GUI_ACTIVE / 8 / duration; MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / 1024 / (GRBM_GUI_ACTIVE / 8).  Compare with "
+                    "`bench_%s_gemm_clock.md` (this library's kernels on the same box class).\n\n"
+                    "| data | shape | median us | clock GHz | MFMA busy |\n|---|---|---|---|---|\n" % (wl, n, n, n, wl))
+            for data, shape, t, ghz, busy in lib:
+                f.write("| %s | %s | %.0f | %.2f | %.1f %% |\n" % (data, shape, t, ghz, busy))
     fetch, write = read_counters(d("fetch")), read_counters(d("write"))
     if fetch:
         lines, total, (cf, cw, sf, sw) = traffic(fetch, write)
