@@ -932,9 +932,12 @@ hipError_t gemm_mfma_bf16(const void* A, int lda, const void* Wt, void* C, int l
     }
     const long long mid = (long long)((M + 127) / 128) * ((N + 127) / 128);
     // split K until every CU has a block, but only while the fp32 partials (8*S*M*N bytes written and
-    // read back) stay below the weight bytes (2*N*K) they help to stream: S <= K / (4 M)
+    // read back) stay below twice the weight bytes (2*N*K) they help to stream: S <= K / (2 M).  (With the bound at
+    // the weight bytes themselves, S <= K / (4 M), the QKV projection of the k = 8 shard of the 70B layer with 1024
+    // tokens stopped at two ranges: 57 us, with four 47 us; the same for the QKV and down projections of the 13B
+    // k = 4 shard with 512 tokens, 44 -> 41 and 46 -> 43 us; the 7B shapes with 256 tokens choose as before.)
     int split = 1;
-    while (split < 8 && mid * split < 256 && (K / 64) % (split * 2) == 0 && (long long)(split * 2) * 4 * M <= K &&
+    while (split < 8 && mid * split < 256 && (K / 64) % (split * 2) == 0 && (long long)(split * 2) * 2 * M <= K &&
            (size_t)(split * 2) * M * N * sizeof(float) <= ws_bytes && ws)
         split *= 2;
     return launch_cfg<128, 128, 2, 2>(a, lda, w, c, ldc, r, M, N, K, epi, s, split, ws, rs);
