@@ -164,3 +164,38 @@ def test_bad_shard_arguments():
         ws.head_and_ffn_ranges(cfg, 3, 0)
     with pytest.raises(ValueError):
         ws.head_and_ffn_ranges(cfg, 2, 2)
+
+
+def _golden(name):
+    import os
+    out = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#") and "=" in line:
+                k, v = (x.strip() for x in line.split("=", 1))
+                out[k] = v
+    return out
+
+
+def test_weight_count_of_the_70b_model_matches_the_size_the_paper_prints():
+    """Section 3.3 prints the one absolute model size of the paper: the 70B model's float16 weights take 140 GiB and
+    need at least four 40 GiB GPUs.  The oracle's element count of a layer (the paper's W, which every cost term of
+    Appendix A and every re-shard volume here is built on) times the layers, plus the two vocabulary matrices, must
+    give that size; a dropped or doubled matrix in the count moves it by 8 % or more."""
+    g = _golden("section3_3_model_weight_bytes.txt")
+    cfg = wl.ModelCfg(hidden=int(g["hidden"]), n_q_heads=int(g["n_q_heads"]), n_kv_heads=int(g["n_kv_heads"]),
+                      head_dim=int(g["head_dim"]), ffn=int(g["ffn"]), n_layers=int(g["n_layers"]), vocab=int(g["vocab"]),
+                      dtype=wl.F16)
+    per_layer = ws.shard_matrix_elems(cfg, 1) + 2 * cfg.hidden
+    # the count agrees with the shapes the layer oracle multiplies with
+    assert per_layer == sum(int(np.prod(s)) for s in wl.layer_weight_shapes(cfg).values())
+    total = (per_layer * cfg.n_layers + 2 * cfg.vocab * cfg.hidden + cfg.hidden) * int(g["bytes_per_element"])
+    printed, tol = float(g["printed_weight_bytes"]), float(g["relative_tolerance"])
+    assert abs(total - printed) <= tol * printed, (total, printed)
+    # "at least four GPUs (160 GiB) are needed to fit the model weights"
+    gib40 = 40 * 2 ** 30
+    assert -(-total // gib40) == int(g["min_gpus_of_40GiB"])
+    # and a tensor-parallel shard holds W / k of the matrices (Appendix A.3)
+    for k in (2, 4, 8):
+        assert ws.shard_matrix_elems(cfg, k) * k == ws.shard_matrix_elems(cfg, 1)
